@@ -1,0 +1,205 @@
+/*
+ * ghostserve_ec.h -- C ABI of the MI355X (gfx950) erasure-code hot path of
+ * GhostServe's shadow checkpointing: k data shards of the KV cache produce m
+ * parity shards (Fig. 1(c); Section 4.1), parity is shipped to pinned host
+ * memory (Alg. 1), and up to m lost shards are rebuilt from the survivors
+ * (Alg. 2).
+ *
+ * The code is a systematic MDS code over GF(2^8) (polynomial 0x11D): the KV
+ * cache is taken as raw bytes -- the reversible integer view of FP16 values of
+ * Section 4.1 -- and every byte offset is coded independently.  The paper
+ * names the code family (XOR, Reed-Solomon; Section 2) but prints no field or
+ * matrix, so the library fixes them: parity block P (m x k) is the Cauchy
+ * matrix 1/(x_i + y_j), x_i = k+i, y_j = j, scaled so that row 0 and column 0
+ * are all ones.  With m = 1 that is exactly XOR parity.
+ *
+ * General conventions
+ *   - "DEVICE" pointers are HIP device addresses on the current device,
+ *     "HOST" pointers are ordinary host addresses, "PINNED" host pointers come
+ *     from hipHostMalloc (or an equivalent page-locked allocation).
+ *   - Pointer arrays (data[], parity[], shards[]) are HOST arrays holding
+ *     DEVICE pointers; they are read during the call and may be freed on return.
+ *   - The caller owns every buffer.  A gs_code owns no device memory; a
+ *     gs_pipe owns its staging buffers, events and copy stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise unless stated.
+ *   - Every entry point returns GS_OK (0) or a negative gs_status.  On any
+ *     error nothing has been enqueued and no buffer is written.
+ *   - Shard base pointers must be 16-byte aligned; shard_bytes may be any
+ *     value (the partial last chunk is masked by bounds, Section 4.2).  Bytes
+ *     at offsets >= shard_bytes are neither read nor written.
+ *   - Input and output buffers of one call must not overlap.
+ *   - A gs_code is immutable after creation and may be shared between threads.
+ */
+#ifndef GHOSTSERVE_EC_H
+#define GHOSTSERVE_EC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gs_code gs_code;
+typedef struct gs_pipe gs_pipe;
+typedef struct gs_step_graph gs_step_graph;
+
+enum gs_status {
+    GS_OK = 0,
+    GS_EINVAL = -1,    /* bad argument (range, alignment, NULL, duplicate index) */
+    GS_ENOMEM = -2,    /* host or device allocation failed                       */
+    GS_ETOOMANY = -3,  /* more erasures than parity shards                       */
+    GS_ESINGULAR = -4, /* survivor matrix not invertible (cannot happen for a code made here) */
+    GS_EHIP = -5       /* a HIP runtime call failed; see gs_last_hip_error()      */
+};
+
+enum gs_kind {
+    GS_CAUCHY = 0,      /* closed form described above                                      */
+    GS_VANDERMONDE = 1  /* systematic form of the Vandermonde matrix over points 0..k+m-1,
+                           with the same normalisation; yields the identical matrix        */
+};
+
+/* Largest code a single kernel launch covers; wider codes run as several
+ * launches that accumulate (transparent to the caller). */
+#define GS_LAUNCH_MAX_K 16
+#define GS_LAUNCH_MAX_M 4
+
+/* ---- code handle (host only; needs no GPU) -------------------------------
+ * Section 2 (Reed-Solomon: distinct coefficients per parity symbol over a
+ * Galois field) and Section 4.1 (N data : K parity, user-selectable).
+ * Requires 1 <= k, 1 <= m, k + m <= 256, kind one of gs_kind; else GS_EINVAL. */
+int gs_make_code(int k, int m, int kind, gs_code **out);
+void gs_free_code(gs_code *code);
+int gs_code_params(const gs_code *code, int *k, int *m);
+/* copies the parity block, m*k bytes row-major, to HOST memory */
+int gs_code_matrix(const gs_code *code, uint8_t *P_out);
+
+/* Rebuild matrix for an erasure pattern (host only).  Shard ids 0..k-1 are
+ * data, k..k+m-1 parity.  The k lowest-numbered surviving shards are used;
+ * their ids go to survivors_out[k], and R_out (n_erased x k, row-major) maps
+ * them to the erased shards in the order listed:
+ *     erased[x] = XOR_j  R[x][j] (x) survivor_j .
+ * A lost data shard r is row r of inverse(A), A the survivors' rows of
+ * [I;P]; a lost parity shard k+i is P[i]*inverse(A) (Section 4.1: recovery
+ * from up to K simultaneous failures).  Errors: GS_EINVAL for an index out of
+ * range or listed twice, GS_ETOOMANY for n_erased > m. */
+int gs_decode_matrix(const gs_code *code, const int *erased, int n_erased,
+                     uint8_t *R_out, int *survivors_out);
+
+/* ---- encode, contiguous shards --------------------------------------------
+ * Alg. 1, "P_i = EC.encode(KV_i)":  for every byte offset t < shard_bytes and
+ * parity row i < m,   parity[i][t] = XOR_{j<k} P[i][j] (x) data[j][t].
+ *   data    HOST array of k DEVICE pointers, each shard_bytes long, read-only
+ *   parity  HOST array of m DEVICE pointers, each shard_bytes long, written
+ * shard_bytes == 0 is a no-op.  One fused pass: no conversion or staging
+ * kernels (Section 5, kernel fusion). */
+int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
+              size_t shard_bytes, void *stream);
+
+/* ---- encode, shards gathered from a paged KV pool -------------------------
+ * Same sum, but shard j is not contiguous: its logical byte stream is, for
+ * plane p = 0..n_planes-1 and slot t = 0..pages_per_shard-1, the page_bytes
+ * bytes at  plane_base[p] + table[j*pages_per_shard + t] * page_bytes,
+ * and that page's parity lands at offset (p*pages_per_shard + t)*page_bytes
+ * of each parity buffer.  (Paged KV cache as in PagedAttention, Section 2;
+ * a plane is one layer's K or V pool, a page one block or one token slot.)
+ *   plane_base       DEVICE array of n_planes DEVICE pointers (16-byte aligned)
+ *   page_bytes       multiple of 16, > 0
+ *   pages_per_plane  number of pages in every plane; a table entry outside
+ *                    [0, pages_per_plane) contributes zero bytes (never read)
+ *   table            DEVICE int32 [k][pages_per_shard]
+ *   parity           HOST array of m DEVICE pointers, each
+ *                    n_planes*pages_per_shard*page_bytes long
+ * plane_base and table are read by the kernel when it runs, so a captured
+ * launch sees their current contents on every replay.
+ * Limits: n_planes <= 65535, pages_per_shard*page_bytes < 64 GiB. */
+int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_planes,
+                    size_t page_bytes, int64_t pages_per_plane,
+                    const int32_t *table, int pages_per_shard,
+                    void *const *parity, void *stream);
+
+/* ---- reconstruct -----------------------------------------------------------
+ * Alg. 2, "KV = EC.reconstruct(KV, P)".
+ *   shards   HOST array of k+m DEVICE pointers (0..k-1 data, k..k+m-1 parity),
+ *            each shard_bytes long.  Entries listed in `erased` are outputs;
+ *            the k lowest-numbered others are read; the rest are ignored and
+ *            may be NULL.  Survivors are never written.
+ *   erased   HOST array of n_erased distinct ids in [0, k+m)
+ * n_erased == 0 is a no-op; n_erased > m gives GS_ETOOMANY. */
+int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
+                   size_t shard_bytes, void *stream);
+
+/* ---- checkpoint / restore pipelines (encode + parity D2H; H2D + reconstruct)
+ * Alg. 1 ships each chunk's parity to host DRAM asynchronously while the next
+ * chunk is produced; Alg. 2 brings parity back and reconstructs chunk by
+ * chunk on streams.  A gs_pipe holds what that needs: `depth` sets of m
+ * device staging buffers of chunk_bytes each, events, and a copy stream of
+ * default priority.  chunk_bytes must be a positive multiple of 16, depth >= 2.
+ * One pipe serves one checkpoint or restore at a time. */
+int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe **out);
+void gs_pipe_destroy(gs_pipe *pipe);
+
+/* Encode `data` chunk by chunk on compute_stream into staging, and copy each
+ * chunk's parity to host_parity[i] + offset on the pipe's copy stream, so the
+ * copy of chunk c overlaps the encode of chunk c+1.
+ *   data         HOST array of k DEVICE pointers, shard_bytes each
+ *   host_parity  HOST array of m PINNED host pointers, shard_bytes each
+ * Returns after enqueuing; the parity bytes are valid once gs_pipe_sync()
+ * returns (or after the event gs_pipe_done_event() on another stream). */
+int gs_checkpoint(gs_pipe *pipe, const void *const *data, size_t shard_bytes,
+                  void *const *host_parity, void *compute_stream);
+
+/* Rebuild the erased shards chunk by chunk.  Parity shards that the decode
+ * needs are read from host_parity (PINNED) through the staging buffers (H2D
+ * on the copy stream, overlapped with the reconstruct kernel of the previous
+ * chunk); data survivors are read in place.
+ *   shards       HOST array of k+m pointers; entries 0..k-1 are DEVICE data
+ *                shards (outputs if erased); entries k..k+m-1 are ignored
+ *                unless erased, in which case they are DEVICE outputs
+ *   host_parity  HOST array of m PINNED pointers (entries for erased parity
+ *                shards are ignored) */
+int gs_restore(gs_pipe *pipe, void *const *shards, void *const *host_parity,
+               const int *erased, int n_erased, size_t shard_bytes, void *compute_stream);
+
+/* block the host until everything the pipe enqueued has finished */
+int gs_pipe_sync(gs_pipe *pipe);
+/* hipEvent_t (as void*) recorded after the last operation enqueued so far */
+void *gs_pipe_done_event(gs_pipe *pipe);
+
+/* ---- captured per-step checkpoint (Section 5: graphs for fixed-size chunks)
+ * Captures gs_encode_paged (+ optional D2H of the m parity buffers into
+ * host_parity, PINNED, may be NULL for no copy) once, and replays it with one
+ * graph launch per decode step.  The block table and plane pointers are read
+ * from device memory at replay time, so the serving engine advances a step by
+ * updating them in place.  No memset nodes are recorded. */
+int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int n_planes,
+                         size_t page_bytes, int64_t pages_per_plane,
+                         const int32_t *table, int pages_per_shard,
+                         void *const *parity, void *const *host_parity,
+                         gs_step_graph **out);
+int gs_step_graph_launch(gs_step_graph *g, void *stream);
+void gs_step_graph_destroy(gs_step_graph *g);
+
+/* ---- diagnostics -----------------------------------------------------------*/
+const char *gs_strerror(int status);
+/* last hipError_t seen by the calling thread in this library (0 = none) */
+int gs_last_hip_error(void);
+/* The five lookup words the kernels use for multiplication by the constant c
+ * (0..255): a byte x is cut into bit fields x[2:0], x[5:3], x[7:6] and
+ *   c (x) x = T0[x & 7] ^ T1[(x >> 3) & 7] ^ T2[x >> 6],
+ * words_out = {T0[0..3], T0[4..7], T1[0..3], T1[4..7], T2[0..3]} with table
+ * entry i in byte (i & 3) of its word.  Host only; exposed so that the table
+ * construction can be checked without a GPU. */
+int gs_coef_words(int c, uint32_t *words_out);
+/* Launch-shape knobs for benchmarking sweeps; values <= 0 restore the default.
+ *   unroll        16-byte vectors per lane per shard per tile (1, 2 or 4)
+ *   tiles_per_wg  consecutive tiles one workgroup processes
+ *   nontemporal   1 = streaming loads/stores, 0 = default cache policy
+ * Results are identical for every setting. */
+int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GHOSTSERVE_EC_H */

@@ -1,0 +1,264 @@
+"""Thin ctypes binding of the C-ABI HIP library (include/ghostserve_ec.h).
+
+Same names as the C entry points; this layer only marshals arguments (device
+pointers out of torch tensors, host pointer arrays, stream handles).  Every
+step of the path runs in the library's HIP kernels.  There is no CPU
+fallback: if the built library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libghostserve_ec.so")
+
+GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP = 0, -1, -2, -3, -4, -5
+GS_CAUCHY, GS_VANDERMONDE = 0, 1
+
+EXPORTS = [
+    "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix",
+    "gs_encode", "gs_encode_paged", "gs_reconstruct",
+    "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
+    "gs_pipe_done_event",
+    "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
+    "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape",
+]
+
+_vp = ctypes.c_void_p
+_vpp = ctypes.POINTER(ctypes.c_void_p)
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_intp = ctypes.POINTER(ctypes.c_int)
+
+_lib = None
+
+
+class GsError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().gs_strerror(status).decode()
+        if status == GS_EHIP:
+            msg += " (hipError %d)" % lib().gs_last_hip_error()
+        super().__init__("%s: %s [%d]" % (where, msg, status))
+
+
+def lib():
+    """Load the HIP library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "HIP library %s is missing: run `python -m paper_2605_00831_amd.build` "
+            "(there is no CPU fallback)" % LIB_PATH)
+    # torch ships its own HIP runtime; import it first so that the library
+    # binds to the runtime that owns torch's device memory and streams
+    import torch  # noqa: F401
+    L = ctypes.CDLL(LIB_PATH)
+    L.gs_make_code.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(_vp)]
+    L.gs_free_code.argtypes = [_vp]
+    L.gs_free_code.restype = None
+    L.gs_code_params.argtypes = [_vp, _intp, _intp]
+    L.gs_code_matrix.argtypes = [_vp, _u8p]
+    L.gs_decode_matrix.argtypes = [_vp, _intp, ctypes.c_int, _u8p, _intp]
+    L.gs_encode.argtypes = [_vp, _vpp, _vpp, ctypes.c_size_t, _vp]
+    L.gs_encode_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
+                                  ctypes.c_int, _vpp, _vp]
+    L.gs_reconstruct.argtypes = [_vp, _vpp, _intp, ctypes.c_int, ctypes.c_size_t, _vp]
+    L.gs_pipe_create.argtypes = [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(_vp)]
+    L.gs_pipe_destroy.argtypes = [_vp]
+    L.gs_pipe_destroy.restype = None
+    L.gs_checkpoint.argtypes = [_vp, _vpp, ctypes.c_size_t, _vpp, _vp]
+    L.gs_restore.argtypes = [_vp, _vpp, _vpp, _intp, ctypes.c_int, ctypes.c_size_t, _vp]
+    L.gs_pipe_sync.argtypes = [_vp]
+    L.gs_pipe_done_event.argtypes = [_vp]
+    L.gs_pipe_done_event.restype = _vp
+    L.gs_step_graph_create.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
+                                       ctypes.c_int, _vpp, _vpp, ctypes.POINTER(_vp)]
+    L.gs_step_graph_launch.argtypes = [_vp, _vp]
+    L.gs_step_graph_destroy.argtypes = [_vp]
+    L.gs_step_graph_destroy.restype = None
+    L.gs_strerror.argtypes = [ctypes.c_int]
+    L.gs_strerror.restype = ctypes.c_char_p
+    L.gs_last_hip_error.argtypes = []
+    L.gs_coef_words.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
+    L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    _lib = L
+    return L
+
+
+def _check(status, where):
+    if status != GS_OK:
+        raise GsError(status, where)
+
+
+def _ptr(x):
+    """Device or host address of a tensor / array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError("cannot take the address of %r" % type(x))
+
+
+def _ptr_array(seq):
+    return (ctypes.c_void_p * len(seq))(*[_ptr(x) for x in seq])
+
+
+def _int_array(seq):
+    seq = list(seq)
+    return (ctypes.c_int * max(len(seq), 1))(*seq), len(seq)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Code:
+    """Owner of a gs_code handle."""
+
+    def __init__(self, handle, k, m):
+        self.handle, self.k, self.m = handle, k, m
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gs_free_code(self.handle)
+            self.handle = None
+
+
+class Pipe:
+    def __init__(self, handle, code):
+        self.handle, self.code = handle, code
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gs_pipe_destroy(self.handle)
+            self.handle = None
+
+
+class StepGraph:
+    def __init__(self, handle, keep):
+        self.handle, self._keep = handle, keep
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gs_step_graph_destroy(self.handle)
+            self.handle = None
+
+
+def gs_make_code(k, m, kind=GS_CAUCHY):
+    h = _vp()
+    _check(lib().gs_make_code(k, m, kind, ctypes.byref(h)), "gs_make_code")
+    return Code(h, k, m)
+
+
+def gs_code_matrix(code):
+    P = np.zeros((code.m, code.k), np.uint8)
+    _check(lib().gs_code_matrix(code.handle, P.ctypes.data_as(_u8p)), "gs_code_matrix")
+    return P
+
+
+def gs_decode_matrix(code, erased):
+    er, n = _int_array(erased)
+    R = np.zeros((n, code.k), np.uint8)
+    surv = (ctypes.c_int * code.k)()
+    _check(lib().gs_decode_matrix(code.handle, er, n, R.ctypes.data_as(_u8p), surv), "gs_decode_matrix")
+    return R, list(surv)
+
+
+def gs_encode(code, data, parity, shard_bytes, stream=None):
+    if len(data) != code.k or len(parity) != code.m:
+        raise ValueError("need k data and m parity pointers")
+    _check(lib().gs_encode(code.handle, _ptr_array(data), _ptr_array(parity), shard_bytes,
+                           _stream(stream)), "gs_encode")
+
+
+def gs_encode_paged(code, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                    parity, stream=None):
+    if len(parity) != code.m:
+        raise ValueError("need m parity pointers")
+    _check(lib().gs_encode_paged(code.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane,
+                                 _ptr(table), pages_per_shard, _ptr_array(parity), _stream(stream)),
+           "gs_encode_paged")
+
+
+def gs_reconstruct(code, shards, erased, shard_bytes, stream=None):
+    if len(shards) != code.k + code.m:
+        raise ValueError("need k+m shard pointers")
+    er, n = _int_array(erased)
+    _check(lib().gs_reconstruct(code.handle, _ptr_array(shards), er, n, shard_bytes, _stream(stream)),
+           "gs_reconstruct")
+
+
+def gs_pipe_create(code, chunk_bytes, depth=2):
+    h = _vp()
+    _check(lib().gs_pipe_create(code.handle, chunk_bytes, depth, ctypes.byref(h)), "gs_pipe_create")
+    return Pipe(h, code)
+
+
+def gs_checkpoint(pipe, data, shard_bytes, host_parity, stream=None):
+    if len(data) != pipe.code.k or len(host_parity) != pipe.code.m:
+        raise ValueError("need k data and m host parity pointers")
+    _check(lib().gs_checkpoint(pipe.handle, _ptr_array(data), shard_bytes, _ptr_array(host_parity),
+                               _stream(stream)), "gs_checkpoint")
+
+
+def gs_restore(pipe, shards, host_parity, erased, shard_bytes, stream=None):
+    if len(shards) != pipe.code.k + pipe.code.m or len(host_parity) != pipe.code.m:
+        raise ValueError("need k+m shard pointers and m host parity pointers")
+    er, n = _int_array(erased)
+    _check(lib().gs_restore(pipe.handle, _ptr_array(shards), _ptr_array(host_parity), er, n, shard_bytes,
+                            _stream(stream)), "gs_restore")
+
+
+def gs_pipe_sync(pipe):
+    _check(lib().gs_pipe_sync(pipe.handle), "gs_pipe_sync")
+
+
+def gs_pipe_done_event(pipe):
+    return lib().gs_pipe_done_event(pipe.handle)
+
+
+def gs_pipe_destroy(pipe):
+    if pipe.handle:
+        lib().gs_pipe_destroy(pipe.handle)
+        pipe.handle = None
+
+
+def gs_step_graph_create(code, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                         parity, host_parity=None):
+    h = _vp()
+    hp = _ptr_array(host_parity) if host_parity is not None else None
+    _check(lib().gs_step_graph_create(code.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane,
+                                      _ptr(table), pages_per_shard, _ptr_array(parity), hp,
+                                      ctypes.byref(h)), "gs_step_graph_create")
+    return StepGraph(h, (code, plane_base, table, parity, host_parity))
+
+
+def gs_step_graph_launch(graph, stream=None):
+    _check(lib().gs_step_graph_launch(graph.handle, _stream(stream)), "gs_step_graph_launch")
+
+
+def gs_step_graph_destroy(graph):
+    if graph.handle:
+        lib().gs_step_graph_destroy(graph.handle)
+        graph.handle = None
+
+
+def gs_coef_words(c):
+    w = (ctypes.c_uint32 * 5)()
+    _check(lib().gs_coef_words(c, w), "gs_coef_words")
+    return list(w)
+
+
+def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1):
+    _check(lib().gs_set_launch_shape(unroll, tiles_per_wg, nontemporal), "gs_set_launch_shape")

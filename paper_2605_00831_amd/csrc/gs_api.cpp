@@ -1,0 +1,252 @@
+// C ABI of the erasure-code library: argument checking, code construction,
+// decode matrices, and the splitting of wide codes into kernel launches.
+#include "../../include/ghostserve_ec.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "gs_gf.h"
+#include "gs_internal.h"
+#include "gs_launch.h"
+
+namespace gs {
+
+thread_local int g_last_hip_error = 0;
+
+// defaults chosen by measurement on MI355X; see gs_set_launch_shape()
+static LaunchShape g_default_shape = {2, 1, 1};
+static LaunchShape g_shape = g_default_shape;
+
+LaunchShape current_shape() { return g_shape; }
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return GS_OK;
+    g_last_hip_error = static_cast<int>(e);
+    return e == hipErrorOutOfMemory ? GS_ENOMEM : GS_EHIP;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// out[r] = XOR_j C[r][j] (x) in[j] for an arbitrary rows x cols matrix: row
+// groups of up to 4, column groups of up to 16, later column groups accumulate.
+int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, void *const *out,
+                 size_t bytes, hipStream_t stream)
+{
+    const LaunchShape shape = current_shape();
+    for (int r0 = 0; r0 < rows; r0 += kLaunchMaxM) {
+        const int nr = std::min(kLaunchMaxM, rows - r0);
+        for (int c0 = 0; c0 < cols; c0 += kLaunchMaxK) {
+            const int nc = std::min(kLaunchMaxK, cols - c0);
+            const hipError_t e = launch_apply(nr, nc, C + static_cast<size_t>(r0) * cols + c0, cols,
+                                              in + c0, out + r0, bytes, c0 != 0, shape, stream);
+            if (e != hipSuccess) return hip_status(e);
+        }
+    }
+    return GS_OK;
+}
+
+int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost)
+{
+    const int n = code->k + code->m;
+    lost.assign(n, 0);
+    if (n_erased < 0 || (n_erased > 0 && erased == nullptr)) return GS_EINVAL;
+    for (int x = 0; x < n_erased; ++x) {
+        if (erased[x] < 0 || erased[x] >= n || lost[erased[x]]) return GS_EINVAL;
+        lost[erased[x]] = 1;
+    }
+    return n_erased > code->m ? GS_ETOOMANY : GS_OK;
+}
+
+int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &R,
+                  std::vector<int> &survivors)
+{
+    const int k = code->k;
+    std::vector<uint8_t> lost;
+    const int rc = check_erasures(code, erased, n_erased, lost);
+    if (rc != GS_OK) return rc;
+    survivors.clear();
+    for (int r = 0; r < k + code->m && static_cast<int>(survivors.size()) < k; ++r)
+        if (!lost[r]) survivors.push_back(r);
+    // A = the survivors' rows of [I ; P]
+    Matrix A(static_cast<size_t>(k) * k, 0);
+    for (int r = 0; r < k; ++r) {
+        const int s = survivors[r];
+        if (s < k) A[r * k + s] = 1;
+        else std::memcpy(&A[r * k], &code->P[static_cast<size_t>(s - k) * k], k);
+    }
+    if (!invert_in_place(k, A)) return GS_ESINGULAR;
+    R.assign(static_cast<size_t>(n_erased) * k, 0);
+    for (int x = 0; x < n_erased; ++x) {
+        const int r = erased[x];
+        if (r < k) {
+            std::memcpy(&R[static_cast<size_t>(x) * k], &A[static_cast<size_t>(r) * k], k);
+        } else {
+            const uint8_t *prow = &code->P[static_cast<size_t>(r - k) * k];
+            for (int c = 0; c < k; ++c) {
+                uint8_t s = 0;
+                for (int t = 0; t < k; ++t) s ^= gf_mul(prow[t], A[t * k + c]);
+                R[static_cast<size_t>(x) * k + c] = s;
+            }
+        }
+    }
+    return GS_OK;
+}
+
+}  // namespace gs
+
+using namespace gs;
+
+extern "C" {
+
+int gs_make_code(int k, int m, int kind, gs_code **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (k < 1 || m < 1 || k + m > 256) return GS_EINVAL;
+    if (kind != GS_CAUCHY && kind != GS_VANDERMONDE) return GS_EINVAL;
+    gs_code *c = new (std::nothrow) gs_code;
+    if (c == nullptr) return GS_ENOMEM;
+    c->k = k;
+    c->m = m;
+    c->kind = kind;
+    c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
+    *out = c;
+    return GS_OK;
+}
+
+void gs_free_code(gs_code *code) { delete code; }
+
+int gs_code_params(const gs_code *code, int *k, int *m)
+{
+    if (code == nullptr) return GS_EINVAL;
+    if (k) *k = code->k;
+    if (m) *m = code->m;
+    return GS_OK;
+}
+
+int gs_code_matrix(const gs_code *code, uint8_t *P_out)
+{
+    if (code == nullptr || P_out == nullptr) return GS_EINVAL;
+    std::memcpy(P_out, code->P.data(), code->P.size());
+    return GS_OK;
+}
+
+int gs_decode_matrix(const gs_code *code, const int *erased, int n_erased, uint8_t *R_out,
+                     int *survivors_out)
+{
+    if (code == nullptr) return GS_EINVAL;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc = decode_matrix(code, erased, n_erased, R, surv);
+    if (rc != GS_OK) return rc;
+    if (R_out && !R.empty()) std::memcpy(R_out, R.data(), R.size());
+    if (survivors_out) std::copy(surv.begin(), surv.end(), survivors_out);
+    return GS_OK;
+}
+
+int gs_encode(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes,
+              void *stream)
+{
+    if (code == nullptr || data == nullptr || parity == nullptr) return GS_EINVAL;
+    if (shard_bytes == 0) return GS_OK;
+    for (int j = 0; j < code->k; ++j)
+        if (data[j] == nullptr || !aligned16(data[j])) return GS_EINVAL;
+    for (int i = 0; i < code->m; ++i)
+        if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
+    return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,
+                        static_cast<hipStream_t>(stream));
+}
+
+int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_planes, size_t page_bytes,
+                    int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                    void *const *parity, void *stream)
+{
+    if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
+    if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
+    if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
+    if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
+    if (n_planes == 0 || pages_per_shard == 0) return GS_OK;
+    if (pages_per_plane == 0) return GS_EINVAL;
+    for (int i = 0; i < code->m; ++i)
+        if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
+    const LaunchShape shape = current_shape();
+    const int k = code->k, m = code->m;
+    for (int r0 = 0; r0 < m; r0 += kLaunchMaxM) {
+        const int nr = std::min(kLaunchMaxM, m - r0);
+        for (int c0 = 0; c0 < k; c0 += kLaunchMaxK) {
+            const int nc = std::min(kLaunchMaxK, k - c0);
+            const hipError_t e = launch_apply_paged(
+                nr, nc, code->P.data() + static_cast<size_t>(r0) * k + c0, k, plane_base, n_planes,
+                page_bytes, pages_per_plane, table + static_cast<size_t>(c0) * pages_per_shard,
+                pages_per_shard, parity + r0, c0 != 0, shape, static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_status(e);
+        }
+    }
+    return GS_OK;
+}
+
+int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
+                   size_t shard_bytes, void *stream)
+{
+    if (code == nullptr || shards == nullptr) return GS_EINVAL;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc = decode_matrix(code, erased, n_erased, R, surv);
+    if (rc != GS_OK) return rc;
+    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
+    std::vector<const void *> in(code->k);
+    std::vector<void *> out(n_erased);
+    for (int j = 0; j < code->k; ++j) {
+        in[j] = shards[surv[j]];
+        if (in[j] == nullptr || !aligned16(in[j])) return GS_EINVAL;
+    }
+    for (int x = 0; x < n_erased; ++x) {
+        out[x] = shards[erased[x]];
+        if (out[x] == nullptr || !aligned16(out[x])) return GS_EINVAL;
+    }
+    return apply_matrix(n_erased, code->k, R.data(), in.data(), out.data(), shard_bytes,
+                        static_cast<hipStream_t>(stream));
+}
+
+const char *gs_strerror(int status)
+{
+    switch (status) {
+        case GS_OK: return "ok";
+        case GS_EINVAL: return "invalid argument";
+        case GS_ENOMEM: return "out of memory";
+        case GS_ETOOMANY: return "more erasures than parity shards";
+        case GS_ESINGULAR: return "survivor matrix is singular";
+        case GS_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int gs_last_hip_error(void) { return g_last_hip_error; }
+
+int gs_coef_words(int c, uint32_t *words_out)
+{
+    if (c < 0 || c > 255 || words_out == nullptr) return GS_EINVAL;
+    const CoefWords w = split_tables(static_cast<uint8_t>(c));
+    for (int i = 0; i < 5; ++i) words_out[i] = w.w[i];
+    return GS_OK;
+}
+
+int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal)
+{
+    LaunchShape s = g_default_shape;
+    if (unroll > 0) {
+        if (unroll != 1 && unroll != 2 && unroll != 4) return GS_EINVAL;
+        s.unroll = unroll;
+    }
+    if (tiles_per_wg > 0) s.tiles_per_wg = tiles_per_wg;
+    if (nontemporal >= 0) s.nontemporal = nontemporal ? 1 : 0;
+    g_shape = s;
+    return GS_OK;
+}
+
+}  // extern "C"

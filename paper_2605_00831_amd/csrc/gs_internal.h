@@ -1,0 +1,27 @@
+// Definitions shared by the translation units of the library (not public).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <cstdint>
+#include <vector>
+
+#include "gs_gf.h"
+#include "gs_launch.h"
+
+struct gs_code {
+    int k = 0, m = 0, kind = 0;
+    gs::Matrix P;  // m x k parity block, row-major
+};
+
+namespace gs {
+
+extern thread_local int g_last_hip_error;
+int hip_status(hipError_t e);
+LaunchShape current_shape();
+
+int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, void *const *out,
+                 size_t bytes, hipStream_t stream);
+int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost);
+int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &R,
+                  std::vector<int> &survivors);
+
+}  // namespace gs

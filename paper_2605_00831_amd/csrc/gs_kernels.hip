@@ -1,0 +1,446 @@
+// HIP kernels for gfx950: apply a small GF(2^8) matrix to k byte streams.
+//
+//   out[r][t] = XOR_j  C[r][j] (x) in[j][t]          r < rows <= 4, j < k <= 16
+//
+// Encode uses C = the code's parity block (Alg. 1, EC.encode); reconstruct
+// uses C = the rebuild matrix of the erasure pattern (Alg. 2, EC.reconstruct).
+// The KV cache is consumed as raw bytes (Section 4.1: reversible integer view
+// of FP16), so there is no conversion pass before or after.
+//
+// Shape of the computation on CDNA4:
+//   * the path is HBM-bound, so every lane moves 16-byte vectors with
+//     consecutive lanes on consecutive addresses (1 KiB per wavefront per
+//     load); a tile is 256 lanes x U vectors per stream;
+//   * several streams' loads are issued before any arithmetic so that each
+//     lane keeps 4*U 16-byte loads in flight;
+//   * multiplication by a constant is linear over GF(2), so it is evaluated
+//     as three byte-table lookups on the bit fields [2:0], [5:3], [7:6] of
+//     each byte, four bytes at a time with v_perm_b32 (an 8-byte table fits
+//     the instruction's two source registers); the tables arrive as kernel
+//     arguments and are read with scalar loads;
+//   * a matrix row of all ones (row 0 of the parity block; the one-parity
+//     code) is a plain XOR and skips the lookups.
+#include <hip/hip_runtime.h>
+#include "gs_gf.h"
+#include "gs_launch.h"
+
+namespace gs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct ApplyArgs {
+    const uint8_t *in[kLaunchMaxK];
+    uint8_t *out[kLaunchMaxM];
+    uint32_t tab[kLaunchMaxM][kLaunchMaxK][8];  // 5 words used per coefficient
+    uint64_t nvec;        // whole 16-byte vectors per stream
+    uint32_t tail;        // trailing bytes after the last whole vector (0..15)
+    int32_t k;            // streams in this launch
+    int32_t accumulate;   // XOR into the existing outputs
+    uint32_t tiles_per_wg;
+};
+
+struct PagedArgs {
+    const uint8_t *const *plane_base;  // device array [n_planes]
+    const int32_t *table;              // device [k][pps], first row of this launch
+    uint8_t *out[kLaunchMaxM];
+    uint32_t tab[kLaunchMaxM][kLaunchMaxK][8];
+    uint64_t vecs_per_plane;   // pps * vpp, < 2^32
+    uint64_t pages_per_plane;  // valid page ids are [0, pages_per_plane)
+    uint32_t vpp;              // 16-byte vectors per page
+    int32_t vpp_shift;         // log2(vpp) if a power of two, else -1
+    uint32_t pps;              // pages per shard
+    int32_t k;
+    int32_t accumulate;
+    uint32_t tiles_per_wg;
+};
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const uint8_t *base, uint64_t vec)
+{
+    const u32x4 *p = reinterpret_cast<const u32x4 *>(base) + vec;
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(uint8_t *base, uint64_t vec, u32x4 v)
+{
+    u32x4 *p = reinterpret_cast<u32x4 *>(base) + vec;
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// c (x) each of the four bytes of d, given the five table words of c.
+// v_perm_b32 picks, per selector byte s in 0..7, byte s of the 64-bit value
+// {first operand : second operand}.
+__device__ __forceinline__ uint32_t mul4(const uint32_t *t, uint32_t s0, uint32_t s1, uint32_t s2)
+{
+    return __builtin_amdgcn_perm(t[1], t[0], s0) ^ __builtin_amdgcn_perm(t[3], t[2], s1) ^
+           __builtin_amdgcn_perm(t[4], t[4], s2);
+}
+
+// same product for a single byte, without the permute instruction
+__device__ __forceinline__ uint32_t mul1(const uint32_t *t, uint32_t x)
+{
+    const uint64_t t0 = (static_cast<uint64_t>(t[1]) << 32) | t[0];
+    const uint64_t t1 = (static_cast<uint64_t>(t[3]) << 32) | t[2];
+    return static_cast<uint32_t>((t0 >> (8 * (x & 7))) ^ (t1 >> (8 * ((x >> 3) & 7))) ^
+                                 (t[4] >> (8 * (x >> 6)))) & 0xFFu;
+}
+
+// acc[r][u] ^= C[r][j] (x) x[u] for all rows
+template <int M, bool ROW0_XOR, int U>
+__device__ __forceinline__ void mac(u32x4 (&acc)[M][U], const u32x4 (&x)[U],
+                                    const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8], int j)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t d = x[u][c];
+            if (ROW0_XOR) acc[0][u][c] ^= d;
+            if (M > (ROW0_XOR ? 1 : 0)) {
+                const uint32_t s0 = d & 0x07070707u;
+                const uint32_t s1 = (d >> 3) & 0x07070707u;
+                const uint32_t s2 = (d >> 6) & 0x03030303u;
+#pragma unroll
+                for (int r = (ROW0_XOR ? 1 : 0); r < M; ++r) acc[r][u][c] ^= mul4(tab[r][j], s0, s1, s2);
+            }
+        }
+    }
+}
+
+constexpr int kBatch = 4;  // streams whose loads are issued together
+
+// One tile of the contiguous kernel.  FULL tiles (every lane in range) carry
+// no predication at all; only the last, ragged tile of a shard takes the
+// predicated form.
+template <int M, bool ROW0_XOR, int U, bool NT, bool FULL>
+__device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
+{
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ok[u] = FULL || v0 + static_cast<uint64_t>(u) * kThreads < a.nvec;
+
+    u32x4 acc[M][U];
+#pragma unroll
+    for (int r = 0; r < M; ++r)
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[r][u] = u32x4{0, 0, 0, 0};
+    if (a.accumulate) {
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ok[u]) acc[r][u] = load16<NT>(a.out[r], v0 + static_cast<uint64_t>(u) * kThreads);
+    }
+
+    int j = 0;
+    for (; j + kBatch <= a.k; j += kBatch) {
+        const uint8_t *src[kBatch];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) src[b] = a.in[j + b];
+        u32x4 x[kBatch][U];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                x[b][u] = u32x4{0, 0, 0, 0};
+                if (ok[u]) x[b][u] = load16<NT>(src[b], v0 + static_cast<uint64_t>(u) * kThreads);
+            }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
+    }
+    for (; j < a.k; ++j) {
+        const uint8_t *src = a.in[j];
+        u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            x[u] = u32x4{0, 0, 0, 0};
+            if (ok[u]) x[u] = load16<NT>(src, v0 + static_cast<uint64_t>(u) * kThreads);
+        }
+        mac<M, ROW0_XOR, U>(acc, x, a.tab, j);
+    }
+
+#pragma unroll
+    for (int r = 0; r < M; ++r)
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) store16<NT>(a.out[r], v0 + static_cast<uint64_t>(u) * kThreads, acc[r][u]);
+}
+
+template <int M, bool ROW0_XOR, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void apply_contig_kernel(const ApplyArgs a)
+{
+    const uint32_t tid = threadIdx.x;
+    constexpr uint64_t kTile = static_cast<uint64_t>(kThreads) * U;
+    const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
+
+    for (uint32_t tt = 0; tt < a.tiles_per_wg; ++tt) {
+        const uint64_t base = (first_tile + tt) * kTile;
+        if (base >= a.nvec) break;
+        if (base + kTile <= a.nvec) contig_tile<M, ROW0_XOR, U, NT, true>(a, base + tid);
+        else contig_tile<M, ROW0_XOR, U, NT, false>(a, base + tid);
+    }
+
+    // trailing bytes of a shard whose length is not a multiple of 16: one
+    // lane per byte, in the last workgroup
+    if (a.tail != 0 && blockIdx.x == gridDim.x - 1 && tid < a.tail) {
+        const uint64_t t = a.nvec * 16 + tid;
+#pragma unroll
+        for (int r = 0; r < M; ++r) {
+            uint32_t s = a.accumulate ? a.out[r][t] : 0u;
+            for (int j = 0; j < a.k; ++j) {
+                const uint32_t xb = a.in[j][t];
+                s ^= (ROW0_XOR && r == 0) ? xb : mul1(a.tab[r][j], xb);
+            }
+            a.out[r][t] = static_cast<uint8_t>(s);
+        }
+    }
+}
+
+// One tile of the paged gather.  A lane whose vector index is past the end of
+// the plane, or whose page id is outside the plane, reads vector 0 / page 0
+// instead (always a valid address) and its value is replaced by zero, so the
+// loads need no branches.
+template <int M, bool ROW0_XOR, int U, bool NT>
+__device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint64_t out_base,
+                                           uint64_t first_vec)
+{
+    bool ok[U];
+    uint32_t v[U], slot[U], off[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t vv = first_vec + static_cast<uint64_t>(u) * kThreads;
+        ok[u] = vv < a.vecs_per_plane;
+        v[u] = ok[u] ? static_cast<uint32_t>(vv) : 0u;
+        slot[u] = a.vpp_shift >= 0 ? (v[u] >> a.vpp_shift) : (v[u] / a.vpp);
+        off[u] = v[u] - slot[u] * a.vpp;
+    }
+
+    u32x4 acc[M][U];
+#pragma unroll
+    for (int r = 0; r < M; ++r)
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[r][u] = u32x4{0, 0, 0, 0};
+    if (a.accumulate) {
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[r][u] = load16<NT>(a.out[r], out_base + v[u]);
+    }
+
+    auto gather = [&](int row, int u) -> u32x4 {
+        const int64_t page = a.table[static_cast<uint64_t>(row) * a.pps + slot[u]];
+        const bool valid = ok[u] && static_cast<uint64_t>(page) < a.pages_per_plane;
+        const uint64_t src = valid ? static_cast<uint64_t>(page) * a.vpp + off[u] : 0ull;
+        const u32x4 x = load16<NT>(pbase, src);
+        return valid ? x : u32x4{0, 0, 0, 0};
+    };
+
+    int j = 0;
+    for (; j + kBatch <= a.k; j += kBatch) {
+        u32x4 x[kBatch][U];
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[b][u] = gather(j + b, u);
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
+    }
+    for (; j < a.k; ++j) {
+        u32x4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = gather(j, u);
+        mac<M, ROW0_XOR, U>(acc, x, a.tab, j);
+    }
+
+#pragma unroll
+    for (int r = 0; r < M; ++r)
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) store16<NT>(a.out[r], out_base + v[u], acc[r][u]);
+}
+
+// Paged gather: blockIdx.y is the plane; blockIdx.x walks the plane's
+// pages_per_shard * vpp vectors.  Each lane finds its page slot, looks the
+// page id up in every shard's table row, and reads from that page.
+template <int M, bool ROW0_XOR, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void apply_paged_kernel(const PagedArgs a)
+{
+    constexpr uint64_t kTile = static_cast<uint64_t>(kThreads) * U;
+    const uint32_t plane = blockIdx.y;
+    const uint8_t *pbase = a.plane_base[plane];
+    const uint64_t out_base = static_cast<uint64_t>(plane) * a.vecs_per_plane;
+    const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
+
+    for (uint32_t tt = 0; tt < a.tiles_per_wg; ++tt) {
+        const uint64_t base = (first_tile + tt) * kTile;
+        if (base >= a.vecs_per_plane) break;
+        paged_tile<M, ROW0_XOR, U, NT>(a, pbase, out_base, base + threadIdx.x);
+    }
+}
+
+// ------------------------------------------------------------------ host side
+
+// table words for every constant, built once
+struct CoefTable {
+    CoefWords c[256];
+    CoefTable()
+    {
+        for (unsigned v = 0; v < 256; ++v) c[v] = split_tables(static_cast<uint8_t>(v));
+    }
+};
+
+static const CoefTable &coef_table()
+{
+    static const CoefTable t;
+    return t;
+}
+
+// Fill the table block and output pointers of a launch; if some row of the
+// coefficient slice is all ones it is moved to row 0 so the XOR shortcut
+// applies.  Returns true when row 0 is all ones.
+template <typename Args>
+static bool fill_rows(Args &a, int rows, int k, const uint8_t *coef, int coef_stride, void *const *out)
+{
+    int order[kLaunchMaxM];
+    for (int r = 0; r < rows; ++r) order[r] = r;
+    bool row0_xor = false;
+    for (int r = 0; r < rows && !row0_xor; ++r) {
+        bool ones = true;
+        for (int j = 0; j < k; ++j) ones = ones && coef[r * coef_stride + j] == 1;
+        if (ones) {
+            order[0] = r;
+            order[r] = 0;
+            row0_xor = true;
+        }
+    }
+    const CoefTable &ct = coef_table();
+    for (int r = 0; r < kLaunchMaxM; ++r) {
+        a.out[r] = r < rows ? static_cast<uint8_t *>(out[order[r]]) : nullptr;
+        for (int j = 0; j < kLaunchMaxK; ++j) {
+            const unsigned c = (r < rows && j < k) ? coef[order[r] * coef_stride + j] : 0u;
+            for (int i = 0; i < 5; ++i) a.tab[r][j][i] = ct.c[c].w[i];
+            a.tab[r][j][5] = a.tab[r][j][6] = a.tab[r][j][7] = 0;
+        }
+    }
+    return row0_xor;
+}
+
+template <template <int, bool, int, bool> class Launcher, typename Args>
+static hipError_t dispatch(int rows, bool row0_xor, int unroll, bool nt, const Args &a, dim3 grid,
+                           hipStream_t stream)
+{
+#define GS_CASE_U(M_, X_, U_)                                              \
+    if (unroll == U_) {                                                    \
+        if (nt) return Launcher<M_, X_, U_, true>::go(a, grid, stream);    \
+        return Launcher<M_, X_, U_, false>::go(a, grid, stream);           \
+    }
+#define GS_CASE_MX(M_, X_)  \
+    if (rows == M_ && row0_xor == X_) { GS_CASE_U(M_, X_, 1) GS_CASE_U(M_, X_, 2) GS_CASE_U(M_, X_, 4) }
+    GS_CASE_MX(1, false) GS_CASE_MX(1, true)
+    GS_CASE_MX(2, false) GS_CASE_MX(2, true)
+    GS_CASE_MX(3, false) GS_CASE_MX(3, true)
+    GS_CASE_MX(4, false) GS_CASE_MX(4, true)
+#undef GS_CASE_MX
+#undef GS_CASE_U
+    return hipErrorInvalidValue;
+}
+
+template <int M, bool X, int U, bool NT>
+struct ContigLauncher {
+    static hipError_t go(const ApplyArgs &a, dim3 grid, hipStream_t stream)
+    {
+        hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        return hipGetLastError();
+    }
+};
+
+template <int M, bool X, int U, bool NT>
+struct PagedLauncher {
+    static hipError_t go(const PagedArgs &a, dim3 grid, hipStream_t stream)
+    {
+        hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        return hipGetLastError();
+    }
+};
+
+static int sane_unroll(int u) { return (u == 1 || u == 2 || u == 4) ? u : 2; }
+
+// workgroups along x, and tiles per workgroup raised if needed so that the
+// grid stays below the launch limit on total threads per dimension
+static void grid_for(uint64_t tiles, uint32_t &tiles_per_wg, uint32_t &wgs)
+{
+    constexpr uint64_t kMaxWgs = 1u << 22;
+    if (tiles_per_wg < 1) tiles_per_wg = 1;
+    uint64_t n = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+    if (n > kMaxWgs) {
+        tiles_per_wg = static_cast<uint32_t>((tiles + kMaxWgs - 1) / kMaxWgs);
+        n = (tiles + tiles_per_wg - 1) / tiles_per_wg;
+    }
+    wgs = static_cast<uint32_t>(n ? n : 1);
+}
+
+hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
+                        const void *const *in, void *const *out, size_t bytes,
+                        bool accumulate, const LaunchShape &shape, hipStream_t stream)
+{
+    if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
+    if (bytes == 0) return hipSuccess;
+    ApplyArgs a;
+    const bool row0_xor = fill_rows(a, rows, k, coef, coef_stride, out);
+    for (int j = 0; j < kLaunchMaxK; ++j) a.in[j] = j < k ? static_cast<const uint8_t *>(in[j]) : nullptr;
+    a.nvec = bytes / 16;
+    a.tail = static_cast<uint32_t>(bytes % 16);
+    a.k = k;
+    a.accumulate = accumulate ? 1 : 0;
+    const int unroll = sane_unroll(shape.unroll);
+    const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
+    const uint64_t tiles = (a.nvec + tile - 1) / tile;
+    uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
+    grid_for(tiles, tpw, wgs);
+    a.tiles_per_wg = tpw;
+    return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), stream);
+}
+
+hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
+                              const void *const *plane_base_dev, int n_planes,
+                              size_t page_bytes, int64_t pages_per_plane,
+                              const int32_t *table_dev, int pages_per_shard,
+                              void *const *out, bool accumulate,
+                              const LaunchShape &shape, hipStream_t stream)
+{
+    if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
+    if (n_planes < 1 || n_planes > 65535 || page_bytes == 0 || page_bytes % 16 != 0) return hipErrorInvalidValue;
+    if (pages_per_shard < 1 || pages_per_plane < 1) return hipErrorInvalidValue;
+    const uint64_t vpp = page_bytes / 16;
+    const uint64_t vecs = vpp * static_cast<uint64_t>(pages_per_shard);
+    if (vpp >= (1ull << 32) || vecs >= (1ull << 32)) return hipErrorInvalidValue;
+    PagedArgs a;
+    const bool row0_xor = fill_rows(a, rows, k, coef, coef_stride, out);
+    a.plane_base = reinterpret_cast<const uint8_t *const *>(plane_base_dev);
+    a.table = table_dev;
+    a.vecs_per_plane = vecs;
+    a.pages_per_plane = static_cast<uint64_t>(pages_per_plane < (1ll << 31) ? pages_per_plane : (1ll << 31));
+    a.vpp = static_cast<uint32_t>(vpp);
+    a.vpp_shift = -1;
+    if ((vpp & (vpp - 1)) == 0) {
+        int s = 0;
+        while ((1ull << s) < vpp) ++s;
+        a.vpp_shift = s;
+    }
+    a.pps = static_cast<uint32_t>(pages_per_shard);
+    a.k = k;
+    a.accumulate = accumulate ? 1 : 0;
+    const int unroll = sane_unroll(shape.unroll);
+    const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
+    const uint64_t tiles = (vecs + tile - 1) / tile;
+    uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
+    grid_for(tiles, tpw, wgs);
+    a.tiles_per_wg = tpw;
+    return dispatch<PagedLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a,
+                                   dim3(wgs, static_cast<uint32_t>(n_planes)), stream);
+}
+
+}  // namespace gs

@@ -1,0 +1,33 @@
+// Internal interface between the C ABI layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <cstddef>
+#include <cstdint>
+
+namespace gs {
+
+constexpr int kLaunchMaxK = 16;  // input streams per launch
+constexpr int kLaunchMaxM = 4;   // output rows per launch
+constexpr int kThreads = 256;    // lanes per workgroup (4 wavefronts of 64)
+
+struct LaunchShape {
+    int unroll;        // 16-byte vectors per lane per stream per tile: 1, 2 or 4
+    int tiles_per_wg;  // consecutive tiles per workgroup
+    int nontemporal;   // streaming cache policy on loads and stores
+};
+
+// One launch: out[r] (r < rows <= 4) = XOR_j coef[r*coef_stride + j] (x) in[j], j < k <= 16,
+// over `bytes` bytes; with accumulate the previous contents of out[r] are XORed in.
+hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
+                        const void *const *in, void *const *out, size_t bytes,
+                        bool accumulate, const LaunchShape &shape, hipStream_t stream);
+
+// One launch of the paged gather variant for table rows [j0, j0+k).
+hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
+                              const void *const *plane_base_dev, int n_planes,
+                              size_t page_bytes, int64_t pages_per_plane,
+                              const int32_t *table_dev, int pages_per_shard,
+                              void *const *out, bool accumulate,
+                              const LaunchShape &shape, hipStream_t stream);
+
+}  // namespace gs

@@ -1,0 +1,253 @@
+// Checkpoint / restore pipelines (encode overlapped with parity D2H; parity
+// H2D overlapped with reconstruct) and the captured per-step checkpoint.
+#include "../../include/ghostserve_ec.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "gs_internal.h"
+
+using namespace gs;
+
+// Staging slot s holds m buffers of chunk_bytes.  Two events per slot:
+//   filled[s]   the slot's producer has finished (encode kernel, or H2D copy)
+//   drained[s]  the slot's consumer has finished (D2H copy, or reconstruct kernel)
+// A producer waits on drained[s] before reusing slot s.
+struct gs_pipe {
+    const gs_code *code = nullptr;
+    size_t chunk_bytes = 0;
+    int depth = 0;
+    uint8_t *staging = nullptr;  // depth * m * chunk_bytes
+    std::vector<hipEvent_t> filled, drained;
+    std::vector<char> used;
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t done = nullptr;
+    bool any = false;
+
+    uint8_t *slot_buf(int slot, int row) const
+    {
+        return staging + (static_cast<size_t>(slot) * code->m + row) * chunk_bytes;
+    }
+};
+
+struct gs_step_graph {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+};
+
+#define GS_TRY(expr)                                 \
+    do {                                             \
+        const hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) return hip_status(e_); \
+    } while (0)
+
+extern "C" {
+
+void gs_pipe_destroy(gs_pipe *p)
+{
+    if (p == nullptr) return;
+    if (p->copy_stream) (void)hipStreamSynchronize(p->copy_stream);
+    for (hipEvent_t e : p->filled) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : p->drained) if (e) (void)hipEventDestroy(e);
+    if (p->done) (void)hipEventDestroy(p->done);
+    if (p->copy_stream) (void)hipStreamDestroy(p->copy_stream);
+    if (p->staging) (void)hipFree(p->staging);
+    delete p;
+}
+
+int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (code == nullptr || chunk_bytes == 0 || chunk_bytes % 16 != 0 || depth < 2 || depth > 64) return GS_EINVAL;
+    gs_pipe *p = new (std::nothrow) gs_pipe;
+    if (p == nullptr) return GS_ENOMEM;
+    p->code = code;
+    p->chunk_bytes = chunk_bytes;
+    p->depth = depth;
+    p->filled.assign(depth, nullptr);
+    p->drained.assign(depth, nullptr);
+    p->used.assign(depth, 0);
+    int rc = GS_OK;
+    auto step = [&](hipError_t e) { if (rc == GS_OK && e != hipSuccess) rc = hip_status(e); };
+    step(hipMalloc(reinterpret_cast<void **>(&p->staging), static_cast<size_t>(depth) * code->m * chunk_bytes));
+    // default priority on purpose: streams of mixed priority are not used
+    step(hipStreamCreateWithFlags(&p->copy_stream, hipStreamNonBlocking));
+    for (int s = 0; s < depth && rc == GS_OK; ++s) {
+        step(hipEventCreateWithFlags(&p->filled[s], hipEventDisableTiming));
+        step(hipEventCreateWithFlags(&p->drained[s], hipEventDisableTiming));
+    }
+    step(hipEventCreateWithFlags(&p->done, hipEventDisableTiming));
+    if (rc != GS_OK) {
+        gs_pipe_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return GS_OK;
+}
+
+int gs_checkpoint(gs_pipe *p, const void *const *data, size_t shard_bytes, void *const *host_parity,
+                  void *compute_stream)
+{
+    if (p == nullptr || data == nullptr || host_parity == nullptr) return GS_EINVAL;
+    const int k = p->code->k, m = p->code->m;
+    for (int j = 0; j < k; ++j)
+        if (data[j] == nullptr || (reinterpret_cast<uintptr_t>(data[j]) & 15u)) return GS_EINVAL;
+    for (int i = 0; i < m; ++i)
+        if (host_parity[i] == nullptr) return GS_EINVAL;
+    if (shard_bytes == 0) return GS_OK;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    std::vector<const void *> in(k);
+    std::vector<void *> out(m);
+    const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    for (size_t c = 0; c < nchunks; ++c) {
+        const int slot = static_cast<int>(c % p->depth);
+        const size_t off = c * p->chunk_bytes;
+        const size_t len = std::min(p->chunk_bytes, shard_bytes - off);
+        if (p->used[slot]) GS_TRY(hipStreamWaitEvent(cs, p->drained[slot], 0));
+        for (int j = 0; j < k; ++j) in[j] = static_cast<const uint8_t *>(data[j]) + off;
+        for (int i = 0; i < m; ++i) out[i] = p->slot_buf(slot, i);
+        const int rc = apply_matrix(m, k, p->code->P.data(), in.data(), out.data(), len, cs);
+        if (rc != GS_OK) return rc;
+        GS_TRY(hipEventRecord(p->filled[slot], cs));
+        GS_TRY(hipStreamWaitEvent(p->copy_stream, p->filled[slot], 0));
+        for (int i = 0; i < m; ++i)
+            GS_TRY(hipMemcpyAsync(static_cast<uint8_t *>(host_parity[i]) + off, p->slot_buf(slot, i), len,
+                                  hipMemcpyDeviceToHost, p->copy_stream));
+        GS_TRY(hipEventRecord(p->drained[slot], p->copy_stream));
+        p->used[slot] = 1;
+    }
+    GS_TRY(hipEventRecord(p->done, p->copy_stream));
+    p->any = true;
+    return GS_OK;
+}
+
+int gs_restore(gs_pipe *p, void *const *shards, void *const *host_parity, const int *erased,
+               int n_erased, size_t shard_bytes, void *compute_stream)
+{
+    if (p == nullptr || shards == nullptr || host_parity == nullptr) return GS_EINVAL;
+    const int k = p->code->k;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc0 = decode_matrix(p->code, erased, n_erased, R, surv);
+    if (rc0 != GS_OK) return rc0;
+    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
+    for (int j = 0; j < k; ++j) {
+        const int s = surv[j];
+        if (s < k) {
+            if (shards[s] == nullptr || (reinterpret_cast<uintptr_t>(shards[s]) & 15u)) return GS_EINVAL;
+        } else if (host_parity[s - k] == nullptr) {
+            return GS_EINVAL;
+        }
+    }
+    for (int x = 0; x < n_erased; ++x)
+        if (shards[erased[x]] == nullptr || (reinterpret_cast<uintptr_t>(shards[erased[x]]) & 15u)) return GS_EINVAL;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    std::vector<const void *> in(k);
+    std::vector<void *> out(n_erased);
+    const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    for (size_t c = 0; c < nchunks; ++c) {
+        const int slot = static_cast<int>(c % p->depth);
+        const size_t off = c * p->chunk_bytes;
+        const size_t len = std::min(p->chunk_bytes, shard_bytes - off);
+        if (p->used[slot]) GS_TRY(hipStreamWaitEvent(p->copy_stream, p->drained[slot], 0));
+        for (int j = 0; j < k; ++j) {
+            const int s = surv[j];
+            if (s < k) {
+                in[j] = static_cast<const uint8_t *>(shards[s]) + off;
+            } else {
+                uint8_t *stage = p->slot_buf(slot, s - k);
+                GS_TRY(hipMemcpyAsync(stage, static_cast<const uint8_t *>(host_parity[s - k]) + off, len,
+                                      hipMemcpyHostToDevice, p->copy_stream));
+                in[j] = stage;
+            }
+        }
+        GS_TRY(hipEventRecord(p->filled[slot], p->copy_stream));
+        GS_TRY(hipStreamWaitEvent(cs, p->filled[slot], 0));
+        for (int x = 0; x < n_erased; ++x) out[x] = static_cast<uint8_t *>(shards[erased[x]]) + off;
+        const int rc = apply_matrix(n_erased, k, R.data(), in.data(), out.data(), len, cs);
+        if (rc != GS_OK) return rc;
+        GS_TRY(hipEventRecord(p->drained[slot], cs));
+        p->used[slot] = 1;
+    }
+    GS_TRY(hipEventRecord(p->done, cs));
+    p->any = true;
+    return GS_OK;
+}
+
+int gs_pipe_sync(gs_pipe *p)
+{
+    if (p == nullptr) return GS_EINVAL;
+    if (!p->any) return GS_OK;
+    GS_TRY(hipEventSynchronize(p->done));
+    return GS_OK;
+}
+
+void *gs_pipe_done_event(gs_pipe *p) { return (p && p->any) ? static_cast<void *>(p->done) : nullptr; }
+
+void gs_step_graph_destroy(gs_step_graph *g)
+{
+    if (g == nullptr) return;
+    if (g->exec) (void)hipGraphExecDestroy(g->exec);
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    delete g;
+}
+
+int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int n_planes,
+                         size_t page_bytes, int64_t pages_per_plane, const int32_t *table,
+                         int pages_per_shard, void *const *parity, void *const *host_parity,
+                         gs_step_graph **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (code == nullptr || n_planes < 1 || pages_per_shard < 1) return GS_EINVAL;
+    gs_step_graph *g = new (std::nothrow) gs_step_graph;
+    if (g == nullptr) return GS_ENOMEM;
+    hipStream_t s = nullptr;
+    hipError_t e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
+    if (e != hipSuccess) {
+        delete g;
+        return hip_status(e);
+    }
+    int rc = GS_OK;
+    e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) rc = hip_status(e);
+    if (rc == GS_OK) {
+        rc = gs_encode_paged(code, plane_base, n_planes, page_bytes, pages_per_plane, table,
+                             pages_per_shard, parity, s);
+        if (rc == GS_OK && host_parity != nullptr) {
+            const size_t bytes = static_cast<size_t>(n_planes) * pages_per_shard * page_bytes;
+            for (int i = 0; i < code->m && rc == GS_OK; ++i) {
+                if (host_parity[i] == nullptr) { rc = GS_EINVAL; break; }
+                e = hipMemcpyAsync(host_parity[i], parity[i], bytes, hipMemcpyDeviceToHost, s);
+                if (e != hipSuccess) rc = hip_status(e);
+            }
+        }
+        // always close the capture, also on failure
+        e = hipStreamEndCapture(s, &g->graph);
+        if (rc == GS_OK && e != hipSuccess) rc = hip_status(e);
+    }
+    if (rc == GS_OK) {
+        e = hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) rc = hip_status(e);
+    }
+    (void)hipStreamDestroy(s);
+    if (rc != GS_OK) {
+        gs_step_graph_destroy(g);
+        return rc;
+    }
+    *out = g;
+    return GS_OK;
+}
+
+int gs_step_graph_launch(gs_step_graph *g, void *stream)
+{
+    if (g == nullptr || g->exec == nullptr) return GS_EINVAL;
+    GS_TRY(hipGraphLaunch(g->exec, static_cast<hipStream_t>(stream)));
+    return GS_OK;
+}
+
+}  // extern "C"

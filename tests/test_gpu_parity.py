@@ -1,0 +1,327 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+byte for byte, on the same seeded inputs.  Integer/byte work, so the bar is
+bit-exact everywhere."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+CANARY = 0xC7
+PAD = 256  # canary bytes after every output buffer
+
+
+@pytest.fixture(scope="module")
+def gs():
+    from paper_2605_00831_amd import binding
+    binding.lib()
+    yield binding
+    binding.gs_set_launch_shape()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def out_buf(nbytes):
+    """device buffer of nbytes + PAD canary bytes (whole thing pre-filled)"""
+    return torch.full((nbytes + PAD,), CANARY, dtype=torch.uint8, device="cuda")
+
+
+def check_out(buf, want):
+    got = buf.cpu().numpy()
+    n = want.size
+    assert np.array_equal(got[:n], want), "payload differs (first at %d)" % int(np.nonzero(got[:n] != want)[0][0])
+    assert (got[n:] == CANARY).all(), "wrote past shard_bytes"
+
+
+def rand_shards(seed, k, S):
+    return [inputs.uniform_bytes_np(seed * 1009 + j, S) for j in range(k)]
+
+
+def gpu_encode(gs, code, data_np, S, stream=None):
+    d = [dev(x) for x in data_np]
+    p = [out_buf(S) for _ in range(code.m)]
+    gs.gs_encode(code, d, p, S, stream)
+    torch.cuda.synchronize()
+    return d, p
+
+
+# ---------------------------------------------------------------- encode
+
+SIZES = [1, 15, 16, 17, 4095, 4096, 4097, 8192 + 16, 65536 + 5, 3 * 8192 + 4080, 1 << 20, (1 << 21) + 3]
+
+
+@pytest.mark.parametrize("k,m", [(4, 2), (4, 1), (8, 2), (8, 3), (1, 1), (2, 4), (3, 3), (5, 3), (7, 2), (16, 4)])
+def test_encode_matches_oracle_over_ragged_sizes(gs, k, m):
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    assert np.array_equal(gs.gs_code_matrix(code), P)
+    for S in SIZES:
+        if k * S > (24 << 20):
+            continue
+        data = rand_shards(S + k, k, S)
+        want = oracle.encode(P, data, nthreads=8)
+        d, p = gpu_encode(gs, code, data, S)
+        for i in range(m):
+            check_out(p[i], want[i])
+        for j in range(k):
+            assert np.array_equal(d[j].cpu().numpy(), data[j])  # inputs untouched
+
+
+@pytest.mark.parametrize("unroll,tiles_per_wg,nt", [(1, 1, 1), (2, 1, 0), (4, 1, 1), (1, 3, 0), (2, 5, 1), (4, 2, 0),
+                                                   (2, 64, 1)])
+def test_every_launch_shape_gives_the_same_bytes(gs, unroll, tiles_per_wg, nt):
+    gs.gs_set_launch_shape(unroll, tiles_per_wg, nt)
+    try:
+        for (k, m), S in itertools.product([(4, 2), (8, 3), (6, 1)], [16 * 256 * 11 + 48 + 7, 777]):
+            code = gs.gs_make_code(k, m)
+            data = rand_shards(S + k + unroll, k, S)
+            want = oracle.encode(oracle.generator(k, m), data, nthreads=8)
+            _, p = gpu_encode(gs, code, data, S)
+            for i in range(m):
+                check_out(p[i], want[i])
+    finally:
+        gs.gs_set_launch_shape()
+
+
+def test_wide_code_runs_as_accumulating_launches(gs):
+    """k > 16 or m > 4 is split into several launches that XOR-accumulate."""
+    for k, m, S in [(20, 6, 70001), (33, 2, 4096 + 9), (17, 5, 123)]:
+        code = gs.gs_make_code(k, m)
+        data = rand_shards(k * 7 + m, k, S)
+        want = oracle.encode(oracle.generator(k, m), data, nthreads=8)
+        _, p = gpu_encode(gs, code, data, S)
+        for i in range(m):
+            check_out(p[i], want[i])
+
+
+def test_encode_on_a_side_stream(gs):
+    k, m, S = 4, 2, (1 << 20) + 100
+    code = gs.gs_make_code(k, m)
+    data = rand_shards(91, k, S)
+    want = oracle.encode(oracle.generator(k, m), data, nthreads=8)
+    s = torch.cuda.Stream()
+    d = [dev(x) for x in data]
+    p = [out_buf(S) for _ in range(m)]
+    torch.cuda.synchronize()
+    gs.gs_encode(code, d, p, S, s)
+    s.synchronize()
+    for i in range(m):
+        check_out(p[i], want[i])
+
+
+def test_config1_tiny_encode_then_lose_1_and_3(gs):
+    """fp16 KV of a 2-layer model, 1024 tokens, 8 MiB, k=4, m=2; erase {1,3}."""
+    c = inputs.CONFIGS["tiny"]
+    buf = inputs.kv_bytes_np(inputs.config_seed("tiny"), inputs.config_total_bytes("tiny"), c["dtype"], c["sigma"])
+    inputs.plant_specials(buf, "fp16", 1)
+    data = [np.ascontiguousarray(s) for s in inputs.split_shards(buf, 4)]
+    S = data[0].size
+    assert S == 2 << 20
+    P = oracle.generator(4, 2)
+    want = oracle.encode(P, data, nthreads=8)
+    code = gs.gs_make_code(4, 2)
+    d, p = gpu_encode(gs, code, data, S)
+    for i in range(2):
+        check_out(p[i], want[i])
+    # failure = flushed buffers: poison the lost shards, rebuild in place
+    shards = d + [x[:S] for x in p]
+    for r in c["erased"]:
+        shards[r].fill_(0xA5)
+    gs.gs_reconstruct(code, shards, list(c["erased"]), S)
+    torch.cuda.synchronize()
+    full = data + want
+    for r in range(6):
+        got = shards[r].cpu().numpy()
+        assert np.array_equal(got, full[r])
+        assert np.array_equal(got.view(np.int16), full[r].view(np.int16))
+    # and the oracle agrees on the same erasure
+    work = [x.copy() for x in full]
+    for r in c["erased"]:
+        work[r][:] = 0xA5
+    oracle.reconstruct(P, work, list(c["erased"]))
+    assert all(np.array_equal(a, b) for a, b in zip(work, full))
+
+
+# ---------------------------------------------------------------- reconstruct
+
+def _stripe_on_gpu(gs, k, m, S, seed, kv=False):
+    if kv:
+        buf = inputs.kv_bytes_np(seed, k * S, "bf16", 1.0)
+        inputs.plant_specials(buf, "bf16", seed)
+        data = [np.ascontiguousarray(x) for x in inputs.split_shards(buf, k)]
+    else:
+        data = rand_shards(seed, k, S)
+    P = oracle.generator(k, m)
+    full = data + oracle.encode(P, data, nthreads=8)
+    return P, full
+
+
+def _reconstruct_and_check(gs, code, P, full, pat, S):
+    n = len(full)
+    bufs = []
+    for r in range(n):
+        if r in pat:
+            b = out_buf(S)
+            b[:S] = 0xA5
+        else:
+            b = torch.cat([dev(full[r]), torch.full((PAD,), CANARY, dtype=torch.uint8, device="cuda")])
+        bufs.append(b)
+    gs.gs_reconstruct(code, bufs, list(pat), S)
+    torch.cuda.synchronize()
+    for r in range(n):
+        check_out(bufs[r], full[r])
+    # the oracle rebuilds the same bytes from the same survivors
+    work = [x.copy() for x in full]
+    for r in pat:
+        work[r][:] = 0xA5
+    oracle.reconstruct(P, work, list(pat))
+    for r in pat:
+        assert np.array_equal(work[r], full[r])
+
+
+@pytest.mark.parametrize("k,m", [(4, 2), (3, 3), (2, 4), (5, 1), (1, 2)])
+def test_reconstruct_every_erasure_subset_small_codes(gs, k, m):
+    S = 4096 + 16 + 5
+    P, full = _stripe_on_gpu(gs, k, m, S, 300 + k * 8 + m)
+    code = gs.gs_make_code(k, m)
+    for pat in inputs.all_erasure_patterns(k + m, m, 1):
+        _reconstruct_and_check(gs, code, P, full, pat, S)
+
+
+def test_config5_small_all_165_triples(gs):
+    """k=8, m=3, S = 64 KiB + 5: shards 0-3 uniform bytes, 4-7 bf16 N(0,1) KV."""
+    c = inputs.CONFIGS["recovery_stress"]
+    S = c["small_shard_bytes"]
+    seed = inputs.config_seed("recovery_stress")
+    data = [inputs.uniform_bytes_np(seed + j, S) for j in range(4)]
+    data += [inputs.kv_bytes_np(seed + j, S, "bf16", 1.0) for j in range(4, 8)]
+    P = oracle.generator(8, 3)
+    full = data + oracle.encode(P, data, nthreads=8)
+    code = gs.gs_make_code(8, 3)
+    pats = list(itertools.combinations(range(11), 3))
+    assert len(pats) == 165
+    for pat in pats:
+        _reconstruct_and_check(gs, code, P, full, pat, S)
+
+
+def test_reconstruct_wide_code_and_order_of_erased_list(gs):
+    k, m, S = 20, 6, 9001
+    P, full = _stripe_on_gpu(gs, k, m, S, 17)
+    code = gs.gs_make_code(k, m)
+    for pat in [(0, 19, 20, 25, 7, 3), (25, 24, 23, 22, 21, 20), (5,), (19, 18, 17, 16, 15, 14)]:
+        _reconstruct_and_check(gs, code, P, full, pat, S)
+
+
+def test_reconstruct_is_lossless_for_float_bit_patterns(gs):
+    k, m, S = 4, 2, 1 << 16
+    P, full = _stripe_on_gpu(gs, k, m, S, 5, kv=True)
+    code = gs.gs_make_code(k, m)
+    _reconstruct_and_check(gs, code, P, full, (0, 2), S)
+    allv = np.concatenate([s.view(np.uint16) for s in full[:k]])
+    for pat in inputs.special_bits("bf16"):
+        assert (allv == pat).any()
+
+
+def test_reconstruct_errors_write_nothing(gs):
+    k, m, S = 4, 2, 1024
+    P, full = _stripe_on_gpu(gs, k, m, S, 6)
+    code = gs.gs_make_code(k, m)
+    bufs = [dev(x) for x in full]
+    for bad, status in [([0, 1, 2], gs.GS_ETOOMANY), ([1, 1], gs.GS_EINVAL), ([9], gs.GS_EINVAL)]:
+        with pytest.raises(gs.GsError) as e:
+            gs.gs_reconstruct(code, bufs, bad, S)
+        assert e.value.status == status
+    gs.gs_reconstruct(code, bufs, [], S)
+    torch.cuda.synchronize()
+    for r in range(k + m):
+        assert np.array_equal(bufs[r].cpu().numpy(), full[r])
+
+
+# ---------------------------------------------------------------- paged
+
+def _paged_case(gs, k, m, n_planes, pps, page_bytes, extra_pages=9, seed=1):
+    num_pages = k * pps + extra_pages
+    planes_np = [inputs.kv_bytes_np(seed * 100 + p, num_pages * page_bytes, "bf16", 1.0) for p in range(n_planes)]
+    table_np = inputs.block_table_np(seed, k, pps, num_pages)
+    P = oracle.generator(k, m)
+    want = oracle.encode_paged(P, planes_np, page_bytes, table_np)
+    planes = [dev(x) for x in planes_np]
+    base = torch.tensor([x.data_ptr() for x in planes], dtype=torch.int64, device="cuda")
+    table = dev(table_np)
+    out_bytes = n_planes * pps * page_bytes
+    par = [out_buf(out_bytes) for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    gs.gs_encode_paged(code, base, n_planes, page_bytes, num_pages, table, pps, par)
+    torch.cuda.synchronize()
+    for i in range(m):
+        check_out(par[i], want[i])
+    for p in range(n_planes):
+        assert np.array_equal(planes[p].cpu().numpy(), planes_np[p])
+    return planes_np, table_np, want
+
+
+@pytest.mark.parametrize("k,m,n_planes,pps,page_bytes", [
+    (4, 1, 64, 16, 2048),    # the decode-step geometry: 64 planes, 16 token slots of 2 KiB
+    (4, 2, 3, 5, 32768),     # whole 16-token blocks
+    (8, 2, 16, 7, 512),      # KV-head-group segments
+    (3, 3, 2, 11, 48),       # page size not a power of two
+    (5, 2, 1, 1, 16),        # one vector
+    (20, 5, 2, 9, 1040),     # wide code through the paged path
+])
+def test_paged_encode_matches_oracle(gs, k, m, n_planes, pps, page_bytes):
+    for shape in [(1, 1, 1), (2, 1, 1), (4, 2, 0)]:
+        gs.gs_set_launch_shape(*shape)
+        try:
+            _paged_case(gs, k, m, n_planes, pps, page_bytes)
+        finally:
+            gs.gs_set_launch_shape()
+
+
+def test_paged_out_of_range_page_ids_read_as_zero(gs):
+    k, m, n_planes, pps, page_bytes = 4, 2, 2, 6, 256
+    num_pages = k * pps
+    planes_np = [inputs.uniform_bytes_np(40 + p, num_pages * page_bytes) for p in range(n_planes)]
+    table_np = inputs.block_table_np(3, k, pps, num_pages)
+    table_bad = table_np.copy()
+    table_bad[1, 2] = -1
+    table_bad[3, 0] = num_pages
+    table_bad[2, 5] = 2 ** 31 - 1
+    # oracle view: those pages are zero pages appended to the pool
+    planes_z = [np.concatenate([pl, np.zeros(page_bytes, np.uint8)]) for pl in planes_np]
+    table_z = table_bad.copy()
+    table_z[(table_bad < 0) | (table_bad >= num_pages)] = num_pages
+    P = oracle.generator(k, m)
+    want = oracle.encode_paged(P, planes_z, page_bytes, table_z)
+    planes = [dev(x) for x in planes_np]
+    base = torch.tensor([x.data_ptr() for x in planes], dtype=torch.int64, device="cuda")
+    par = [out_buf(n_planes * pps * page_bytes) for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    gs.gs_encode_paged(code, base, n_planes, page_bytes, num_pages, dev(table_bad), pps, par)
+    torch.cuda.synchronize()
+    for i in range(m):
+        check_out(par[i], want[i])
+
+
+def test_paged_identity_table_equals_contiguous_encode(gs):
+    k, m, pps, page_bytes = 4, 2, 8, 4096
+    plane_np = inputs.uniform_bytes_np(4, k * pps * page_bytes)
+    table_np = np.arange(k * pps, dtype=np.int32).reshape(k, pps)
+    plane = dev(plane_np)
+    base = torch.tensor([plane.data_ptr()], dtype=torch.int64, device="cuda")
+    code = gs.gs_make_code(k, m)
+    S = pps * page_bytes
+    par_p = [out_buf(S) for _ in range(m)]
+    par_c = [out_buf(S) for _ in range(m)]
+    gs.gs_encode_paged(code, base, 1, page_bytes, k * pps, dev(table_np), pps, par_p)
+    gs.gs_encode(code, [plane[j * S:(j + 1) * S] for j in range(k)], par_c, S)
+    torch.cuda.synchronize()
+    for i in range(m):
+        assert torch.equal(par_p[i], par_c[i])

@@ -1,0 +1,136 @@
+"""CPU-only checks of the HIP library's host side: it loads, exports what the
+header declares, builds the same generator and rebuild matrices as the oracle
+(two independent implementations: closed-form Cauchy + shift-and-reduce
+multiply in the library, Vandermonde + elimination + log/exp in the oracle),
+builds correct lookup words, and rejects bad arguments.  No kernel is
+launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import binding as gs
+from paper_2605_00831_amd import inputs
+from tests import _gfref
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "ghostserve_ec.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(gs_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(gs.EXPORTS)
+    L = gs.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+@pytest.mark.parametrize("k,m", [(1, 1), (4, 1), (4, 2), (8, 2), (8, 3), (5, 3), (16, 4), (20, 6),
+                                 (17, 5), (250, 6), (1, 255), (128, 128)])
+def test_generator_matches_oracle_for_both_kinds(k, m):
+    want = oracle.generator(k, m)
+    for kind in (gs.GS_CAUCHY, gs.GS_VANDERMONDE):
+        code = gs.gs_make_code(k, m, kind)
+        assert np.array_equal(gs.gs_code_matrix(code), want)
+
+
+def test_make_code_rejects_bad_parameters():
+    for k, m, kind in [(0, 1, 0), (1, 0, 0), (-3, 2, 0), (200, 57, 0), (4, 2, 2), (4, 2, -1)]:
+        with pytest.raises(gs.GsError) as e:
+            gs.gs_make_code(k, m, kind)
+        assert e.value.status == gs.GS_EINVAL
+    gs.gs_make_code(200, 56)
+
+
+@pytest.mark.parametrize("k,m", [(4, 2), (8, 3), (5, 3), (2, 4), (3, 1)])
+def test_decode_matrix_matches_oracle_for_every_pattern(k, m):
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    for pat in inputs.all_erasure_patterns(k + m, m, 0):
+        for order in (list(pat), list(reversed(pat))):
+            R, surv = gs.gs_decode_matrix(code, order)
+            Ro, so = oracle.decode_matrix(P, order)
+            assert surv == so and np.array_equal(R, Ro), (k, m, order)
+
+
+def test_decode_matrix_errors():
+    code = gs.gs_make_code(4, 2)
+    for bad, status in [([0, 0], gs.GS_EINVAL), ([6], gs.GS_EINVAL), ([-1], gs.GS_EINVAL),
+                        ([0, 1, 2], gs.GS_ETOOMANY)]:
+        with pytest.raises(gs.GsError) as e:
+            gs.gs_decode_matrix(code, bad)
+        assert e.value.status == status
+
+
+def _perm_b32(hi, lo, sel):
+    """v_perm_b32 for selector bytes 0..7: byte s of the 64-bit value {hi:lo}."""
+    pool = [(lo >> (8 * i)) & 0xFF for i in range(4)] + [(hi >> (8 * i)) & 0xFF for i in range(4)]
+    out = 0
+    for b in range(4):
+        s = (sel >> (8 * b)) & 0xFF
+        assert s < 8
+        out |= pool[s] << (8 * b)
+    return out
+
+
+def test_lookup_words_multiply_every_byte_by_every_constant():
+    t = _gfref.T()
+    rng = np.random.default_rng(3)
+    for c in range(256):
+        w = gs.gs_coef_words(c)
+        # all 256 byte values, four at a time, the way the kernel does it
+        for base in range(0, 256, 4):
+            d = base | (base + 1) << 8 | (base + 2) << 16 | (base + 3) << 24
+            s0, s1, s2 = d & 0x07070707, (d >> 3) & 0x07070707, (d >> 6) & 0x03030303
+            got = _perm_b32(w[1], w[0], s0) ^ _perm_b32(w[3], w[2], s1) ^ _perm_b32(w[4], w[4], s2)
+            want = sum(int(t[c, base + i]) << (8 * i) for i in range(4))
+            assert got == want, (c, base)
+        d = int(rng.integers(0, 1 << 32))
+        s0, s1, s2 = d & 0x07070707, (d >> 3) & 0x07070707, (d >> 6) & 0x03030303
+        got = _perm_b32(w[1], w[0], s0) ^ _perm_b32(w[3], w[2], s1) ^ _perm_b32(w[4], w[4], s2)
+        want = sum(int(t[c, (d >> (8 * i)) & 0xFF]) << (8 * i) for i in range(4))
+        assert got == want
+
+
+def test_entry_points_validate_before_touching_the_gpu():
+    """Every check below fails in argument validation, so no HIP call is made."""
+    L = gs.lib()
+    code = gs.gs_make_code(4, 2)
+    vp = ctypes.c_void_p
+    good = (vp * 4)(0x1000, 0x2000, 0x3000, 0x4000)
+    par = (vp * 2)(0x5000, 0x6000)
+    odd = (vp * 4)(0x1000, 0x2001, 0x3000, 0x4000)
+    null = (vp * 4)(0x1000, None, 0x3000, 0x4000)
+    assert L.gs_encode(None, good, par, 64, None) == gs.GS_EINVAL
+    assert L.gs_encode(code.handle, odd, par, 64, None) == gs.GS_EINVAL
+    assert L.gs_encode(code.handle, null, par, 64, None) == gs.GS_EINVAL
+    assert L.gs_encode(code.handle, good, None, 64, None) == gs.GS_EINVAL
+    assert L.gs_encode(code.handle, good, par, 0, None) == gs.GS_OK          # empty shard: no-op
+    six = (vp * 6)(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000)
+    er = (ctypes.c_int * 3)(0, 1, 2)
+    assert L.gs_reconstruct(code.handle, six, er, 3, 64, None) == gs.GS_ETOOMANY
+    er = (ctypes.c_int * 2)(1, 1)
+    assert L.gs_reconstruct(code.handle, six, er, 2, 64, None) == gs.GS_EINVAL
+    er = (ctypes.c_int * 1)(7)
+    assert L.gs_reconstruct(code.handle, six, er, 1, 64, None) == gs.GS_EINVAL
+    assert L.gs_reconstruct(code.handle, six, er, 0, 64, None) == gs.GS_OK   # nothing erased: no-op
+    er = (ctypes.c_int * 1)(2)
+    assert L.gs_reconstruct(code.handle, six, er, 1, 0, None) == gs.GS_OK    # empty shards: no-op
+    # paged: page size must be a positive multiple of 16; sizes must be in range
+    for page_bytes, n_planes, ppp, pps in [(0, 1, 8, 4), (24, 1, 8, 4), (64, -1, 8, 4), (64, 70000, 8, 4),
+                                           (64, 1, 8, -2), (64, 1, 0, 4), (1 << 40, 1, 8, 4)]:
+        assert L.gs_encode_paged(code.handle, 0x1000, n_planes, page_bytes, ppp, 0x2000, pps, par,
+                                 None) == gs.GS_EINVAL
+    assert L.gs_encode_paged(code.handle, 0x1000, 0, 64, 8, 0x2000, 4, par, None) == gs.GS_OK
+    assert L.gs_encode_paged(code.handle, 0x1000, 3, 64, 8, 0x2000, 0, par, None) == gs.GS_OK
+    out = vp()
+    assert L.gs_pipe_create(code.handle, 100, 2, ctypes.byref(out)) == gs.GS_EINVAL   # not a multiple of 16
+    assert L.gs_pipe_create(code.handle, 1024, 1, ctypes.byref(out)) == gs.GS_EINVAL  # depth < 2
+    assert L.gs_set_launch_shape(3, 1, 1) == gs.GS_EINVAL
+    assert L.gs_set_launch_shape(0, 0, -1) == gs.GS_OK
+    assert L.gs_strerror(gs.GS_ETOOMANY).decode() == "more erasures than parity shards"
