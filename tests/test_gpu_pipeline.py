@@ -1,0 +1,159 @@
+"""GPU parity for the checkpoint / restore pipelines (encode + parity D2H into
+pinned host memory; parity H2D + reconstruct) and the captured per-step
+checkpoint, against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gs():
+    from paper_2605_00831_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def pinned(nbytes, fill=0x5A):
+    t = torch.empty(nbytes + 64, dtype=torch.uint8, pin_memory=True)
+    t.fill_(fill)
+    return t
+
+
+@pytest.mark.parametrize("k,m,S,chunk,depth", [
+    (4, 2, (1 << 20) + 37, 256 << 10, 2),   # 5 chunks, ragged last chunk
+    (8, 2, 3 << 18, 1 << 18, 3),            # exact multiple
+    (4, 1, 1000, 4096, 2),                  # single short chunk
+    (8, 3, (1 << 19) + 16, 64 << 10, 4),    # many chunks, depth 4
+])
+def test_checkpoint_pipeline_parity_lands_in_pinned_host_memory(gs, k, m, S, chunk, depth):
+    data_np = [inputs.kv_bytes_np(50 + j, S, "bf16", 0.5) for j in range(k)]
+    want = oracle.encode(oracle.generator(k, m), data_np, nthreads=8)
+    code = gs.gs_make_code(k, m)
+    pipe = gs.gs_pipe_create(code, chunk, depth)
+    data = [dev(x) for x in data_np]
+    host = [pinned(S) for _ in range(m)]
+    torch.cuda.synchronize()
+    for rep in range(2):  # second run reuses staging slots that are still marked used
+        for h in host:
+            h.fill_(0x5A)
+        gs.gs_checkpoint(pipe, data, S, host)
+        gs.gs_pipe_sync(pipe)
+        for i in range(m):
+            got = host[i].numpy()
+            assert np.array_equal(got[:S], want[i]), (rep, i)
+            assert (got[S:] == 0x5A).all()
+    gs.gs_pipe_destroy(pipe)
+
+
+@pytest.mark.parametrize("k,m,S,chunk,pat", [
+    (4, 2, (1 << 20) + 37, 256 << 10, (1, 3)),      # two data shards lost: both parities come back H2D
+    (4, 2, (1 << 20) + 37, 256 << 10, (0,)),        # one lost: only parity 0 is read
+    (8, 3, (1 << 19) + 16, 64 << 10, (2, 5, 9)),    # data + a parity shard lost
+    (8, 3, 1 << 18, 1 << 18, (8, 9, 10)),           # only parity lost: re-encode, no H2D
+    (4, 2, 5000, 4096, (3, 5)),
+])
+def test_restore_pipeline_rebuilds_from_host_parity(gs, k, m, S, chunk, pat):
+    data_np = [inputs.uniform_bytes_np(70 + j, S) for j in range(k)]
+    P = oracle.generator(k, m)
+    par_np = oracle.encode(P, data_np, nthreads=8)
+    full = data_np + par_np
+    code = gs.gs_make_code(k, m)
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    host = []
+    for i in range(m):
+        h = pinned(S)
+        h[:S] = torch.from_numpy(par_np[i])
+        host.append(h)
+    shards = []
+    for r in range(k + m):
+        if r < k:
+            t = dev(full[r]) if r not in pat else torch.full((S + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        else:
+            t = torch.full((S + 64,), 0xA5, dtype=torch.uint8, device="cuda") if r in pat else None
+        shards.append(t)
+    torch.cuda.synchronize()
+    gs.gs_restore(pipe, shards, host, list(pat), S)
+    gs.gs_pipe_sync(pipe)
+    torch.cuda.synchronize()
+    for r in pat:
+        got = shards[r].cpu().numpy()
+        assert np.array_equal(got[:S], full[r]), r
+        assert (got[S:] == 0xA5).all()
+    for r in range(k):
+        if r not in pat:
+            assert np.array_equal(shards[r].cpu().numpy(), full[r])
+    # same answer as the oracle's reconstruct
+    work = [x.copy() for x in full]
+    for r in pat:
+        work[r][:] = 0
+    oracle.reconstruct(P, work, list(pat))
+    for r in pat:
+        assert np.array_equal(work[r], full[r])
+    gs.gs_pipe_destroy(pipe)
+
+
+def test_checkpoint_then_restore_on_one_pipe(gs):
+    k, m, S, chunk = 4, 2, (3 << 18) + 48, 1 << 18
+    data_np = [inputs.kv_bytes_np(90 + j, S, "fp16", 1.0) for j in range(k)]
+    code = gs.gs_make_code(k, m)
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    data = [dev(x) for x in data_np]
+    host = [pinned(S) for _ in range(m)]
+    torch.cuda.synchronize()
+    gs.gs_checkpoint(pipe, data, S, host)
+    gs.gs_pipe_sync(pipe)
+    data[1].fill_(0xA5)
+    data[2].fill_(0xA5)
+    gs.gs_restore(pipe, data + [None, None], host, [1, 2], S)
+    gs.gs_pipe_sync(pipe)
+    torch.cuda.synchronize()
+    for j in range(k):
+        assert np.array_equal(data[j].cpu().numpy(), data_np[j])
+
+
+def test_step_graph_replays_track_the_block_table(gs):
+    """Decode-step checkpoint: 64 planes, 16-token blocks of 2 KiB slots, 64
+    sequences in k=4 shards of 16, m=1 (XOR).  The graph is captured once; each
+    step the engine rewrites the device block table in place and replays."""
+    k, m, n_planes, seqs_per_shard, slot_bytes, block_tokens = 4, 1, 64, 16, 2048, 16
+    n_blocks = 96
+    pages_per_plane = n_blocks * block_tokens
+    rng = np.random.default_rng(inputs.config_seed("decode_paged"))
+    planes_np = [inputs.kv_bytes_np(1000 + p, pages_per_plane * slot_bytes, "bf16", 1.0) for p in range(n_planes)]
+    planes = [dev(x) for x in planes_np]
+    base = torch.tensor([x.data_ptr() for x in planes], dtype=torch.int64, device="cuda")
+    table = torch.zeros((k, seqs_per_shard), dtype=torch.int32, device="cuda")
+    out_bytes = n_planes * seqs_per_shard * slot_bytes
+    par = [torch.zeros(out_bytes, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    host = [pinned(out_bytes) for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    torch.cuda.synchronize()
+    graph = gs.gs_step_graph_create(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard,
+                                    par, host)
+    eager = [torch.zeros(out_bytes, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    for step in range(6):
+        blocks = rng.permutation(n_blocks)[: k * seqs_per_shard].reshape(k, seqs_per_shard)
+        table_np = (blocks * block_tokens + (step % block_tokens)).astype(np.int32)
+        table.copy_(torch.from_numpy(table_np))          # program's own eager work between replays
+        torch.cuda.synchronize()
+        gs.gs_step_graph_launch(graph)
+        torch.cuda.synchronize()
+        gs.gs_encode_paged(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, eager)
+        torch.cuda.synchronize()
+        want = oracle.encode_paged(P, planes_np, slot_bytes, table_np)
+        for i in range(m):
+            assert np.array_equal(par[i].cpu().numpy(), want[i]), step
+            assert np.array_equal(host[i].numpy()[:out_bytes], want[i]), step
+            assert torch.equal(eager[i], par[i])
+    gs.gs_step_graph_destroy(graph)
