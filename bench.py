@@ -1,0 +1,314 @@
+#!/usr/bin/env python3
+"""Benchmark of the erasure-code hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A "step" is one pass of the hot path over the workload's resident KV bytes:
+build the code and the rebuild matrix on the host, encode the k data shards
+into m parity shards (gs_encode), then lose shards and rebuild them from the
+survivors (gs_reconstruct).  `value` is the data bytes that pass through those
+two kernels per second of wall time, inputs already in HBM.  The PCIe legs
+(parity D2H pipeline, H2D restore), the paged per-step path and the CPU
+oracle's rate are measured outside the timed steps and reported as extra
+fields of the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
+
+# HBM traffic of one encode launch measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE, scaled by a plain copy kernel of known size; see
+# profiles/encode_contig_llama8b_prefill.md.  Bytes per launch, or None.
+MEASURED_TRAFFIC_BYTES = {
+    "llama8b_prefill": (33554573 + 16777248) * 1024,   # fetch (scaled x2.0000) + write, KiB -> bytes
+}
+
+
+def pctl(xs, q):
+    xs = sorted(xs)
+    return xs[min(len(xs) - 1, int(q * len(xs)))]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_prefill",
+                    choices=["llama8b_prefill", "llama70b_longctx", "tiny"])
+    ap.add_argument("--no-extras", action="store_true", help="skip PCIe pipelines, paged steps and CPU baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 8 GiB device-to-device copy kernel (counter calibration under rocprofv3 --pmc)")
+    ap.add_argument("--cpu-sample-mib", type=int, default=4096, help="bytes per shard for the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_00831_amd import binding as gs
+    from paper_2605_00831_amd import inputs
+
+    gs.lib()  # hard error if the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+
+    cfg = inputs.CONFIGS[args.workload]
+    k, m = cfg["k"], cfg["m"]
+    total = inputs.config_total_bytes(args.workload)
+    S = total // k
+    erased = list(cfg.get("erased", (1, 3) if k >= 4 else (0,)))[:m]
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    log("[bench] workload %s: k=%d m=%d S=%.3f GiB total %.1f GiB" % (args.workload, k, m, S / 2**30, total / 2**30))
+
+    t0 = time.perf_counter()
+    buf = inputs.kv_bytes_device(inputs.config_seed(args.workload), total, cfg["dtype"], cfg["sigma"], dev)
+    data = [buf[j * S:(j + 1) * S] for j in range(k)]
+    parity = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(m)]
+    torch.cuda.synchronize()
+    log("[bench] inputs generated in %.1f s" % (time.perf_counter() - t0))
+    shards = data + parity
+
+    def step(ev=None):
+        code = gs.gs_make_code(k, m)
+        gs.gs_decode_matrix(code, erased)
+        if ev:
+            ev[0].record()
+        gs.gs_encode(code, data, parity, S)
+        if ev:
+            ev[1].record()
+        gs.gs_reconstruct(code, shards, erased, S)
+        if ev:
+            ev[2].record()
+
+    if args.calibrate_copy:
+        # a plain elementwise copy of known size: reads 8 GiB, writes 8 GiB
+        parity[0].copy_(data[0])
+        torch.cuda.synchronize()
+        log("[bench] calibration copy: %d bytes read, %d bytes written" % (S, S))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    enc_ms = [e[0].elapsed_time(e[1]) for e in evs]
+    rec_ms = [e[1].elapsed_time(e[2]) for e in evs]
+    enc_avg, rec_avg = sum(enc_ms) / len(enc_ms), sum(rec_ms) / len(rec_ms)
+    ms_per_step = wall * 1e3 / args.steps
+    data_bytes_per_step = 2 * k * S  # k*S through encode + k*S of stripe restored by reconstruct
+    value = data_bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    log("[bench] step %.3f ms: encode %.3f ms, reconstruct %.3f ms" % (ms_per_step, enc_avg, rec_avg))
+
+    enc_alg_bytes = (k + m) * S
+    rec_alg_bytes = (k + len(erased)) * S
+    achieved = enc_alg_bytes / (enc_avg * 1e-3) / 1e9
+    out = {
+        "metric": "encode+reconstruct GB/s (data bytes) on 1 MI355X",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "k": k, "m": m, "shard_bytes": S, "kv_dtype": cfg["dtype"],
+                   "erased": erased, "launch": "gs_encode + gs_reconstruct, default launch shape"},
+        "encode_GBps_data": round(k * S / (enc_avg * 1e-3) / 1e9, 1),
+        "reconstruct_GBps_data": round(k * S / (rec_avg * 1e-3) / 1e9, 1),
+        "encode_ms": round(enc_avg, 4),
+        "reconstruct_ms": round(rec_avg, 4),
+        "reconstruct_hbm_frac": round(rec_alg_bytes / (rec_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": {
+            "kernel": "apply_contig_kernel (encode, k=%d m=%d)" % (k, m),
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "algorithmic_bytes_per_launch": enc_alg_bytes,
+            "avg_launch_ms": round(enc_avg, 4),
+        },
+    }
+
+    if not args.no_extras:
+        out.update(extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log))
+
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log):
+    res = {}
+    dev = "cuda:0"
+    code = gs.gs_make_code(k, m)
+
+    # ---- checkpoint latency: chunked encode overlapped with parity D2H into pinned memory
+    chunk_tokens = cfg.get("chunk_tokens")
+    if chunk_tokens:
+        per_tok = inputs.bytes_per_token(cfg["layers"])
+        chunk = chunk_tokens * cfg["batch"] * per_tok // k
+    else:
+        chunk = max(16, (S // 4 + 15) // 16 * 16)
+    t0 = time.perf_counter()
+    host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    log("[bench] pinned %.1f GiB of host memory in %.1f s" % (m * S / 2**30, time.perf_counter() - t0))
+    # plain pinned D2H / H2D rate of one parity shard, same run
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    host[0].copy_(parity[0], non_blocking=True)
+    torch.cuda.synchronize()
+    d2h = S / (time.perf_counter() - t0) / 1e9
+    t0 = time.perf_counter()
+    parity[0].copy_(host[0], non_blocking=True)
+    torch.cuda.synchronize()
+    h2d = S / (time.perf_counter() - t0) / 1e9
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    lat = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gs.gs_checkpoint(pipe, data, S, host)
+        gs.gs_pipe_sync(pipe)
+        lat.append(time.perf_counter() - t0)
+    ck = min(lat)
+    # serial reference: encode everything, then copy everything
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    gs.gs_encode(code, data, parity, S)
+    for i in range(m):
+        host[i].copy_(parity[i], non_blocking=True)
+    torch.cuda.synchronize()
+    serial = time.perf_counter() - t0
+    res["checkpoint"] = {
+        "latency_ms": round(ck * 1e3, 2), "chunk_bytes_per_shard": chunk, "parity_bytes": m * S,
+        "parity_GBps": round(m * S / ck / 1e9, 2),
+        "frac_of_pcie_gen5_x16": round(m * S / ck / 1e9 / PCIE_GEN5_X16_GBPS, 3),
+        "plain_pinned_d2h_GBps": round(d2h, 2), "plain_pinned_h2d_GBps": round(h2d, 2),
+        "frac_of_plain_d2h": round(m * S / ck / 1e9 / d2h, 3),
+        "unpipelined_encode_then_copy_ms": round(serial * 1e3, 2),
+        "data_GBps_pcie_inclusive": round(k * S / ck / 1e9, 1),
+    }
+    log("[bench] checkpoint %.1f ms (parity %.1f GB/s, plain D2H %.1f GB/s, unpipelined %.1f ms)"
+        % (ck * 1e3, m * S / ck / 1e9, d2h, serial * 1e3))
+
+    # ---- restore latency: parity H2D overlapped with reconstruct
+    lat = []
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        gs.gs_restore(pipe, data + [None] * m, host, erased, S)
+        gs.gs_pipe_sync(pipe)
+        lat.append(time.perf_counter() - t0)
+    n_par = len(erased)  # every erased data shard pulls one parity shard back
+    res["restore"] = {"latency_ms": round(min(lat) * 1e3, 2), "erased": erased,
+                      "parity_h2d_GBps": round(n_par * S / min(lat) / 1e9, 2)}
+    log("[bench] restore %.1f ms" % (min(lat) * 1e3))
+    gs.gs_pipe_destroy(pipe)
+
+    # ---- CPU oracle on the same bytes (bounded sample), all host cores
+    import oracle
+    nthreads = min(os.cpu_count() or 1, 16)
+    Ss = min(S, args.cpu_sample_mib << 20)
+    host_data = [d[:Ss].cpu().numpy() for d in data]
+    P = oracle.generator(k, m)
+    t0 = time.perf_counter()
+    want = oracle.encode(P, host_data, nthreads=nthreads)
+    cpu_s = time.perf_counter() - t0
+    gs.gs_encode(code, data, parity, S)
+    torch.cuda.synchronize()
+    same = all(np.array_equal(parity[i][:Ss].cpu().numpy(), want[i]) for i in range(m))
+    res["cpu_baseline"] = {"value": round(k * Ss / cpu_s / 1e9, 3), "unit": "GB/s", "cores": nthreads,
+                           "kind": "oracle",
+                           "sample": "encode of the first %d MiB of each of the %d shards (%.1f GiB of data), %.1f s"
+                                     % (Ss >> 20, k, k * Ss / 2**30, cpu_s),
+                           "gpu_parity_matches_oracle_on_sample": bool(same)}
+    log("[bench] oracle on %d threads: %.3f GB/s; GPU parity equal on sample: %s" % (nthreads, k * Ss / cpu_s / 1e9, same))
+    del host_data, want
+
+    # ---- streaming decode-step checkpoint (paged, k=4, m=1), latency over 1000 steps
+    res["decode_step"] = decode_steps(torch, gs, inputs, log)
+    return res
+
+
+def decode_steps(torch, gs, inputs, log):
+    c = inputs.CONFIGS["decode_paged"]
+    k, m, steps = c["k"], c["m"], c["steps"]
+    n_planes = c["layers"] * 2
+    block_tokens, slot_bytes = c["block_tokens"], 8 * 128 * 2
+    seqs_per_shard = c["batch"] // k
+    n_blocks = c["batch"] * 8  # a few blocks per sequence in the pool
+    pages_per_plane = n_blocks * block_tokens
+    dev = "cuda:0"
+    pool = inputs.kv_bytes_device(inputs.config_seed("decode_paged"), n_planes * pages_per_plane * slot_bytes,
+                                  c["dtype"], c["sigma"], dev)
+    plane_bytes = pages_per_plane * slot_bytes
+    base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(n_planes)], dtype=torch.int64, device=dev)
+    rng = np.random.default_rng(inputs.config_seed("decode_paged") + inputs.TABLE_SEED_OFFSET)
+    blocks = rng.permutation(n_blocks)[: c["batch"]].reshape(k, seqs_per_shard)
+    tables = torch.from_numpy(np.stack([(blocks * block_tokens + (s % block_tokens)).astype(np.int32)
+                                        for s in range(block_tokens)])).to(dev)
+    table = tables[0].clone()
+    out_bytes = n_planes * seqs_per_shard * slot_bytes
+    par = [torch.empty(out_bytes, dtype=torch.uint8, device=dev) for _ in range(m)]
+    host = [torch.empty(out_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    torch.cuda.synchronize()
+
+    def run(fn):
+        lat = []
+        for s in range(steps + 20):
+            table.copy_(tables[s % block_tokens])  # the engine moves every sequence to its next slot
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - t0) * 1e6)
+        lat = lat[20:]
+        return {"p50_us": round(pctl(lat, 0.5), 1), "p99_us": round(pctl(lat, 0.99), 1),
+                "mean_us": round(sum(lat) / len(lat), 1)}
+
+    res = {"new_kv_bytes_per_step": k * out_bytes, "steps": steps}
+    res["eager_encode_only"] = run(lambda: gs.gs_encode_paged(code, base, n_planes, slot_bytes, pages_per_plane,
+                                                              table, seqs_per_shard, par))
+
+    def eager_d2h():
+        gs.gs_encode_paged(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, par)
+        for i in range(m):
+            host[i].copy_(par[i], non_blocking=True)
+    res["eager_encode_d2h"] = run(eager_d2h)
+    g0 = gs.gs_step_graph_create(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, par, None)
+    res["graph_encode_only"] = run(lambda: gs.gs_step_graph_launch(g0))
+    g1 = gs.gs_step_graph_create(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, par, host)
+    res["graph_encode_d2h"] = run(lambda: gs.gs_step_graph_launch(g1))
+    gs.gs_step_graph_destroy(g0)
+    gs.gs_step_graph_destroy(g1)
+    log("[bench] decode step: " + json.dumps(res))
+    return res
+
+
+if __name__ == "__main__":
+    sys.exit(main())
