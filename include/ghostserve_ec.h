@@ -192,12 +192,16 @@ int gs_last_hip_error(void);
  * entry i in byte (i & 3) of its word.  Host only; exposed so that the table
  * construction can be checked without a GPU. */
 int gs_coef_words(int c, uint32_t *words_out);
-/* Launch-shape knobs for benchmarking sweeps; values <= 0 restore the default.
- *   unroll        16-byte vectors per lane per shard per tile (1, 2 or 4)
- *   tiles_per_wg  consecutive tiles one workgroup processes
- *   nontemporal   1 = streaming loads/stores, 0 = default cache policy
+/* Launch-shape knobs for benchmarking sweeps; a value <= 0 (< 0 for the last
+ * two) restores that knob's default.
+ *   unroll            16-byte vectors per lane per shard per tile (1, 2 or 4)
+ *   tiles_per_wg      consecutive tiles one workgroup processes
+ *   nontemporal       1 = streaming loads/stores, 0 = default cache policy
+ *   interleave_shift  log2 of the modulus with which the contiguous kernel
+ *                     deals 1 KiB pieces to workgroups (0 = consecutive
+ *                     pieces, default 5; at most 10)
  * Results are identical for every setting. */
-int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal);
+int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
 
 #ifdef __cplusplus
 }

@@ -82,7 +82,7 @@ def lib():
     L.gs_strerror.restype = ctypes.c_char_p
     L.gs_last_hip_error.argtypes = []
     L.gs_coef_words.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
-    L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     _lib = L
     return L
 
@@ -260,5 +260,6 @@ def gs_coef_words(c):
     return list(w)
 
 
-def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1):
-    _check(lib().gs_set_launch_shape(unroll, tiles_per_wg, nontemporal), "gs_set_launch_shape")
+def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1, interleave_shift=-1):
+    _check(lib().gs_set_launch_shape(unroll, tiles_per_wg, nontemporal, interleave_shift),
+           "gs_set_launch_shape")

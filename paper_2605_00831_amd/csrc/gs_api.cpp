@@ -18,7 +18,7 @@ namespace gs {
 thread_local int g_last_hip_error = 0;
 
 // defaults chosen by measurement on MI355X; see gs_set_launch_shape()
-static LaunchShape g_default_shape = {2, 1, 1};
+static LaunchShape g_default_shape = {2, 1, 1, 5};
 static LaunchShape g_shape = g_default_shape;
 
 LaunchShape current_shape() { return g_shape; }
@@ -236,7 +236,7 @@ int gs_coef_words(int c, uint32_t *words_out)
     return GS_OK;
 }
 
-int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal)
+int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift)
 {
     LaunchShape s = g_default_shape;
     if (unroll > 0) {
@@ -245,6 +245,10 @@ int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal)
     }
     if (tiles_per_wg > 0) s.tiles_per_wg = tiles_per_wg;
     if (nontemporal >= 0) s.nontemporal = nontemporal ? 1 : 0;
+    if (interleave_shift >= 0) {
+        if (interleave_shift > 10) return GS_EINVAL;
+        s.interleave_shift = interleave_shift;
+    }
     g_shape = s;
     return GS_OK;
 }

@@ -37,6 +37,7 @@ struct ApplyArgs {
     int32_t k;            // streams in this launch
     int32_t accumulate;   // XOR into the existing outputs
     uint32_t tiles_per_wg;
+    uint32_t nx_shift;    // log2 of the interleave modulus (0 = plain consecutive tiles)
 };
 
 struct PagedArgs {
@@ -112,15 +113,15 @@ __device__ __forceinline__ void mac(u32x4 (&acc)[M][U], const u32x4 (&x)[U],
 
 constexpr int kBatch = 4;  // streams whose loads are issued together
 
-// One tile of the contiguous kernel.  FULL tiles (every lane in range) carry
-// no predication at all; only the last, ragged tile of a shard takes the
-// predicated form.
+// One tile of the contiguous kernel: each lane handles the U vectors v[0..U).
+// FULL tiles (every lane in range) carry no predication at all; only tiles
+// that reach past the end of the shard take the predicated form.
 template <int M, bool ROW0_XOR, int U, bool NT, bool FULL>
-__device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
+__device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (&v)[U])
 {
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = FULL || v0 + static_cast<uint64_t>(u) * kThreads < a.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || v[u] < a.nvec;
 
     u32x4 acc[M][U];
 #pragma unroll
@@ -132,7 +133,7 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
         for (int r = 0; r < M; ++r)
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) acc[r][u] = load16<NT>(a.out[r], v0 + static_cast<uint64_t>(u) * kThreads);
+                if (ok[u]) acc[r][u] = load16<NT>(a.out[r], v[u]);
     }
 
     int j = 0;
@@ -146,7 +147,7 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 x[b][u] = u32x4{0, 0, 0, 0};
-                if (ok[u]) x[b][u] = load16<NT>(src[b], v0 + static_cast<uint64_t>(u) * kThreads);
+                if (ok[u]) x[b][u] = load16<NT>(src[b], v[u]);
             }
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
@@ -157,7 +158,7 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u] = u32x4{0, 0, 0, 0};
-            if (ok[u]) x[u] = load16<NT>(src, v0 + static_cast<uint64_t>(u) * kThreads);
+            if (ok[u]) x[u] = load16<NT>(src, v[u]);
         }
         mac<M, ROW0_XOR, U>(acc, x, a.tab, j);
     }
@@ -166,21 +167,40 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, uint64_t v0)
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(a.out[r], v0 + static_cast<uint64_t>(u) * kThreads, acc[r][u]);
+            if (ok[u]) store16<NT>(a.out[r], v[u], acc[r][u]);
 }
 
+// Work distribution.  A shard is cut into 1 KiB pieces (one 16-byte vector per
+// lane of a wavefront).  Workgroups are dealt to the 8 XCDs round-robin by
+// index, and HBM throughput is best when a given XCD keeps touching the same
+// 1 KiB residue class of the address space.  So a tile (one workgroup, 4
+// wavefronts x U pieces) is not 4*U consecutive pieces: with interleave
+// modulus NX = 2^nx_shift, tile t = g*NX + r takes the pieces
+//     (g*4U + q)*NX + r,   q = 0..4U-1,
+// i.e. every NX-th piece inside a super-tile of NX*4U pieces, wavefront w
+// taking q = w*U .. w*U+U-1.  All NX tiles of a super-tile together cover it
+// exactly once.  nx_shift = 0 gives plain consecutive tiles.
 template <int M, bool ROW0_XOR, int U, bool NT>
 __global__ __launch_bounds__(kThreads) void apply_contig_kernel(const ApplyArgs a)
 {
     const uint32_t tid = threadIdx.x;
-    constexpr uint64_t kTile = static_cast<uint64_t>(kThreads) * U;
+    const uint32_t wave = tid >> 6, lane = tid & 63u;
+    constexpr uint32_t kPieces = (kThreads / 64) * U;  // pieces per tile
     const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
+    const uint64_t nx_mask = (1ull << a.nx_shift) - 1;
 
     for (uint32_t tt = 0; tt < a.tiles_per_wg; ++tt) {
-        const uint64_t base = (first_tile + tt) * kTile;
-        if (base >= a.nvec) break;
-        if (base + kTile <= a.nvec) contig_tile<M, ROW0_XOR, U, NT, true>(a, base + tid);
-        else contig_tile<M, ROW0_XOR, U, NT, false>(a, base + tid);
+        const uint64_t t = first_tile + tt;
+        const uint64_t g = t >> a.nx_shift, r = t & nx_mask;
+        // first vector of the super-tile; nothing to do once it is past the end
+        const uint64_t super_first = ((g * kPieces) << a.nx_shift) * 64;
+        if (super_first >= a.nvec) break;
+        uint64_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
+        const uint64_t super_end = (((g + 1) * kPieces) << a.nx_shift) * 64;
+        if (super_end <= a.nvec) contig_tile<M, ROW0_XOR, U, NT, true>(a, v);
+        else contig_tile<M, ROW0_XOR, U, NT, false>(a, v);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
@@ -396,11 +416,17 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
     const int unroll = sane_unroll(shape.unroll);
+    // tiles come in super-tiles of NX tiles; round the tile count up to whole super-tiles
+    uint32_t nx_shift = shape.interleave_shift >= 0 && shape.interleave_shift <= 10
+                            ? static_cast<uint32_t>(shape.interleave_shift) : 5u;
     const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
-    const uint64_t tiles = (a.nvec + tile - 1) / tile;
+    while (nx_shift > 0 && (tile << nx_shift) > a.nvec) --nx_shift;  // small shards: no idle tiles
+    const uint64_t super = tile << nx_shift;
+    const uint64_t tiles = ((a.nvec + super - 1) / super) << nx_shift;
     uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
+    a.nx_shift = nx_shift;
     return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), stream);
 }
 

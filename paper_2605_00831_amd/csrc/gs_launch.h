@@ -14,6 +14,7 @@ struct LaunchShape {
     int unroll;        // 16-byte vectors per lane per stream per tile: 1, 2 or 4
     int tiles_per_wg;  // consecutive tiles per workgroup
     int nontemporal;   // streaming cache policy on loads and stores
+    int interleave_shift;  // log2 of the XCD interleave modulus of the contiguous kernel (0 = off)
 };
 
 // One launch: out[r] (r < rows <= 4) = XOR_j coef[r*coef_stride + j] (x) in[j], j < k <= 16,

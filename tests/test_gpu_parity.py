@@ -75,12 +75,14 @@ def test_encode_matches_oracle_over_ragged_sizes(gs, k, m):
             assert np.array_equal(d[j].cpu().numpy(), data[j])  # inputs untouched
 
 
-@pytest.mark.parametrize("unroll,tiles_per_wg,nt", [(1, 1, 1), (2, 1, 0), (4, 1, 1), (1, 3, 0), (2, 5, 1), (4, 2, 0),
-                                                   (2, 64, 1)])
-def test_every_launch_shape_gives_the_same_bytes(gs, unroll, tiles_per_wg, nt):
-    gs.gs_set_launch_shape(unroll, tiles_per_wg, nt)
+@pytest.mark.parametrize("unroll,tiles_per_wg,nt,ilv", [
+    (1, 1, 1, 5), (2, 1, 0, 5), (4, 1, 1, 5), (1, 3, 0, 3), (2, 5, 1, 0), (4, 2, 0, 1), (2, 64, 1, 5), (2, 1, 1, 10),
+    (1, 7, 1, 6), (2, 1, 1, 0)])
+def test_every_launch_shape_gives_the_same_bytes(gs, unroll, tiles_per_wg, nt, ilv):
+    gs.gs_set_launch_shape(unroll, tiles_per_wg, nt, ilv)
     try:
-        for (k, m), S in itertools.product([(4, 2), (8, 3), (6, 1)], [16 * 256 * 11 + 48 + 7, 777]):
+        sizes = [16 * 256 * 11 + 48 + 7, 777, (1 << 20) + 16 * 64 * 3 + 9, 256 * 1024, 256 * 1024 - 16]
+        for (k, m), S in itertools.product([(4, 2), (8, 3), (6, 1)], sizes):
             code = gs.gs_make_code(k, m)
             data = rand_shards(S + k + unroll, k, S)
             want = oracle.encode(oracle.generator(k, m), data, nthreads=8)

@@ -131,6 +131,7 @@ def test_entry_points_validate_before_touching_the_gpu():
     out = vp()
     assert L.gs_pipe_create(code.handle, 100, 2, ctypes.byref(out)) == gs.GS_EINVAL   # not a multiple of 16
     assert L.gs_pipe_create(code.handle, 1024, 1, ctypes.byref(out)) == gs.GS_EINVAL  # depth < 2
-    assert L.gs_set_launch_shape(3, 1, 1) == gs.GS_EINVAL
-    assert L.gs_set_launch_shape(0, 0, -1) == gs.GS_OK
+    assert L.gs_set_launch_shape(3, 1, 1, -1) == gs.GS_EINVAL
+    assert L.gs_set_launch_shape(2, 1, 1, 11) == gs.GS_EINVAL
+    assert L.gs_set_launch_shape(0, 0, -1, -1) == gs.GS_OK
     assert L.gs_strerror(gs.GS_ETOOMANY).decode() == "more erasures than parity shards"
