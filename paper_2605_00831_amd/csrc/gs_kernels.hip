@@ -89,9 +89,20 @@ __device__ __forceinline__ uint32_t mul1(const uint32_t *t, uint32_t x)
                                  (t[4] >> (8 * (x >> 6)))) & 0xFFu;
 }
 
+// The accumulators are plain dwords.  pin() is an empty asm that makes the
+// compiler materialise the value at that point: without it the XOR chains of
+// all streams are reassociated into one wide tree whose leaves (every lookup
+// result of a tile) are alive at once, which costs hundreds of registers.
+__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+v"(v)); }
+
+struct Acc4 { uint32_t c[4]; };
+
+__device__ __forceinline__ u32x4 to_vec(const Acc4 &a) { return u32x4{a.c[0], a.c[1], a.c[2], a.c[3]}; }
+__device__ __forceinline__ Acc4 from_vec(u32x4 v) { return Acc4{{v[0], v[1], v[2], v[3]}}; }
+
 // acc[r][u] ^= C[r][j] (x) x[u] for all rows
 template <int M, bool ROW0_XOR, int U>
-__device__ __forceinline__ void mac(u32x4 (&acc)[M][U], const u32x4 (&x)[U],
+__device__ __forceinline__ void mac(Acc4 (&acc)[M][U], const u32x4 (&x)[U],
                                     const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8], int j)
 {
 #pragma unroll
@@ -99,13 +110,19 @@ __device__ __forceinline__ void mac(u32x4 (&acc)[M][U], const u32x4 (&x)[U],
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint32_t d = x[u][c];
-            if (ROW0_XOR) acc[0][u][c] ^= d;
+            if (ROW0_XOR) {
+                acc[0][u].c[c] ^= d;
+                pin(acc[0][u].c[c]);
+            }
             if (M > (ROW0_XOR ? 1 : 0)) {
                 const uint32_t s0 = d & 0x07070707u;
                 const uint32_t s1 = (d >> 3) & 0x07070707u;
                 const uint32_t s2 = (d >> 6) & 0x03030303u;
 #pragma unroll
-                for (int r = (ROW0_XOR ? 1 : 0); r < M; ++r) acc[r][u][c] ^= mul4(tab[r][j], s0, s1, s2);
+                for (int r = (ROW0_XOR ? 1 : 0); r < M; ++r) {
+                    acc[r][u].c[c] ^= mul4(tab[r][j], s0, s1, s2);
+                    pin(acc[r][u].c[c]);
+                }
             }
         }
     }
@@ -123,17 +140,17 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (
 #pragma unroll
     for (int u = 0; u < U; ++u) ok[u] = FULL || v[u] < a.nvec;
 
-    u32x4 acc[M][U];
+    Acc4 acc[M][U];
 #pragma unroll
     for (int r = 0; r < M; ++r)
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc[r][u] = u32x4{0, 0, 0, 0};
+        for (int u = 0; u < U; ++u) acc[r][u] = Acc4{{0, 0, 0, 0}};
     if (a.accumulate) {
 #pragma unroll
         for (int r = 0; r < M; ++r)
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) acc[r][u] = load16<NT>(a.out[r], v[u]);
+                if (ok[u]) acc[r][u] = from_vec(load16<NT>(a.out[r], v[u]));
     }
 
     int j = 0;
@@ -167,7 +184,16 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(a.out[r], v[u], acc[r][u]);
+            if (ok[u]) store16<NT>(a.out[r], v[u], to_vec(acc[r][u]));
+}
+
+// Occupancy the register allocator is asked to reach (wavefronts per SIMD).
+// The path is bandwidth-bound: many resident wavefronts with a few loads each
+// beat few wavefronts with long dependency-free instruction runs.
+template <int M, bool ROW0_XOR, int U>
+constexpr int kWavesPerEu()
+{
+    return U == 1 ? 8 : 4;  // 64 resp. 128 VGPRs; every variant fits without spilling
 }
 
 // Work distribution.  A shard is cut into 1 KiB pieces (one 16-byte vector per
@@ -181,7 +207,8 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (
 // taking q = w*U .. w*U+U-1.  All NX tiles of a super-tile together cover it
 // exactly once.  nx_shift = 0 gives plain consecutive tiles.
 template <int M, bool ROW0_XOR, int U, bool NT>
-__global__ __launch_bounds__(kThreads) void apply_contig_kernel(const ApplyArgs a)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
+void apply_contig_kernel(const ApplyArgs a)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6, lane = tid & 63u;
@@ -238,16 +265,16 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
         off[u] = v[u] - slot[u] * a.vpp;
     }
 
-    u32x4 acc[M][U];
+    Acc4 acc[M][U];
 #pragma unroll
     for (int r = 0; r < M; ++r)
 #pragma unroll
-        for (int u = 0; u < U; ++u) acc[r][u] = u32x4{0, 0, 0, 0};
+        for (int u = 0; u < U; ++u) acc[r][u] = Acc4{{0, 0, 0, 0}};
     if (a.accumulate) {
 #pragma unroll
         for (int r = 0; r < M; ++r)
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[r][u] = load16<NT>(a.out[r], out_base + v[u]);
+            for (int u = 0; u < U; ++u) acc[r][u] = from_vec(load16<NT>(a.out[r], out_base + v[u]));
     }
 
     auto gather = [&](int row, int u) -> u32x4 {
@@ -279,7 +306,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(a.out[r], out_base + v[u], acc[r][u]);
+            if (ok[u]) store16<NT>(a.out[r], out_base + v[u], to_vec(acc[r][u]));
 }
 
 // Paged gather: blockIdx.y is the plane; blockIdx.x walks the plane's
@@ -358,7 +385,9 @@ static hipError_t dispatch(int rows, bool row0_xor, int unroll, bool nt, const A
         return Launcher<M_, X_, U_, false>::go(a, grid, stream);           \
     }
 #define GS_CASE_MX(M_, X_)  \
-    if (rows == M_ && row0_xor == X_) { GS_CASE_U(M_, X_, 1) GS_CASE_U(M_, X_, 2) GS_CASE_U(M_, X_, 4) }
+    if (rows == M_ && row0_xor == X_) { GS_CASE_U(M_, X_, 1) GS_CASE_U(M_, X_, 2) }
+    if (rows == 1 && row0_xor == false) { GS_CASE_U(1, false, 4) }
+    if (rows == 1 && row0_xor == true) { GS_CASE_U(1, true, 4) }
     GS_CASE_MX(1, false) GS_CASE_MX(1, true)
     GS_CASE_MX(2, false) GS_CASE_MX(2, true)
     GS_CASE_MX(3, false) GS_CASE_MX(3, true)
@@ -386,7 +415,12 @@ struct PagedLauncher {
     }
 };
 
-static int sane_unroll(int u) { return (u == 1 || u == 2 || u == 4) ? u : 2; }
+// 4 vectors per lane exist only for the single-row kernels; wider ones would spill
+static int sane_unroll(int u, int rows)
+{
+    if (u == 4 && rows > 1) return 2;
+    return (u == 1 || u == 2 || u == 4) ? u : 2;
+}
 
 // workgroups along x, and tiles per workgroup raised if needed so that the
 // grid stays below the launch limit on total threads per dimension
@@ -415,7 +449,7 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.tail = static_cast<uint32_t>(bytes % 16);
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
-    const int unroll = sane_unroll(shape.unroll);
+    const int unroll = sane_unroll(shape.unroll, rows);
     // tiles come in super-tiles of NX tiles; round the tile count up to whole super-tiles
     uint32_t nx_shift = shape.interleave_shift >= 0 && shape.interleave_shift <= 10
                             ? static_cast<uint32_t>(shape.interleave_shift) : 5u;
@@ -459,7 +493,7 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     a.pps = static_cast<uint32_t>(pages_per_shard);
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
-    const int unroll = sane_unroll(shape.unroll);
+    const int unroll = sane_unroll(shape.unroll, rows);
     const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
     const uint64_t tiles = (vecs + tile - 1) / tile;
     uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
