@@ -1,0 +1,192 @@
+"""GPU parity at the full sizes of the measured workloads, in the launch
+configuration bench.py times (default launch shape, one launch per call).
+
+The oracle cannot encode 32-40 GiB in seconds, so these tests check
+  - sampled windows (shard starts and ends, both sides of the 4 GiB offset,
+    seeded random offsets with odd lengths) byte for byte against the oracle
+    on the same bytes copied to the host;
+  - the XOR-fold invariant over the WHOLE buffers: folding a shard to a 4 KiB
+    block by XOR commutes with the code, so oracle.encode(folds of data) must
+    equal the folds of the GPU parity (folds computed with torch ops, which
+    share nothing with the kernels);
+  - reconstruct at full size: rebuilt shards equal the originals bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+FOLD = 4096
+
+
+@pytest.fixture(scope="module")
+def gs():
+    from paper_2605_00831_amd import binding
+    binding.lib()
+    binding.gs_set_launch_shape()
+    return binding
+
+
+def xor_fold(t):
+    """XOR of all FOLD-byte blocks of a uint8 device tensor (length a multiple
+    of FOLD and a power-of-two number of blocks times an odd factor)."""
+    x = t.view(torch.int64).reshape(-1, FOLD // 8)
+    while x.shape[0] > 1:
+        n = x.shape[0]
+        if n % 2:
+            x = torch.cat([x[:1] ^ x[n - 1:], x[1:n - 1]])
+            n -= 1
+        x = x[: n // 2] ^ x[n // 2:]
+    return x.reshape(-1).view(torch.uint8).cpu().numpy()
+
+
+def windows(S, seed, count=6):
+    """(offset, length) pairs inside [0, S)"""
+    rng = np.random.default_rng(seed)
+    w = [(0, 65536 + 7), (S - 65536 - 3, 65536 + 3)]
+    if S > (1 << 32):
+        w += [((1 << 32) - 4099, 8200), ((1 << 32), 4096 + 5)]
+    if S > (1 << 31):
+        w += [((1 << 31) - 33, 70)]
+    for _ in range(count):
+        n = int(rng.integers(1, 200000))
+        w.append((int(rng.integers(0, S - n)), n))
+    return w
+
+
+def check_windows(P, data, parity, S, seed):
+    k, m = P.shape[1], P.shape[0]
+    for off, n in windows(S, seed):
+        host = [np.ascontiguousarray(d[off:off + n].cpu().numpy()) for d in data]
+        want = oracle.encode(P, host, nthreads=8)
+        for i in range(m):
+            got = parity[i][off:off + n].cpu().numpy()
+            assert np.array_equal(got, want[i]), "parity %d differs in window at %d (+%d)" % (i, off, n)
+
+
+def check_folds(P, data, parity):
+    folds = [np.ascontiguousarray(xor_fold(d)) for d in data]
+    want = oracle.encode(P, folds)
+    for i in range(P.shape[0]):
+        assert np.array_equal(xor_fold(parity[i]), want[i]), "fold of parity %d differs" % i
+
+
+def run_bulk(gs, name):
+    cfg = inputs.CONFIGS[name]
+    k, m = cfg["k"], cfg["m"]
+    total = inputs.config_total_bytes(name)
+    S = total // k
+    free, _ = torch.cuda.mem_get_info()
+    need = total + m * S + 2 * S + (4 << 30)
+    if free < need:
+        pytest.skip("needs %.0f GiB of free device memory" % (need / 2**30))
+    buf = inputs.kv_bytes_device(inputs.config_seed(name), total, cfg["dtype"], cfg["sigma"], "cuda")
+    data = [buf[j * S:(j + 1) * S] for j in range(k)]
+    parity = [torch.full((S,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    assert np.array_equal(gs.gs_code_matrix(code), P)
+    gs.gs_encode(code, data, parity, S)
+    torch.cuda.synchronize()
+    check_windows(P, data, parity, S, inputs.config_seed(name))
+    check_folds(P, data, parity)
+    # lose two data shards (failure = flushed buffers), rebuild in place, compare
+    lost = [1, k - 1]
+    keep = [data[r].clone() for r in lost]
+    for r in lost:
+        data[r].fill_(0xA5)
+    gs.gs_reconstruct(code, data + parity, lost, S)
+    torch.cuda.synchronize()
+    for r, orig in zip(lost, keep):
+        assert torch.equal(data[r], orig), "shard %d not rebuilt bit for bit" % r
+    del keep
+    # lose a data shard and a parity shard
+    lost = [0, k + 1]
+    keep = [data[0].clone(), parity[1].clone()]
+    data[0].fill_(0xA5)
+    parity[1].fill_(0xA5)
+    gs.gs_reconstruct(code, data + parity, lost, S)
+    torch.cuda.synchronize()
+    assert torch.equal(data[0], keep[0]) and torch.equal(parity[1], keep[1])
+
+
+def test_llama8b_prefill_full_size(gs):
+    """32 GiB bf16 N(0, 0.5), k=4 shards of 8 GiB (offsets beyond 2^32), m=2."""
+    run_bulk(gs, "llama8b_prefill")
+
+
+def test_llama70b_longctx_full_size(gs):
+    """40 GiB bf16 N(0, 1), k=8 shards of 5 GiB, m=2."""
+    run_bulk(gs, "llama70b_longctx")
+
+
+def test_recovery_stress_full_size_20_seeded_patterns(gs):
+    """k=8, m=3, S=512 MiB: shards 0-3 uniform bytes, shards 4-7 bf16 KV held
+    in 32 KiB pages (16-token blocks) behind a permutation table and gathered
+    to contiguous survivors; parity lives in pinned host memory and comes back
+    H2D through the restore pipeline; 20 seeded erasure triples."""
+    c = inputs.CONFIGS["recovery_stress"]
+    k, m, S = c["k"], c["m"], c["shard_bytes"]
+    seed = inputs.config_seed("recovery_stress")
+    page = 32768
+    pages = S // page
+    data = [inputs.uniform_bytes_device(seed + j, S, "cuda") for j in range(4)]
+    pool = inputs.kv_bytes_device(seed + 7, 4 * S, "bf16", 1.0, "cuda").view(4 * pages, page)
+    table = torch.from_numpy(inputs.block_table_np(seed, 4, pages, 4 * pages)).cuda()
+    data += [pool[table[j].long()].reshape(-1).contiguous() for j in range(4)]
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    parity = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    gs.gs_encode(code, data, parity, S)
+    torch.cuda.synchronize()
+    check_windows(P, data, parity, S, seed)
+    check_folds(P, data, parity)
+    # the same parity through the paged entry: shards 4-7 straight from the pool
+    # (k=4 sub-code check: paged encode of the KV shards equals contiguous encode of their gathers)
+    code4 = gs.gs_make_code(4, 2)
+    base = torch.tensor([pool.data_ptr()], dtype=torch.int64, device="cuda")
+    pp = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    pc = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    gs.gs_encode_paged(code4, base, 1, page, 4 * pages, table, pages, pp)
+    gs.gs_encode(code4, data[4:], pc, S)
+    torch.cuda.synchronize()
+    assert torch.equal(pp[0], pc[0]) and torch.equal(pp[1], pc[1])
+    check_windows(oracle.generator(4, 2), data[4:], pp, S, seed + 1)
+    del pp, pc
+    # parity goes to pinned host memory; device copies are dropped
+    host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    for i in range(m):
+        host[i].copy_(parity[i])
+    torch.cuda.synchronize()
+    full = data + parity
+    pipe = gs.gs_pipe_create(code, 64 << 20, 2)
+    pats = inputs.random_erasure_patterns(seed, k + m, 3, c["patterns_full"])
+    assert len(pats) == 20
+    for pat in pats:
+        work = []
+        for r in range(k + m):
+            if r in pat:
+                work.append(torch.full((S,), 0xA5, dtype=torch.uint8, device="cuda"))
+            elif r < k:
+                work.append(full[r])
+            else:
+                work.append(None)          # surviving parity is only in host memory
+        gs.gs_restore(pipe, work, host, list(pat), S)
+        gs.gs_pipe_sync(pipe)
+        torch.cuda.synchronize()
+        for r in pat:
+            assert torch.equal(work[r], full[r]), (pat, r)
+        del work
+    # one pattern also through the plain entry with parity resident
+    pat = pats[0]
+    work = [torch.full((S,), 0xA5, dtype=torch.uint8, device="cuda") if r in pat else full[r] for r in range(k + m)]
+    gs.gs_reconstruct(code, work, list(pat), S)
+    torch.cuda.synchronize()
+    for r in pat:
+        assert torch.equal(work[r], full[r])
+    gs.gs_pipe_destroy(pipe)
