@@ -30,7 +30,7 @@ PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 # WRITE_SIZE, scaled by a plain copy kernel of known size; see
 # profiles/encode_contig_llama8b_prefill.md.  Bytes per launch, or None.
 MEASURED_TRAFFIC_BYTES = {
-    "llama8b_prefill": (33554573 + 16777248) * 1024,   # fetch (scaled x2.0000) + write, KiB -> bytes
+    "llama8b_prefill": 51539161269,   # FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000, KiB -> bytes
 }
 
 
