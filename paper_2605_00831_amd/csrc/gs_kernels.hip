@@ -53,6 +53,7 @@ struct PagedArgs {
     int32_t k;
     int32_t accumulate;
     uint32_t tiles_per_wg;
+    uint32_t nx_shift;         // log2 of the piece interleave modulus
 };
 
 template <bool NT>
@@ -250,18 +251,31 @@ void apply_contig_kernel(const ApplyArgs a)
 // the plane, or whose page id is outside the plane, reads vector 0 / page 0
 // instead (always a valid address) and its value is replaced by zero, so the
 // loads need no branches.
-template <int M, bool ROW0_XOR, int U, bool NT>
+//
+// WAVE_PAGE: the page size is a multiple of 1 KiB, so the 64 lanes of a piece
+// share one page.  The slot is then wavefront-uniform and the table entry is
+// fetched with a scalar load through the constant address space (the table is
+// never written while the kernel runs), which takes the per-lane divide and
+// the vector table loads off the critical path.
+typedef const int32_t __attribute__((address_space(4))) *ConstTable;
+
+template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE>
 __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint64_t out_base,
-                                           uint64_t first_vec)
+                                           const uint64_t (&vv)[U])
 {
     bool ok[U];
     uint32_t v[U], slot[U], off[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t vv = first_vec + static_cast<uint64_t>(u) * kThreads;
-        ok[u] = vv < a.vecs_per_plane;
-        v[u] = ok[u] ? static_cast<uint32_t>(vv) : 0u;
-        slot[u] = a.vpp_shift >= 0 ? (v[u] >> a.vpp_shift) : (v[u] / a.vpp);
+        ok[u] = vv[u] < a.vecs_per_plane;
+        v[u] = ok[u] ? static_cast<uint32_t>(vv[u]) : 0u;
+        if (WAVE_PAGE) {
+            // vecs_per_plane is a multiple of 64 here, so ok[u] and the slot are uniform
+            const uint32_t first = __builtin_amdgcn_readfirstlane(v[u]);
+            slot[u] = a.vpp_shift >= 0 ? (first >> a.vpp_shift) : (first / a.vpp);
+        } else {
+            slot[u] = a.vpp_shift >= 0 ? (v[u] >> a.vpp_shift) : (v[u] / a.vpp);
+        }
         off[u] = v[u] - slot[u] * a.vpp;
     }
 
@@ -278,7 +292,8 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     }
 
     auto gather = [&](int row, int u) -> u32x4 {
-        const int64_t page = a.table[static_cast<uint64_t>(row) * a.pps + slot[u]];
+        const uint64_t entry = static_cast<uint64_t>(row) * a.pps + slot[u];
+        const int64_t page = WAVE_PAGE ? ((ConstTable)a.table)[entry] : a.table[entry];
         const bool valid = ok[u] && static_cast<uint64_t>(page) < a.pages_per_plane;
         const uint64_t src = valid ? static_cast<uint64_t>(page) * a.vpp + off[u] : 0ull;
         const u32x4 x = load16<NT>(pbase, src);
@@ -310,21 +325,30 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
 }
 
 // Paged gather: blockIdx.y is the plane; blockIdx.x walks the plane's
-// pages_per_shard * vpp vectors.  Each lane finds its page slot, looks the
-// page id up in every shard's table row, and reads from that page.
-template <int M, bool ROW0_XOR, int U, bool NT>
-__global__ __launch_bounds__(kThreads) void apply_paged_kernel(const PagedArgs a)
+// pages_per_shard * vpp vectors in the same interleaved 1 KiB pieces as the
+// contiguous kernel (gridDim.x is a multiple of the interleave modulus, so the
+// piece residue still names the XCD).  Each lane finds its page slot, looks
+// the page id up in every shard's table row, and reads from that page.
+template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
+void apply_paged_kernel(const PagedArgs a)
 {
-    constexpr uint64_t kTile = static_cast<uint64_t>(kThreads) * U;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    constexpr uint32_t kPieces = (kThreads / 64) * U;
     const uint32_t plane = blockIdx.y;
     const uint8_t *pbase = a.plane_base[plane];
     const uint64_t out_base = static_cast<uint64_t>(plane) * a.vecs_per_plane;
     const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
+    const uint64_t nx_mask = (1ull << a.nx_shift) - 1;
 
     for (uint32_t tt = 0; tt < a.tiles_per_wg; ++tt) {
-        const uint64_t base = (first_tile + tt) * kTile;
-        if (base >= a.vecs_per_plane) break;
-        paged_tile<M, ROW0_XOR, U, NT>(a, pbase, out_base, base + threadIdx.x);
+        const uint64_t t = first_tile + tt;
+        const uint64_t g = t >> a.nx_shift, r = t & nx_mask;
+        if (((g * kPieces) << a.nx_shift) * 64 >= a.vecs_per_plane) break;
+        uint64_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
+        paged_tile<M, ROW0_XOR, U, NT, WAVE_PAGE>(a, pbase, out_base, v);
     }
 }
 
@@ -410,7 +434,10 @@ template <int M, bool X, int U, bool NT>
 struct PagedLauncher {
     static hipError_t go(const PagedArgs &a, dim3 grid, hipStream_t stream)
     {
-        hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        if (a.vpp % 64 == 0)
+            hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT, true>), grid, dim3(kThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT, false>), grid, dim3(kThreads), 0, stream, a);
         return hipGetLastError();
     }
 };
@@ -436,6 +463,17 @@ static void grid_for(uint64_t tiles, uint32_t &tiles_per_wg, uint32_t &wgs)
     wgs = static_cast<uint32_t>(n ? n : 1);
 }
 
+// Interleave modulus (shrunk for short streams so that no tile is idle) and the
+// tile count rounded up to whole super-tiles.
+static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t &nx_shift, uint64_t &tiles)
+{
+    nx_shift = wanted_shift >= 0 && wanted_shift <= 10 ? static_cast<uint32_t>(wanted_shift) : 5u;
+    const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
+    while (nx_shift > 0 && (tile << nx_shift) > nvec) --nx_shift;
+    const uint64_t super = tile << nx_shift;
+    tiles = ((nvec + super - 1) / super) << nx_shift;
+}
+
 hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
                         const void *const *in, void *const *out, size_t bytes,
                         bool accumulate, const LaunchShape &shape, hipStream_t stream)
@@ -450,13 +488,9 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
     const int unroll = sane_unroll(shape.unroll, rows);
-    // tiles come in super-tiles of NX tiles; round the tile count up to whole super-tiles
-    uint32_t nx_shift = shape.interleave_shift >= 0 && shape.interleave_shift <= 10
-                            ? static_cast<uint32_t>(shape.interleave_shift) : 5u;
-    const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
-    while (nx_shift > 0 && (tile << nx_shift) > a.nvec) --nx_shift;  // small shards: no idle tiles
-    const uint64_t super = tile << nx_shift;
-    const uint64_t tiles = ((a.nvec + super - 1) / super) << nx_shift;
+    uint32_t nx_shift;
+    uint64_t tiles;
+    interleave_for(a.nvec, unroll, shape.interleave_shift, nx_shift, tiles);
     uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
@@ -494,11 +528,14 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
     const int unroll = sane_unroll(shape.unroll, rows);
-    const uint64_t tile = static_cast<uint64_t>(kThreads) * unroll;
-    const uint64_t tiles = (vecs + tile - 1) / tile;
-    uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
+    uint32_t nx_shift;
+    uint64_t tiles;
+    interleave_for(vecs, unroll, shape.interleave_shift, nx_shift, tiles);
+    // one tile per workgroup keeps gridDim.x a multiple of the modulus
+    uint32_t tpw = 1, wgs = 1;
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
+    a.nx_shift = nx_shift;
     return dispatch<PagedLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a,
                                    dim3(wgs, static_cast<uint32_t>(n_planes)), stream);
 }
