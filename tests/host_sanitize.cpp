@@ -1,0 +1,65 @@
+// Host-only exercise of the library's field / matrix code under
+// AddressSanitizer + UndefinedBehaviorSanitizer (built and run by
+// tests/test_host_sanitize.py with g++; no HIP involved).
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "../paper_2605_00831_amd/csrc/gs_gf.cpp"
+
+using namespace gs;
+
+static int fail(const char *what, int a, int b)
+{
+    std::printf("FAIL %s (%d, %d)\n", what, a, b);
+    return 1;
+}
+
+int main()
+{
+    // field: inverse and distributivity on every element
+    for (int a = 1; a < 256; ++a)
+        if (gf_mul(static_cast<uint8_t>(a), gf_inv(static_cast<uint8_t>(a))) != 1) return fail("inverse", a, 0);
+    for (int a = 0; a < 256; ++a)
+        for (int b = 0; b < 256; ++b)
+            if (gf_mul(a, b) != gf_mul(b, a) || gf_mul(a, b ^ 0x5A) != (gf_mul(a, b) ^ gf_mul(a, 0x5A)))
+                return fail("axioms", a, b);
+    // both generator routes agree, are normalised, and every k x k mix of identity
+    // and parity rows taken below is invertible with A * inverse(A) = I
+    for (int k = 1; k <= 40; k += 3)
+        for (int m = 1; m <= 7; ++m) {
+            Matrix c = cauchy_parity_block(k, m), v = vandermonde_parity_block(k, m);
+            if (c != v) return fail("routes differ", k, m);
+            for (int j = 0; j < k; ++j) if (c[j] != 1) return fail("row 0", k, m);
+            for (int i = 0; i < m; ++i) if (c[i * k] != 1) return fail("col 0", k, m);
+            const int use = m < k ? m : k;  // replace the first `use` identity rows by parity rows
+            Matrix A(static_cast<size_t>(k) * k, 0);
+            for (int r = 0; r < k; ++r) {
+                if (r < use) for (int col = 0; col < k; ++col) A[r * k + col] = c[r * k + col];
+                else A[r * k + r] = 1;
+            }
+            Matrix Ai = A;
+            if (!invert_in_place(k, Ai)) return fail("singular", k, m);
+            for (int r = 0; r < k; ++r)
+                for (int col = 0; col < k; ++col) {
+                    uint8_t s = 0;
+                    for (int t = 0; t < k; ++t) s ^= gf_mul(A[r * k + t], Ai[t * k + col]);
+                    if (s != (r == col)) return fail("A*Ainv", k, m);
+                }
+        }
+    // extremes of the parameter range
+    if (cauchy_parity_block(255, 1).size() != 255 || cauchy_parity_block(1, 255).size() != 255) return fail("extremes", 0, 0);
+    Matrix sing = {1, 2, 1, 2};
+    if (invert_in_place(2, sing)) return fail("singular not detected", 0, 0);
+    // lookup words reproduce the product for every constant and byte
+    for (int c = 0; c < 256; ++c) {
+        const CoefWords w = split_tables(static_cast<uint8_t>(c));
+        for (int x = 0; x < 256; ++x) {
+            auto byte = [&](int word, int idx) { return (w.w[word + (idx >> 2)] >> (8 * (idx & 3))) & 0xFFu; };
+            const unsigned got = byte(0, x & 7) ^ byte(2, (x >> 3) & 7) ^ byte(4, x >> 6);
+            if (got != gf_mul(static_cast<uint8_t>(c), static_cast<uint8_t>(x))) return fail("split tables", c, x);
+        }
+    }
+    std::printf("OK\n");
+    return 0;
+}

@@ -327,3 +327,64 @@ def test_paged_identity_table_equals_contiguous_encode(gs):
     torch.cuda.synchronize()
     for i in range(m):
         assert torch.equal(par_p[i], par_c[i])
+
+
+# ---------------------------------------------------------------- extremes
+
+def test_widest_code_the_field_allows(gs):
+    """k + m = 256 is the limit (distinct evaluation points in GF(2^8))."""
+    for k, m in [(250, 6), (1, 255), (128, 128)]:
+        S = 1111 if k * m > 4000 else 4099
+        code = gs.gs_make_code(k, m)
+        data = rand_shards(k + m, k, S)
+        want = oracle.encode(oracle.generator(k, m), data, nthreads=8)
+        _, p = gpu_encode(gs, code, data, S)
+        for i in range(m):
+            check_out(p[i], want[i])
+    # lose the maximum number of shards of the (250, 6) code
+    k, m, S = 250, 6, 515
+    P, full = _stripe_on_gpu(gs, k, m, S, 99)
+    code = gs.gs_make_code(k, m)
+    _reconstruct_and_check(gs, code, P, full, (0, 17, 100, 249, 250, 255), S)
+
+
+def test_empty_inputs_are_no_ops_on_the_gpu(gs):
+    code = gs.gs_make_code(4, 2)
+    d = [torch.zeros(16, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    p = [out_buf(0) for _ in range(2)]
+    gs.gs_encode(code, d, p, 0)
+    gs.gs_reconstruct(code, d + p, [1], 0)
+    gs.gs_reconstruct(code, d + p, [], 16)
+    base = torch.tensor([d[0].data_ptr()], dtype=torch.int64, device="cuda")
+    table = torch.zeros((4, 1), dtype=torch.int32, device="cuda")
+    gs.gs_encode_paged(code, base, 0, 16, 1, table, 1, p)
+    gs.gs_encode_paged(code, base, 1, 16, 1, table, 0, p)
+    torch.cuda.synchronize()
+    for b in p:
+        assert (b.cpu().numpy() == CANARY).all()
+
+
+def test_misaligned_or_null_pointers_are_rejected(gs):
+    code = gs.gs_make_code(4, 2)
+    big = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    good = [big[i * 256:(i + 1) * 256] for i in range(4)]
+    par = [out_buf(256) for _ in range(2)]
+    bad = list(good)
+    bad[2] = big[1001:1257]
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_encode(code, bad, par, 256)
+    assert e.value.status == gs.GS_EINVAL
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_encode(code, good, [par[0], None], 256)
+    assert e.value.status == gs.GS_EINVAL
+    # a survivor that the decode needs must be present
+    shards = good + [p[:256] for p in par]
+    gs.gs_encode(code, good, par, 256)
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_reconstruct(code, [good[0], None, good[2], good[3], par[0], par[1]], [0], 256)
+    assert e.value.status == gs.GS_EINVAL
+    # ... but a survivor beyond the first k may be missing
+    gs.gs_reconstruct(code, [good[0], good[1], good[2], good[3], par[0], None], [0], 256)
+    torch.cuda.synchronize()
+    for b in par:
+        assert (b.cpu().numpy()[256:] == CANARY).all()
