@@ -44,6 +44,8 @@ extern "C" {
 typedef struct gs_code gs_code;
 typedef struct gs_pipe gs_pipe;
 typedef struct gs_step_graph gs_step_graph;
+typedef struct gs_batch gs_batch;
+typedef struct gs_pool gs_pool;
 
 enum gs_status {
     GS_OK = 0,
@@ -180,6 +182,42 @@ int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int
                          gs_step_graph **out);
 int gs_step_graph_launch(gs_step_graph *g, void *stream);
 void gs_step_graph_destroy(gs_step_graph *g);
+
+/* ---- many chunks at once ---------------------------------------------------
+ * Section 5: recovery reconstructs many chunks concurrently ("each chunk is
+ * assigned to a dedicated stream"), and with continuous batching every request
+ * encodes its own chunk.  Small chunks do not fill 256 CUs one launch at a
+ * time, so two forms are offered.
+ *
+ * Grouped launch (gs_batch): all chunks go through ONE kernel launch; their
+ * pointers and lengths travel in a descriptor array that the gs_batch owns
+ * (device buffer + pinned host mirror, a ring of 4 slots so that consecutive
+ * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only,
+ * max_chunks <= 65535.  One gs_batch serves one thread at a time.
+ *   data     HOST array of n_chunks*k DEVICE pointers, chunk-major
+ *   parity   HOST array of n_chunks*m DEVICE pointers, chunk-major
+ *   shards   HOST array of n_chunks*(k+m) DEVICE pointers, chunk-major, same
+ *            meaning per chunk as in gs_reconstruct; one erasure pattern for
+ *            all chunks (a failed device loses the same shard of every chunk)
+ *   shard_bytes  HOST array of n_chunks lengths (any values, 0 = skip)
+ * Results per chunk are exactly those of gs_encode / gs_reconstruct. */
+int gs_batch_create(const gs_code *code, int max_chunks, gs_batch **out);
+void gs_batch_destroy(gs_batch *batch);
+int gs_encode_batch(gs_batch *batch, int n_chunks, const void *const *data, void *const *parity,
+                    const size_t *shard_bytes, void *stream);
+int gs_reconstruct_batch(gs_batch *batch, int n_chunks, void *const *shards, const int *erased,
+                         int n_erased, const size_t *shard_bytes, void *stream);
+
+/* Stream pool (gs_pool): the paper's form.  Chunk c is enqueued on pool
+ * stream c mod n_streams (default priority); the pool streams start after the
+ * work already enqueued on `stream`, and `stream` continues only after every
+ * chunk has finished.  1 <= n_streams <= 64.  Same array layouts as above. */
+int gs_pool_create(int n_streams, gs_pool **out);
+void gs_pool_destroy(gs_pool *pool);
+int gs_encode_streams(const gs_code *code, gs_pool *pool, int n_chunks, const void *const *data,
+                      void *const *parity, const size_t *shard_bytes, void *stream);
+int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, void *const *shards,
+                           const int *erased, int n_erased, const size_t *shard_bytes, void *stream);
 
 /* ---- diagnostics -----------------------------------------------------------*/
 const char *gs_strerror(int status);

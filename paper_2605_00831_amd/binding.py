@@ -22,6 +22,8 @@ EXPORTS = [
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
     "gs_pipe_done_event",
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
+    "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
+    "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
     "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape",
 ]
 
@@ -78,6 +80,17 @@ def lib():
     L.gs_step_graph_launch.argtypes = [_vp, _vp]
     L.gs_step_graph_destroy.argtypes = [_vp]
     L.gs_step_graph_destroy.restype = None
+    _szp = ctypes.POINTER(ctypes.c_size_t)
+    L.gs_batch_create.argtypes = [_vp, ctypes.c_int, ctypes.POINTER(_vp)]
+    L.gs_batch_destroy.argtypes = [_vp]
+    L.gs_batch_destroy.restype = None
+    L.gs_encode_batch.argtypes = [_vp, ctypes.c_int, _vpp, _vpp, _szp, _vp]
+    L.gs_reconstruct_batch.argtypes = [_vp, ctypes.c_int, _vpp, _intp, ctypes.c_int, _szp, _vp]
+    L.gs_pool_create.argtypes = [ctypes.c_int, ctypes.POINTER(_vp)]
+    L.gs_pool_destroy.argtypes = [_vp]
+    L.gs_pool_destroy.restype = None
+    L.gs_encode_streams.argtypes = [_vp, _vp, ctypes.c_int, _vpp, _vpp, _szp, _vp]
+    L.gs_reconstruct_streams.argtypes = [_vp, _vp, ctypes.c_int, _vpp, _intp, ctypes.c_int, _szp, _vp]
     L.gs_strerror.argtypes = [ctypes.c_int]
     L.gs_strerror.restype = ctypes.c_char_p
     L.gs_last_hip_error.argtypes = []
@@ -252,6 +265,92 @@ def gs_step_graph_destroy(graph):
     if graph.handle:
         lib().gs_step_graph_destroy(graph.handle)
         graph.handle = None
+
+
+class Batch:
+    def __init__(self, handle, code):
+        self.handle, self.code = handle, code
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gs_batch_destroy(self.handle)
+            self.handle = None
+
+
+class Pool:
+    def __init__(self, handle):
+        self.handle = handle
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.gs_pool_destroy(self.handle)
+            self.handle = None
+
+
+def _flat_ptrs(chunks, width):
+    """list (per chunk) of lists of `width` pointers -> one flat pointer array"""
+    flat = []
+    for c in chunks:
+        if len(c) != width:
+            raise ValueError("every chunk needs %d pointers" % width)
+        flat.extend(c)
+    return _ptr_array(flat)
+
+
+def _size_array(sizes):
+    sizes = list(sizes)
+    return (ctypes.c_size_t * max(len(sizes), 1))(*sizes)
+
+
+def gs_batch_create(code, max_chunks):
+    h = _vp()
+    _check(lib().gs_batch_create(code.handle, max_chunks, ctypes.byref(h)), "gs_batch_create")
+    return Batch(h, code)
+
+
+def gs_batch_destroy(batch):
+    if batch.handle:
+        lib().gs_batch_destroy(batch.handle)
+        batch.handle = None
+
+
+def gs_encode_batch(batch, data, parity, shard_bytes, stream=None):
+    """data / parity: per chunk, a list of k resp. m tensors or addresses."""
+    n = len(data)
+    _check(lib().gs_encode_batch(batch.handle, n, _flat_ptrs(data, batch.code.k), _flat_ptrs(parity, batch.code.m),
+                                 _size_array(shard_bytes), _stream(stream)), "gs_encode_batch")
+
+
+def gs_reconstruct_batch(batch, shards, erased, shard_bytes, stream=None):
+    n = len(shards)
+    er, ne = _int_array(erased)
+    _check(lib().gs_reconstruct_batch(batch.handle, n, _flat_ptrs(shards, batch.code.k + batch.code.m), er, ne,
+                                      _size_array(shard_bytes), _stream(stream)), "gs_reconstruct_batch")
+
+
+def gs_pool_create(n_streams):
+    h = _vp()
+    _check(lib().gs_pool_create(n_streams, ctypes.byref(h)), "gs_pool_create")
+    return Pool(h)
+
+
+def gs_pool_destroy(pool):
+    if pool.handle:
+        lib().gs_pool_destroy(pool.handle)
+        pool.handle = None
+
+
+def gs_encode_streams(code, pool, data, parity, shard_bytes, stream=None):
+    n = len(data)
+    _check(lib().gs_encode_streams(code.handle, pool.handle, n, _flat_ptrs(data, code.k), _flat_ptrs(parity, code.m),
+                                   _size_array(shard_bytes), _stream(stream)), "gs_encode_streams")
+
+
+def gs_reconstruct_streams(code, pool, shards, erased, shard_bytes, stream=None):
+    n = len(shards)
+    er, ne = _int_array(erased)
+    _check(lib().gs_reconstruct_streams(code.handle, pool.handle, n, _flat_ptrs(shards, code.k + code.m), er, ne,
+                                        _size_array(shard_bytes), _stream(stream)), "gs_reconstruct_streams")
 
 
 def gs_coef_words(c):

@@ -1,0 +1,241 @@
+// Many chunks at once: a grouped launch over a device-side descriptor array
+// (gs_batch), and the one-stream-per-chunk form the paper describes (gs_pool).
+#include "../../include/ghostserve_ec.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "gs_internal.h"
+
+using namespace gs;
+
+namespace {
+constexpr int kRing = 4;  // descriptor slots in flight per gs_batch
+}
+
+// Descriptor slots are reused round-robin; a slot's event is recorded after
+// the kernel that reads it, and the host waits on it only when the ring wraps
+// while that kernel is still running.
+struct gs_batch {
+    const gs_code *code = nullptr;
+    int max_chunks = 0;
+    size_t slot_bytes = 0;
+    uint8_t *dev = nullptr;     // kRing * slot_bytes
+    uint8_t *host = nullptr;    // pinned mirror
+    hipEvent_t done[kRing] = {};
+    bool used[kRing] = {};
+    unsigned next = 0;
+};
+
+struct gs_pool {
+    std::vector<hipStream_t> streams;
+    hipEvent_t fork = nullptr;
+    std::vector<hipEvent_t> join;
+};
+
+#define GS_TRY(expr)                                 \
+    do {                                             \
+        const hipError_t e_ = (expr);                \
+        if (e_ != hipSuccess) return hip_status(e_); \
+    } while (0)
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Enqueue one grouped launch: rows x k matrix C over n chunks; in/out are
+// chunk-major pointer arrays with strides in_stride / out_stride entries.
+static int run_batch(gs_batch *b, int rows, const uint8_t *C, int n, const void *const *in, int in_stride,
+                     void *const *out, int out_stride, const size_t *bytes, hipStream_t stream)
+{
+    const int k = b->code->k;
+    const LaunchShape shape = current_shape();
+    size_t max_bytes = 0;
+    for (int c = 0; c < n; ++c) max_bytes = std::max(max_bytes, bytes[c]);
+    if (max_bytes == 0) return GS_OK;
+    if (max_bytes >= (1ull << 36)) return GS_EINVAL;  // 64 GiB per stream and chunk
+    const unsigned slot = b->next % kRing;
+    if (b->used[slot]) GS_TRY(hipEventSynchronize(b->done[slot]));
+    uint8_t *hslot = b->host + static_cast<size_t>(slot) * b->slot_bytes;
+    uint8_t *dslot = b->dev + static_cast<size_t>(slot) * b->slot_bytes;
+    for (int c = 0; c < n; ++c)
+        write_batch_desc(hslot, c, rows, k, C, k, in + static_cast<size_t>(c) * in_stride,
+                         out + static_cast<size_t>(c) * out_stride, bytes[c], shape);
+    GS_TRY(hipMemcpyAsync(dslot, hslot, static_cast<size_t>(n) * batch_desc_bytes(), hipMemcpyHostToDevice, stream));
+    GS_TRY(launch_apply_batch(rows, k, C, k, dslot, n, max_bytes, shape, stream));
+    GS_TRY(hipEventRecord(b->done[slot], stream));
+    b->used[slot] = true;
+    ++b->next;
+    return GS_OK;
+}
+
+// chunk c runs on pool stream c mod n; the pool streams start after everything
+// already enqueued on `stream`, and `stream` continues after all of them
+template <typename PerChunk>
+static int fan_out(gs_pool *p, int n_chunks, hipStream_t stream, PerChunk per_chunk)
+{
+    const int ns = static_cast<int>(p->streams.size());
+    const int active = std::min(ns, n_chunks);
+    GS_TRY(hipEventRecord(p->fork, stream));
+    for (int s = 0; s < active; ++s) GS_TRY(hipStreamWaitEvent(p->streams[s], p->fork, 0));
+    for (int c = 0; c < n_chunks; ++c) {
+        const int rc = per_chunk(c, p->streams[c % ns]);
+        if (rc != GS_OK) return rc;
+    }
+    for (int s = 0; s < active; ++s) {
+        GS_TRY(hipEventRecord(p->join[s], p->streams[s]));
+        GS_TRY(hipStreamWaitEvent(stream, p->join[s], 0));
+    }
+    return GS_OK;
+}
+
+extern "C" {
+
+void gs_batch_destroy(gs_batch *b)
+{
+    if (b == nullptr) return;
+    for (int s = 0; s < kRing; ++s) {
+        if (b->used[s]) (void)hipEventSynchronize(b->done[s]);
+        if (b->done[s]) (void)hipEventDestroy(b->done[s]);
+    }
+    if (b->dev) (void)hipFree(b->dev);
+    if (b->host) (void)hipHostFree(b->host);
+    delete b;
+}
+
+int gs_batch_create(const gs_code *code, int max_chunks, gs_batch **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (code == nullptr || max_chunks < 1 || max_chunks > 65535) return GS_EINVAL;
+    if (code->k > kLaunchMaxK || code->m > kLaunchMaxM) return GS_EINVAL;
+    gs_batch *b = new (std::nothrow) gs_batch;
+    if (b == nullptr) return GS_ENOMEM;
+    b->code = code;
+    b->max_chunks = max_chunks;
+    b->slot_bytes = static_cast<size_t>(max_chunks) * batch_desc_bytes();
+    int rc = GS_OK;
+    auto step = [&](hipError_t e) { if (rc == GS_OK && e != hipSuccess) rc = hip_status(e); };
+    step(hipMalloc(reinterpret_cast<void **>(&b->dev), kRing * b->slot_bytes));
+    step(hipHostMalloc(reinterpret_cast<void **>(&b->host), kRing * b->slot_bytes, hipHostMallocDefault));
+    for (int s = 0; s < kRing && rc == GS_OK; ++s) step(hipEventCreateWithFlags(&b->done[s], hipEventDisableTiming));
+    if (rc != GS_OK) {
+        gs_batch_destroy(b);
+        return rc;
+    }
+    *out = b;
+    return GS_OK;
+}
+
+int gs_encode_batch(gs_batch *b, int n_chunks, const void *const *data, void *const *parity,
+                    const size_t *shard_bytes, void *stream)
+{
+    if (b == nullptr || n_chunks < 0 || n_chunks > b->max_chunks) return GS_EINVAL;
+    if (n_chunks == 0) return GS_OK;
+    if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
+    const int k = b->code->k, m = b->code->m;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (shard_bytes[c] == 0) continue;
+        for (int j = 0; j < k; ++j)
+            if (data[c * k + j] == nullptr || !aligned16(data[c * k + j])) return GS_EINVAL;
+        for (int i = 0; i < m; ++i)
+            if (parity[c * m + i] == nullptr || !aligned16(parity[c * m + i])) return GS_EINVAL;
+    }
+    return run_batch(b, m, b->code->P.data(), n_chunks, data, k, parity, m, shard_bytes,
+                     static_cast<hipStream_t>(stream));
+}
+
+int gs_reconstruct_batch(gs_batch *b, int n_chunks, void *const *shards, const int *erased, int n_erased,
+                         const size_t *shard_bytes, void *stream)
+{
+    if (b == nullptr || n_chunks < 0 || n_chunks > b->max_chunks) return GS_EINVAL;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc = decode_matrix(b->code, erased, n_erased, R, surv);
+    if (rc != GS_OK) return rc;
+    if (n_chunks == 0 || n_erased == 0) return GS_OK;
+    if (shards == nullptr || shard_bytes == nullptr) return GS_EINVAL;
+    const int k = b->code->k, n = k + b->code->m;
+    std::vector<const void *> in(static_cast<size_t>(n_chunks) * k);
+    std::vector<void *> out(static_cast<size_t>(n_chunks) * n_erased);
+    for (int c = 0; c < n_chunks; ++c) {
+        for (int j = 0; j < k; ++j) {
+            const void *p = shards[static_cast<size_t>(c) * n + surv[j]];
+            if (shard_bytes[c] != 0 && (p == nullptr || !aligned16(p))) return GS_EINVAL;
+            in[static_cast<size_t>(c) * k + j] = p;
+        }
+        for (int x = 0; x < n_erased; ++x) {
+            void *p = shards[static_cast<size_t>(c) * n + erased[x]];
+            if (shard_bytes[c] != 0 && (p == nullptr || !aligned16(p))) return GS_EINVAL;
+            out[static_cast<size_t>(c) * n_erased + x] = p;
+        }
+    }
+    return run_batch(b, n_erased, R.data(), n_chunks, in.data(), k, out.data(), n_erased, shard_bytes,
+                     static_cast<hipStream_t>(stream));
+}
+
+// ---- one stream per chunk (Section 5, "CUDA Streams"; continuous batching) ----
+
+void gs_pool_destroy(gs_pool *p)
+{
+    if (p == nullptr) return;
+    for (hipStream_t s : p->streams) if (s) { (void)hipStreamSynchronize(s); (void)hipStreamDestroy(s); }
+    for (hipEvent_t e : p->join) if (e) (void)hipEventDestroy(e);
+    if (p->fork) (void)hipEventDestroy(p->fork);
+    delete p;
+}
+
+int gs_pool_create(int n_streams, gs_pool **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (n_streams < 1 || n_streams > 64) return GS_EINVAL;
+    gs_pool *p = new (std::nothrow) gs_pool;
+    if (p == nullptr) return GS_ENOMEM;
+    p->streams.assign(n_streams, nullptr);
+    p->join.assign(n_streams, nullptr);
+    int rc = GS_OK;
+    auto step = [&](hipError_t e) { if (rc == GS_OK && e != hipSuccess) rc = hip_status(e); };
+    for (int s = 0; s < n_streams && rc == GS_OK; ++s) {
+        step(hipStreamCreateWithFlags(&p->streams[s], hipStreamNonBlocking));  // default priority
+        step(hipEventCreateWithFlags(&p->join[s], hipEventDisableTiming));
+    }
+    step(hipEventCreateWithFlags(&p->fork, hipEventDisableTiming));
+    if (rc != GS_OK) {
+        gs_pool_destroy(p);
+        return rc;
+    }
+    *out = p;
+    return GS_OK;
+}
+
+int gs_encode_streams(const gs_code *code, gs_pool *pool, int n_chunks, const void *const *data,
+                      void *const *parity, const size_t *shard_bytes, void *stream)
+{
+    if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
+    if (n_chunks == 0) return GS_OK;
+    if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
+    const int k = code->k, m = code->m;
+    return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
+        return gs_encode(code, data + static_cast<size_t>(c) * k, parity + static_cast<size_t>(c) * m,
+                         shard_bytes[c], s);
+    });
+}
+
+int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, void *const *shards,
+                           const int *erased, int n_erased, const size_t *shard_bytes, void *stream)
+{
+    if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
+    std::vector<uint8_t> lost;
+    const int rc = check_erasures(code, erased, n_erased, lost);
+    if (rc != GS_OK) return rc;
+    if (n_chunks == 0 || n_erased == 0) return GS_OK;
+    if (shards == nullptr || shard_bytes == nullptr) return GS_EINVAL;
+    const int n = code->k + code->m;
+    return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
+        return gs_reconstruct(code, shards + static_cast<size_t>(c) * n, erased, n_erased, shard_bytes[c], s);
+    });
+}
+
+}  // extern "C"

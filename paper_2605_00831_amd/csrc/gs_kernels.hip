@@ -40,6 +40,21 @@ struct ApplyArgs {
     uint32_t nx_shift;    // log2 of the interleave modulus (0 = plain consecutive tiles)
 };
 
+// one chunk of a batched launch (device memory)
+struct BatchDesc {
+    const uint8_t *in[kLaunchMaxK];
+    uint8_t *out[kLaunchMaxM];
+    uint64_t nvec;
+    uint32_t tail;
+    uint32_t nx_shift;
+};
+
+struct BatchArgs {
+    const BatchDesc *descs;  // device array, one per blockIdx.y
+    uint32_t tab[kLaunchMaxM][kLaunchMaxK][8];
+    int32_t k;
+};
+
 struct PagedArgs {
     const uint8_t *const *plane_base;  // device array [n_planes]
     const int32_t *table;              // device [k][pps], first row of this launch
@@ -131,34 +146,37 @@ __device__ __forceinline__ void mac(Acc4 (&acc)[M][U], const u32x4 (&x)[U],
 
 constexpr int kBatch = 4;  // streams whose loads are issued together
 
-// One tile of the contiguous kernel: each lane handles the U vectors v[0..U).
+// One tile over contiguous streams: each lane handles the U vectors v[0..U).
 // FULL tiles (every lane in range) carry no predication at all; only tiles
 // that reach past the end of the shard take the predicated form.
-template <int M, bool ROW0_XOR, int U, bool NT, bool FULL>
-__device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (&v)[U])
+// S names where the stream pointers and the length live: the kernel arguments
+// (ApplyArgs) or a per-chunk descriptor in device memory (BatchDesc).
+template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, class S>
+__device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
+                                            int k, int accumulate, const uint64_t (&v)[U])
 {
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = FULL || v[u] < a.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || v[u] < s.nvec;
 
     Acc4 acc[M][U];
 #pragma unroll
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[r][u] = Acc4{{0, 0, 0, 0}};
-    if (a.accumulate) {
+    if (accumulate) {
 #pragma unroll
         for (int r = 0; r < M; ++r)
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) acc[r][u] = from_vec(load16<NT>(a.out[r], v[u]));
+                if (ok[u]) acc[r][u] = from_vec(load16<NT>(s.out[r], v[u]));
     }
 
     int j = 0;
-    for (; j + kBatch <= a.k; j += kBatch) {
+    for (; j + kBatch <= k; j += kBatch) {
         const uint8_t *src[kBatch];
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) src[b] = a.in[j + b];
+        for (int b = 0; b < kBatch; ++b) src[b] = s.in[j + b];
         u32x4 x[kBatch][U];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b)
@@ -168,24 +186,24 @@ __device__ __forceinline__ void contig_tile(const ApplyArgs &a, const uint64_t (
                 if (ok[u]) x[b][u] = load16<NT>(src[b], v[u]);
             }
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
+        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], tab, j + b);
     }
-    for (; j < a.k; ++j) {
-        const uint8_t *src = a.in[j];
+    for (; j < k; ++j) {
+        const uint8_t *src = s.in[j];
         u32x4 x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u] = u32x4{0, 0, 0, 0};
             if (ok[u]) x[u] = load16<NT>(src, v[u]);
         }
-        mac<M, ROW0_XOR, U>(acc, x, a.tab, j);
+        mac<M, ROW0_XOR, U>(acc, x, tab, j);
     }
 
 #pragma unroll
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(a.out[r], v[u], to_vec(acc[r][u]));
+            if (ok[u]) store16<NT>(s.out[r], v[u], to_vec(acc[r][u]));
 }
 
 // Occupancy the register allocator is asked to reach (wavefronts per SIMD).
@@ -207,44 +225,69 @@ constexpr int kWavesPerEu()
 // i.e. every NX-th piece inside a super-tile of NX*4U pieces, wavefront w
 // taking q = w*U .. w*U+U-1.  All NX tiles of a super-tile together cover it
 // exactly once.  nx_shift = 0 gives plain consecutive tiles.
-template <int M, bool ROW0_XOR, int U, bool NT>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
-void apply_contig_kernel(const ApplyArgs a)
+template <int M, bool ROW0_XOR, int U, bool NT, class S>
+__device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
+                                               int k, int accumulate, uint32_t tiles_per_wg, bool last_wg)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6, lane = tid & 63u;
     constexpr uint32_t kPieces = (kThreads / 64) * U;  // pieces per tile
-    const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
-    const uint64_t nx_mask = (1ull << a.nx_shift) - 1;
+    const uint32_t nx_shift = s.nx_shift;
+    const uint64_t nvec = s.nvec;
+    const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * tiles_per_wg;
+    const uint64_t nx_mask = (1ull << nx_shift) - 1;
 
-    for (uint32_t tt = 0; tt < a.tiles_per_wg; ++tt) {
+    for (uint32_t tt = 0; tt < tiles_per_wg; ++tt) {
         const uint64_t t = first_tile + tt;
-        const uint64_t g = t >> a.nx_shift, r = t & nx_mask;
+        const uint64_t g = t >> nx_shift, r = t & nx_mask;
         // first vector of the super-tile; nothing to do once it is past the end
-        const uint64_t super_first = ((g * kPieces) << a.nx_shift) * 64;
-        if (super_first >= a.nvec) break;
+        const uint64_t super_first = ((g * kPieces) << nx_shift) * 64;
+        if (super_first >= nvec) break;
         uint64_t v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
-        const uint64_t super_end = (((g + 1) * kPieces) << a.nx_shift) * 64;
-        if (super_end <= a.nvec) contig_tile<M, ROW0_XOR, U, NT, true>(a, v);
-        else contig_tile<M, ROW0_XOR, U, NT, false>(a, v);
+        for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << nx_shift) + r) << 6) + lane;
+        const uint64_t super_end = (((g + 1) * kPieces) << nx_shift) * 64;
+        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true>(s, tab, k, accumulate, v);
+        else contig_tile<M, ROW0_XOR, U, NT, false>(s, tab, k, accumulate, v);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
     // lane per byte, in the last workgroup
-    if (a.tail != 0 && blockIdx.x == gridDim.x - 1 && tid < a.tail) {
-        const uint64_t t = a.nvec * 16 + tid;
+    const uint32_t tail = s.tail;
+    if (tail != 0 && last_wg && tid < tail) {
+        const uint64_t t = nvec * 16 + tid;
 #pragma unroll
         for (int r = 0; r < M; ++r) {
-            uint32_t s = a.accumulate ? a.out[r][t] : 0u;
-            for (int j = 0; j < a.k; ++j) {
-                const uint32_t xb = a.in[j][t];
-                s ^= (ROW0_XOR && r == 0) ? xb : mul1(a.tab[r][j], xb);
+            uint8_t *dst = s.out[r];
+            uint32_t sum = accumulate ? dst[t] : 0u;
+            for (int j = 0; j < k; ++j) {
+                const uint32_t xb = s.in[j][t];
+                sum ^= (ROW0_XOR && r == 0) ? xb : mul1(tab[r][j], xb);
             }
-            a.out[r][t] = static_cast<uint8_t>(s);
+            dst[t] = static_cast<uint8_t>(sum);
         }
     }
+}
+
+template <int M, bool ROW0_XOR, int U, bool NT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
+void apply_contig_kernel(const ApplyArgs a)
+{
+    contig_streams<M, ROW0_XOR, U, NT>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+}
+
+// Many independent chunks in one launch (one request's chunk, or one chunk of
+// a long prefill, each): blockIdx.y is the chunk, its pointers and length come
+// from a descriptor array in device memory, read with scalar loads through the
+// constant address space (descriptors are never written while the kernel runs).
+typedef const BatchDesc __attribute__((address_space(4))) *ConstDesc;
+
+template <int M, bool ROW0_XOR, int U, bool NT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
+void apply_batch_kernel(const BatchArgs a)
+{
+    ConstDesc d = (ConstDesc)a.descs + blockIdx.y;
+    contig_streams<M, ROW0_XOR, U, NT>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
 }
 
 // One tile of the paged gather.  A lane whose vector index is past the end of
@@ -369,34 +412,51 @@ static const CoefTable &coef_table()
     return t;
 }
 
-// Fill the table block and output pointers of a launch; if some row of the
-// coefficient slice is all ones it is moved to row 0 so the XOR shortcut
-// applies.  Returns true when row 0 is all ones.
-template <typename Args>
-static bool fill_rows(Args &a, int rows, int k, const uint8_t *coef, int coef_stride, void *const *out)
-{
+// Row order of a launch: if some row of the coefficient slice is all ones it
+// is moved to position 0 so that the XOR shortcut applies.
+struct RowPlan {
     int order[kLaunchMaxM];
-    for (int r = 0; r < rows; ++r) order[r] = r;
-    bool row0_xor = false;
-    for (int r = 0; r < rows && !row0_xor; ++r) {
+    bool row0_xor;
+};
+
+static RowPlan plan_rows(int rows, int k, const uint8_t *coef, int coef_stride)
+{
+    RowPlan p;
+    for (int r = 0; r < kLaunchMaxM; ++r) p.order[r] = r;
+    p.row0_xor = false;
+    for (int r = 0; r < rows && !p.row0_xor; ++r) {
         bool ones = true;
         for (int j = 0; j < k; ++j) ones = ones && coef[r * coef_stride + j] == 1;
         if (ones) {
-            order[0] = r;
-            order[r] = 0;
-            row0_xor = true;
+            p.order[0] = r;
+            p.order[r] = 0;
+            p.row0_xor = true;
         }
     }
+    return p;
+}
+
+// table block of a launch, rows in plan order
+template <typename Args>
+static void fill_tables(Args &a, const RowPlan &p, int rows, int k, const uint8_t *coef, int coef_stride)
+{
     const CoefTable &ct = coef_table();
-    for (int r = 0; r < kLaunchMaxM; ++r) {
-        a.out[r] = r < rows ? static_cast<uint8_t *>(out[order[r]]) : nullptr;
+    for (int r = 0; r < kLaunchMaxM; ++r)
         for (int j = 0; j < kLaunchMaxK; ++j) {
-            const unsigned c = (r < rows && j < k) ? coef[order[r] * coef_stride + j] : 0u;
+            const unsigned c = (r < rows && j < k) ? coef[p.order[r] * coef_stride + j] : 0u;
             for (int i = 0; i < 5; ++i) a.tab[r][j][i] = ct.c[c].w[i];
             a.tab[r][j][5] = a.tab[r][j][6] = a.tab[r][j][7] = 0;
         }
-    }
-    return row0_xor;
+}
+
+// tables and output pointers of a launch; returns true when row 0 is all ones
+template <typename Args>
+static bool fill_rows(Args &a, int rows, int k, const uint8_t *coef, int coef_stride, void *const *out)
+{
+    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
+    fill_tables(a, p, rows, k, coef, coef_stride);
+    for (int r = 0; r < kLaunchMaxM; ++r) a.out[r] = r < rows ? static_cast<uint8_t *>(out[p.order[r]]) : nullptr;
+    return p.row0_xor;
 }
 
 template <template <int, bool, int, bool> class Launcher, typename Args>
@@ -496,6 +556,52 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
     return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), stream);
+}
+
+template <int M, bool X, int U, bool NT>
+struct BatchLauncher {
+    static hipError_t go(const BatchArgs &a, dim3 grid, hipStream_t stream)
+    {
+        hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        return hipGetLastError();
+    }
+};
+
+size_t batch_desc_bytes() { return sizeof(BatchDesc); }
+
+void write_batch_desc(void *slot, int idx, int rows, int k, const uint8_t *coef, int coef_stride,
+                      const void *const *in, void *const *out, size_t bytes, const LaunchShape &shape)
+{
+    BatchDesc &d = static_cast<BatchDesc *>(slot)[idx];
+    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
+    for (int j = 0; j < kLaunchMaxK; ++j) d.in[j] = j < k ? static_cast<const uint8_t *>(in[j]) : nullptr;
+    for (int r = 0; r < kLaunchMaxM; ++r) d.out[r] = r < rows ? static_cast<uint8_t *>(out[p.order[r]]) : nullptr;
+    d.nvec = bytes / 16;
+    d.tail = static_cast<uint32_t>(bytes % 16);
+    uint64_t tiles;
+    interleave_for(d.nvec, sane_unroll(shape.unroll, rows), shape.interleave_shift, d.nx_shift, tiles);
+}
+
+hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_stride, const void *descs_dev,
+                              int n_chunks, size_t max_bytes, const LaunchShape &shape, hipStream_t stream)
+{
+    if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
+    if (n_chunks < 1 || n_chunks > 65535) return hipErrorInvalidValue;
+    if (max_bytes == 0) return hipSuccess;
+    BatchArgs a;
+    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
+    fill_tables(a, p, rows, k, coef, coef_stride);
+    a.descs = static_cast<const BatchDesc *>(descs_dev);
+    a.k = k;
+    const int unroll = sane_unroll(shape.unroll, rows);
+    uint32_t nx_shift;
+    uint64_t tiles;
+    interleave_for(max_bytes / 16, unroll, shape.interleave_shift, nx_shift, tiles);
+    uint32_t tpw = 1, wgs = 1;
+    grid_for(tiles, tpw, wgs);
+    if (tpw != 1) return hipErrorInvalidValue;  // chunks this large go through launch_apply
+    return dispatch<BatchLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
+                                   dim3(wgs, static_cast<uint32_t>(n_chunks)), stream);
 }
 
 hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,

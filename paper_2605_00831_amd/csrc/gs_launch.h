@@ -31,4 +31,14 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
                               void *const *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream);
 
+// Batched form: n_chunks independent stream sets in one launch (blockIdx.y =
+// chunk).  Descriptors are written on the host with write_batch_desc() into a
+// buffer of n * batch_desc_bytes() bytes, copied to the device by the caller,
+// and passed as descs_dev.  max_bytes is the largest chunk's stream length.
+size_t batch_desc_bytes();
+void write_batch_desc(void *slot, int idx, int rows, int k, const uint8_t *coef, int coef_stride,
+                      const void *const *in, void *const *out, size_t bytes, const LaunchShape &shape);
+hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_stride, const void *descs_dev,
+                              int n_chunks, size_t max_bytes, const LaunchShape &shape, hipStream_t stream);
+
 }  // namespace gs
