@@ -251,7 +251,57 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
 
     # ---- streaming decode-step checkpoint (paged, k=4, m=1), latency over 1000 steps
     res["decode_step"] = decode_steps(torch, gs, inputs, log)
+    # ---- many small chunks: one launch per chunk, a stream per chunk, or one grouped launch
+    res["many_chunks"] = many_chunks(torch, gs, log)
     return res
+
+
+def many_chunks(torch, gs, log):
+    """Recovery of many chunks at once (one lost shard of an 8+2 code) and
+    per-request encodes (4+1), three ways; host-timed enqueue -> sync, median."""
+    def wall(fn, iters=15, warm=3):
+        for _ in range(warm):
+            fn()
+        ts = []
+        for _ in range(iters):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
+        return sorted(ts)[len(ts) // 2] * 1e3
+
+    out = []
+    for k, m, er, S, n in [(8, 2, [3], 2 << 20, 64), (8, 2, [3, 6], 256 << 10, 256), (4, 1, None, 512 << 10, 64)]:
+        code = gs.gs_make_code(k, m)
+        big = torch.empty(n * (k + m) * S, dtype=torch.uint8, device="cuda")
+        big.random_(0, 256)
+        shards = [[big[(c * (k + m) + r) * S:(c * (k + m) + r + 1) * S] for r in range(k + m)] for c in range(n)]
+        sizes = [S] * n
+        batch = gs.gs_batch_create(code, n)
+        pool = gs.gs_pool_create(16)
+        if er is None:
+            data, par = [row[:k] for row in shards], [row[k:] for row in shards]
+            forms = {"one_launch_per_chunk_ms": lambda: [gs.gs_encode(code, data[c], par[c], S) for c in range(n)],
+                     "stream_pool_16_ms": lambda: gs.gs_encode_streams(code, pool, data, par, sizes),
+                     "grouped_launch_ms": lambda: gs.gs_encode_batch(batch, data, par, sizes)}
+            traffic = (k + m) * S * n
+        else:
+            forms = {"one_launch_per_chunk_ms": lambda: [gs.gs_reconstruct(code, shards[c], er, S) for c in range(n)],
+                     "stream_pool_16_ms": lambda: gs.gs_reconstruct_streams(code, pool, shards, er, sizes),
+                     "grouped_launch_ms": lambda: gs.gs_reconstruct_batch(batch, shards, er, sizes)}
+            traffic = (k + len(er)) * S * n
+        row = {"op": "encode" if er is None else "reconstruct", "k": k, "m": m, "erased": er,
+               "chunks": n, "shard_bytes": S}
+        for name, fn in forms.items():
+            row[name] = round(wall(fn), 4)
+        row["grouped_launch_traffic_GBps"] = round(traffic / row["grouped_launch_ms"] / 1e6, 1)
+        out.append(row)
+        gs.gs_batch_destroy(batch)
+        gs.gs_pool_destroy(pool)
+        del big, shards
+    log("[bench] many chunks: " + json.dumps(out))
+    return out
 
 
 def decode_steps(torch, gs, inputs, log):
