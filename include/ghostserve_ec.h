@@ -219,6 +219,30 @@ int gs_encode_streams(const gs_code *code, gs_pool *pool, int n_chunks, const vo
 int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, void *const *shards,
                            const int *erased, int n_erased, const size_t *shard_bytes, void *stream);
 
+/* ---- hybrid recovery planner (host only) -----------------------------------
+ * Alg. 2 recomputes the first r chunks of the lost KV cache on the restarted
+ * device while the other n-r chunks are reconstructed from the survivors and
+ * the parity coming back over PCIe; r = get_recompute_units(...) is left
+ * undefined by the paper.  Here it is the r in [0, n] that minimises
+ *     max( recompute(r), restore(n - r) )
+ * under a cost model the caller fills from its own measurements:
+ *     recompute(r) = sum_{i<r} (recompute_base_s + recompute_growth_s * i)
+ *                    (a chunk's prefill grows with the context before it)
+ *     restore(q)   = 0 for q = 0, else restore_startup_s + the two faster of
+ *                    {gather_s, h2d_s, reconstruct_s} once + q * the slowest
+ *                    (a three-stage pipeline per chunk)
+ * Ties go to the smaller r.  r = n means pure recomputation (short inputs).
+ * All costs are seconds per chunk, finite and >= 0, else GS_EINVAL. */
+typedef struct gs_recovery_costs {
+    double recompute_base_s;    /* prefill of one chunk with no context before it     */
+    double recompute_growth_s;  /* extra prefill time per chunk of preceding context  */
+    double gather_s;            /* collect one chunk's surviving data shards          */
+    double h2d_s;               /* bring one chunk's parity back from host memory     */
+    double reconstruct_s;       /* reconstruct kernel on one chunk                    */
+    double restore_startup_s;   /* fixed cost of starting the restore pipeline at all */
+} gs_recovery_costs;
+int gs_recompute_units(int n_chunks, const gs_recovery_costs *costs, int *r_out, double *makespan_out);
+
 /* ---- diagnostics -----------------------------------------------------------*/
 const char *gs_strerror(int status);
 /* last hipError_t seen by the calling thread in this library (0 = none) */

@@ -35,6 +35,10 @@ def build(force=False):
     return _LIB
 
 
+class _Costs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("base", "growth", "gather", "h2d", "reconstruct", "startup")]
+
+
 _lib = None
 
 
@@ -61,6 +65,7 @@ def lib():
                                         _u8p, _intp]
         L.gso_reconstruct.argtypes = [ctypes.c_int, ctypes.c_int, _u8p, _u8pp, _intp,
                                       ctypes.c_int, ctypes.c_size_t]
+        L.gso_recompute_units.argtypes = [ctypes.c_int, ctypes.POINTER(_Costs), ctypes.POINTER(ctypes.c_double)]
         L.gso_init()
         _lib = L
     return _lib
@@ -194,3 +199,11 @@ def reconstruct(P, shards, erased):
     if rc:
         raise ValueError("bad erasure list")
     return shards
+
+
+def recompute_units(n_chunks, base, growth, gather, h2d, reconstruct, startup=0.0):
+    """(r, makespan): brute force over every r in [0, n]."""
+    c = _Costs(base, growth, gather, h2d, reconstruct, startup)
+    t = ctypes.c_double()
+    r = lib().gso_recompute_units(n_chunks, ctypes.byref(c), ctypes.byref(t))
+    return r, t.value

@@ -372,3 +372,43 @@ int gso_encode_mt(int k, int m, const uint8_t *P,
     }
     return 0;
 }
+
+/* ---- hybrid recovery planner (Alg. 2, get_recompute_units) -----------------
+ * The paper names the function but never defines it.  Reading: recompute the
+ * first r chunks while the other n-r are restored through a three-stage
+ * pipeline (gather survivors, parity H2D, reconstruct); pick the r in [0, n]
+ * with the smallest max(recompute(r), restore(n-r)), smallest r on a tie.
+ * The oracle evaluates every r with the sums written out term by term. */
+struct gso_costs { double base, growth, gather, h2d, reconstruct, startup; };
+
+static double gso_recompute(const struct gso_costs *c, int r)
+{
+    double t = 0.0;
+    for (int i = 0; i < r; i++) t += c->base + c->growth * (double)i;
+    return t;
+}
+
+static double gso_restore(const struct gso_costs *c, int q)
+{
+    if (q <= 0) return 0.0;
+    double slow = c->gather;
+    if (c->h2d > slow) slow = c->h2d;
+    if (c->reconstruct > slow) slow = c->reconstruct;
+    double once = c->gather + c->h2d + c->reconstruct - slow;
+    double t = c->startup + once;
+    for (int i = 0; i < q; i++) t += slow;
+    return t;
+}
+
+int gso_recompute_units(int n, const struct gso_costs *c, double *makespan_out)
+{
+    int best = 0;
+    double best_t = -1.0;
+    for (int r = 0; r <= n; r++) {
+        double a = gso_recompute(c, r), b = gso_restore(c, n - r);
+        double t = a > b ? a : b;
+        if (best_t < 0.0 || t < best_t) { best_t = t; best = r; }
+    }
+    if (makespan_out) *makespan_out = best_t < 0.0 ? 0.0 : best_t;
+    return best;
+}

@@ -24,6 +24,7 @@ EXPORTS = [
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
     "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
     "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
+    "gs_recompute_units",
     "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape",
 ]
 
@@ -31,6 +32,13 @@ _vp = ctypes.c_void_p
 _vpp = ctypes.POINTER(ctypes.c_void_p)
 _u8p = ctypes.POINTER(ctypes.c_uint8)
 _intp = ctypes.POINTER(ctypes.c_int)
+
+class RecoveryCosts(ctypes.Structure):
+    """seconds per chunk; see gs_recovery_costs in the header"""
+    _fields_ = [("recompute_base_s", ctypes.c_double), ("recompute_growth_s", ctypes.c_double),
+                ("gather_s", ctypes.c_double), ("h2d_s", ctypes.c_double),
+                ("reconstruct_s", ctypes.c_double), ("restore_startup_s", ctypes.c_double)]
+
 
 _lib = None
 
@@ -91,6 +99,8 @@ def lib():
     L.gs_pool_destroy.restype = None
     L.gs_encode_streams.argtypes = [_vp, _vp, ctypes.c_int, _vpp, _vpp, _szp, _vp]
     L.gs_reconstruct_streams.argtypes = [_vp, _vp, ctypes.c_int, _vpp, _intp, ctypes.c_int, _szp, _vp]
+    L.gs_recompute_units.argtypes = [ctypes.c_int, ctypes.POINTER(RecoveryCosts), _intp,
+                                     ctypes.POINTER(ctypes.c_double)]
     L.gs_strerror.argtypes = [ctypes.c_int]
     L.gs_strerror.restype = ctypes.c_char_p
     L.gs_last_hip_error.argtypes = []
@@ -351,6 +361,17 @@ def gs_reconstruct_streams(code, pool, shards, erased, shard_bytes, stream=None)
     er, ne = _int_array(erased)
     _check(lib().gs_reconstruct_streams(code.handle, pool.handle, n, _flat_ptrs(shards, code.k + code.m), er, ne,
                                         _size_array(shard_bytes), _stream(stream)), "gs_reconstruct_streams")
+
+
+def gs_recompute_units(n_chunks, recompute_base_s, recompute_growth_s, gather_s, h2d_s, reconstruct_s,
+                       restore_startup_s=0.0):
+    """(r, makespan_s): chunks to recompute, and the modelled recovery time"""
+    costs = RecoveryCosts(recompute_base_s, recompute_growth_s, gather_s, h2d_s, reconstruct_s, restore_startup_s)
+    r = ctypes.c_int()
+    t = ctypes.c_double()
+    _check(lib().gs_recompute_units(n_chunks, ctypes.byref(costs), ctypes.byref(r), ctypes.byref(t)),
+           "gs_recompute_units")
+    return r.value, t.value
 
 
 def gs_coef_words(c):
