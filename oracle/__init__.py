@@ -15,6 +15,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gs_oracle.c")
+_SRC_RDP = os.path.join(_HERE, "gs_rdp_oracle.c")
 _LIB = os.path.join(_HERE, "libgs_oracle.so")
 
 _u8p = ctypes.POINTER(ctypes.c_uint8)
@@ -25,12 +26,13 @@ _intp = ctypes.POINTER(ctypes.c_int)
 
 def build(force=False):
     """Compile the oracle with gcc -O2 (no SIMD flags) if missing or stale."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC),
+                                                                       os.path.getmtime(_SRC_RDP))
     if force or stale:
         tmp = _LIB + ".%d.tmp" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
-             "-o", tmp, _SRC, "-lpthread"])
+             "-o", tmp, _SRC, _SRC_RDP, "-lpthread"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -66,6 +68,9 @@ def lib():
         L.gso_reconstruct.argtypes = [ctypes.c_int, ctypes.c_int, _u8p, _u8pp, _intp,
                                       ctypes.c_int, ctypes.c_size_t]
         L.gso_recompute_units.argtypes = [ctypes.c_int, ctypes.POINTER(_Costs), ctypes.POINTER(ctypes.c_double)]
+        L.gso_rdp_prime.argtypes = [ctypes.c_int]
+        L.gso_rdp_encode.argtypes = [ctypes.c_int, _u8pp, ctypes.c_size_t]
+        L.gso_rdp_reconstruct.argtypes = [ctypes.c_int, _u8pp, _intp, ctypes.c_int, ctypes.c_size_t]
         L.gso_init()
         _lib = L
     return _lib
@@ -207,3 +212,36 @@ def recompute_units(n_chunks, base, growth, gather, h2d, reconstruct, startup=0.
     t = ctypes.c_double()
     r = lib().gso_recompute_units(n_chunks, ctypes.byref(c), ctypes.byref(t))
     return r, t.value
+
+
+def rdp_prime(k):
+    return lib().gso_rdp_prime(k)
+
+
+def rdp_encode(data):
+    """data: list of k equal-length uint8 arrays (length a multiple of p-1)
+    -> [row parity, diagonal parity]."""
+    k, S = len(data), data[0].size
+    for d in data:
+        _check_u8(d, "data shard")
+        assert d.size == S
+    par = [np.zeros(S, np.uint8), np.zeros(S, np.uint8)]
+    if lib().gso_rdp_encode(k, _ptr_array(list(data) + par), S):
+        raise ValueError("bad RDP geometry: k=%d S=%d" % (k, S))
+    return par
+
+
+def rdp_reconstruct(shards, erased):
+    """shards: k data + row parity + diagonal parity; erased ones are rebuilt in place."""
+    k, S = len(shards) - 2, shards[0].size
+    for s in shards:
+        _check_u8(s, "shard")
+        assert s.size == S
+    e = len(erased)
+    er = (ctypes.c_int * max(e, 1))(*erased)
+    rc = lib().gso_rdp_reconstruct(k, _ptr_array(shards), er, e, S)
+    if rc == -3:
+        raise OverflowError("RDP tolerates two erasures")
+    if rc:
+        raise ValueError("bad RDP arguments")
+    return shards

@@ -1,0 +1,165 @@
+/*
+ * gs_rdp_oracle.c -- plain CPU oracle for Row-Diagonal Parity (RDP), the
+ * XOR-only double-parity code that GhostServe offers next to XOR and
+ * Reed-Solomon (Section 2 and Section 4.1 of the paper name it and cite
+ * Corbett et al., "Row-Diagonal Parity for Double Disk Failure Correction";
+ * the geometry below is that publication's, restated).
+ *
+ * TEST INFRASTRUCTURE, like gs_oracle.c: never linked or imported by the HIP
+ * library, shares no code with it.
+ *
+ * Geometry.  p is a prime > 2.  A stripe has p-1 rows and p+1 "disks":
+ *   disks 0 .. p-2   data   (only the first k hold real shards; the others
+ *                            are imaginary all-zero disks when k < p-1)
+ *   disk  p-1        row parity
+ *   disk  p          diagonal parity
+ * A shard of S bytes is cut into p-1 equal blocks of B = S/(p-1) bytes; block
+ * i of a shard is row i.  Block (i, j), j <= p-1, lies on diagonal (i+j) mod p;
+ * diagonal p-1 is the one diagonal that is not stored.
+ *   row parity      R[i] = XOR_{j<=p-2} D[i][j]
+ *   diagonal parity Q[d] = XOR of all blocks (i, j), i <= p-2, j <= p-1, with
+ *                          (i+j) mod p = d,          for d = 0 .. p-2
+ * Reconstruction follows the publication's procedure: a lost diagonal-parity
+ * disk is re-encoded; a single lost data/row disk comes from the row
+ * equations; two lost disks among 0..p-1 are rebuilt by the diagonal walk
+ * (use a diagonal that misses one of the two disks to get a block of the
+ * other, then that block's row to get a block of the first, and so on, two
+ * chains, each ending at the unstored diagonal).
+ *
+ * Pins (tests/test_oracle_rdp.py): row parity == numpy XOR; generator matrix
+ * read out by impulses and checked for rank over GF(2) under every pair of
+ * lost disks (independent elimination); exhaustive search for the unique
+ * completion on the smallest stripe; round trips over every pair of disks for
+ * every k <= 16.  Nothing here is "parity unpinned".
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static int is_prime(int n)
+{
+    if (n < 2) return 0;
+    for (int d = 2; d * d <= n; d++)
+        if (n % d == 0) return 0;
+    return 1;
+}
+
+/* smallest prime p >= max(3, k+1): room for k data disks */
+int gso_rdp_prime(int k)
+{
+    int p = k + 1 < 3 ? 3 : k + 1;
+    while (!is_prime(p)) p++;
+    return p;
+}
+
+static void xor_into(uint8_t *dst, const uint8_t *src, size_t n)
+{
+    for (size_t t = 0; t < n; t++) dst[t] ^= src[t];
+}
+
+/* block (row i) of disk j, or NULL for an imaginary zero disk */
+static uint8_t *blk(uint8_t *const *disk, int k, int p, size_t B, int i, int j)
+{
+    if (j < k) return disk[j] + (size_t)i * B;            /* data shard j        */
+    if (j < p - 1) return NULL;                           /* imaginary zero disk */
+    return disk[k + (j - (p - 1))] + (size_t)i * B;       /* row / diagonal parity */
+}
+
+/* disk[0..k-1] data, disk[k] row parity, disk[k+1] diagonal parity; S bytes each.
+ * Returns 0, -1 if S is not a multiple of p-1 or k is out of range. */
+int gso_rdp_encode(int k, uint8_t *const *disk, size_t S)
+{
+    if (k < 1 || k > 254) return -1;
+    int p = gso_rdp_prime(k);
+    if (S % (size_t)(p - 1)) return -1;
+    size_t B = S / (size_t)(p - 1);
+    memset(disk[k], 0, S);
+    memset(disk[k + 1], 0, S);
+    for (int i = 0; i < p - 1; i++)
+        for (int j = 0; j < k; j++) xor_into(blk(disk, k, p, B, i, p - 1), blk(disk, k, p, B, i, j), B);
+    for (int i = 0; i < p - 1; i++)
+        for (int j = 0; j <= p - 1; j++) {
+            int d = (i + j) % p;
+            const uint8_t *b = blk(disk, k, p, B, i, j);
+            if (d == p - 1 || b == NULL) continue;
+            xor_into(blk(disk, k, p, B, d, p), b, B);
+        }
+    return 0;
+}
+
+/* recompute block (i, j) from its row: XOR of the other p-1 blocks of row i among disks 0..p-1 */
+static void from_row(uint8_t *const *disk, int k, int p, size_t B, int i, int j)
+{
+    uint8_t *dst = blk(disk, k, p, B, i, j);
+    memset(dst, 0, B);
+    for (int c = 0; c <= p - 1; c++) {
+        const uint8_t *b = blk(disk, k, p, B, i, c);
+        if (c != j && b) xor_into(dst, b, B);
+    }
+}
+
+/* recompute block (i, j) from its diagonal d = (i+j) mod p (d != p-1):
+ * diagonal parity block d XOR the other blocks of that diagonal */
+static void from_diagonal(uint8_t *const *disk, int k, int p, size_t B, int i, int j)
+{
+    int d = (i + j) % p;
+    uint8_t *dst = blk(disk, k, p, B, i, j);
+    memcpy(dst, blk(disk, k, p, B, d, p), B);
+    for (int c = 0; c <= p - 1; c++) {
+        int r = ((d - c) % p + p) % p;
+        if (c == j || r == p - 1) continue;
+        const uint8_t *b = blk(disk, k, p, B, r, c);
+        if (b) xor_into(dst, b, B);
+    }
+}
+
+/* erased: shard indices in [0, k+2) (k = row parity, k+1 = diagonal parity).
+ * Returns 0; -1 bad arguments; -3 more than two erasures. */
+int gso_rdp_reconstruct(int k, uint8_t *const *disk, const int *erased, int e, size_t S)
+{
+    if (k < 1 || k > 254 || e < 0) return -1;
+    int p = gso_rdp_prime(k);
+    if (S % (size_t)(p - 1)) return -1;
+    size_t B = S / (size_t)(p - 1);
+    int lost[2] = {-1, -1}, n = 0, diag_lost = 0;
+    for (int x = 0; x < e; x++) {
+        if (erased[x] < 0 || erased[x] > k + 1) return -1;
+        for (int y = 0; y < x; y++)
+            if (erased[y] == erased[x]) return -1;
+    }
+    if (e > 2) return -3;
+    for (int x = 0; x < e; x++) {
+        if (erased[x] == k + 1) diag_lost = 1;
+        else lost[n++] = erased[x] < k ? erased[x] : p - 1;   /* stripe disk number */
+    }
+    if (n == 1) {
+        for (int i = 0; i < p - 1; i++) from_row(disk, k, p, B, i, lost[0]);
+    } else if (n == 2) {
+        /* diagonal walk.  Diagonal d has no block on disk (d+1) mod p.  Start each
+         * chain on the diagonal that misses one lost disk, alternate diagonal and
+         * row steps, stop when the next diagonal is the unstored one. */
+        for (int s = 0; s < 2; s++) {
+            int a = lost[s], b = lost[1 - s];          /* first diagonal misses disk a */
+            int d = ((a - 1) % p + p) % p;
+            while (d != p - 1) {
+                int i = ((d - b) % p + p) % p;         /* row of diagonal d on disk b */
+                from_diagonal(disk, k, p, B, i, b);
+                from_row(disk, k, p, B, i, a);
+                d = (i + a) % p;                       /* diagonal of the block just rebuilt */
+            }
+        }
+    }
+    if (diag_lost) {
+        /* re-encode the diagonal parity from the (now complete) stripe */
+        memset(disk[k + 1], 0, S);
+        for (int i = 0; i < p - 1; i++)
+            for (int j = 0; j <= p - 1; j++) {
+                int d = (i + j) % p;
+                const uint8_t *b = blk(disk, k, p, B, i, j);
+                if (d == p - 1 || b == NULL) continue;
+                xor_into(blk(disk, k, p, B, d, p), b, B);
+            }
+    }
+    return 0;
+}

@@ -1,0 +1,134 @@
+"""Pins for the RDP oracle (row-diagonal parity; the paper's Section 2 cites
+it as the XOR-only code that survives any two simultaneous shard failures).
+
+What fixes the expected values here: row parity is the plain XOR of the data;
+the code must be MDS for two erasures -- checked (a) by reading the code's
+generator out with impulses and testing, with an independent GF(2)
+elimination, that the surviving symbols determine the data under every pair of
+lost disks, and (b) by exhaustive search for completions on small stripes --
+and reconstruction must return the original bytes for every pair of disks."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import inputs
+
+
+def gf2_rank(M):
+    M = (np.array(M, dtype=np.uint8) & 1).copy()
+    rank = 0
+    rows, cols = M.shape
+    for c in range(cols):
+        piv = None
+        for r in range(rank, rows):
+            if M[r, c]:
+                piv = r
+                break
+        if piv is None:
+            continue
+        M[[rank, piv]] = M[[piv, rank]]
+        for r in range(rows):
+            if r != rank and M[r, c]:
+                M[r] ^= M[rank]
+        rank += 1
+    return rank
+
+
+def test_prime_choice():
+    assert [oracle.rdp_prime(k) for k in (1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 16)] == \
+        [3, 3, 5, 5, 7, 7, 11, 11, 11, 13, 13, 17]
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 6, 8, 10, 16])
+def test_row_parity_is_xor_and_length_must_divide(k):
+    p = oracle.rdp_prime(k)
+    S = (p - 1) * 37
+    data = [inputs.uniform_bytes_np(3 * k + j, S) for j in range(k)]
+    par = oracle.rdp_encode(data)
+    assert np.array_equal(par[0], np.bitwise_xor.reduce(np.stack(data), axis=0))
+    with pytest.raises(ValueError):
+        oracle.rdp_encode([d[:S - 1].copy() for d in data])
+
+
+@pytest.mark.parametrize("k", [2, 3, 4, 6, 8, 10])
+def test_generator_read_out_by_impulses_is_mds_for_two_erasures(k):
+    """One bit per block: encode unit vectors to get the (k+2)(p-1) x k(p-1)
+    generator over GF(2); losing any two disks must leave full column rank."""
+    p = oracle.rdp_prime(k)
+    rows = p - 1
+    n_in = k * rows
+    G = np.zeros(((k + 2) * rows, n_in), np.uint8)
+    for j in range(k):
+        for i in range(rows):
+            data = [np.zeros(rows, np.uint8) for _ in range(k)]
+            data[j][i] = 1
+            par = oracle.rdp_encode(data)
+            col = np.concatenate(data + par)
+            G[:, j * rows + i] = col
+    # systematic part is the identity
+    assert np.array_equal(G[:n_in], np.eye(n_in, dtype=np.uint8))
+    # linear: a random bit vector encodes to G @ x over GF(2)
+    rng = np.random.default_rng(k)
+    x = rng.integers(0, 2, n_in, dtype=np.uint8)
+    data = [np.ascontiguousarray(x[j * rows:(j + 1) * rows]) for j in range(k)]
+    par = oracle.rdp_encode(data)
+    assert np.array_equal(np.concatenate(data + par), (G.astype(np.int64) @ x) % 2)
+    for a, b in itertools.combinations(range(k + 2), 2):
+        keep = [r for d in range(k + 2) if d not in (a, b) for r in range(d * rows, (d + 1) * rows)]
+        assert gf2_rank(G[keep]) == n_in, (k, a, b)
+    # and it is not 3-erasure tolerant (it has only two parity disks)
+    keep = [r for d in range(3, k + 2) for r in range(d * rows, (d + 1) * rows)]
+    if k >= 3:
+        assert gf2_rank(G[keep]) < n_in
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_exhaustive_search_finds_exactly_one_completion(k):
+    """Smallest stripes, one bit per block: with two data disks gone, try every
+    assignment of their bits; exactly one is consistent with both parities."""
+    p = oracle.rdp_prime(k)
+    rows = p - 1
+    rng = np.random.default_rng(40 + k)
+    for trial in range(3):
+        data = [rng.integers(0, 2, rows, dtype=np.uint8) for _ in range(k)]
+        par = oracle.rdp_encode(data)
+        for a, b in itertools.combinations(range(k), 2):
+            hits = []
+            for bits in itertools.product((0, 1), repeat=2 * rows):
+                cand = [d.copy() for d in data]
+                cand[a] = np.array(bits[:rows], np.uint8)
+                cand[b] = np.array(bits[rows:], np.uint8)
+                cp = oracle.rdp_encode(cand)
+                if np.array_equal(cp[0], par[0]) and np.array_equal(cp[1], par[1]):
+                    hits.append(bits)
+            assert len(hits) == 1
+            assert hits[0] == tuple(data[a]) + tuple(data[b])
+
+
+@pytest.mark.parametrize("k", list(range(1, 17)))
+def test_round_trip_every_single_and_double_erasure(k):
+    p = oracle.rdp_prime(k)
+    S = (p - 1) * 16 + 0
+    data = [inputs.kv_bytes_np(50 * k + j, S, "bf16", 1.0) for j in range(k)]
+    full = [d.copy() for d in data] + oracle.rdp_encode(data)
+    pats = [()] + list(itertools.combinations(range(k + 2), 1)) + list(itertools.combinations(range(k + 2), 2))
+    for pat in pats:
+        for order in (pat, pat[::-1]):
+            work = [x.copy() for x in full]
+            for r in order:
+                work[r][:] = 0xA5
+            oracle.rdp_reconstruct(work, list(order))
+            for r in range(k + 2):
+                assert np.array_equal(work[r], full[r]), (k, order, r)
+
+
+def test_reconstruct_errors():
+    data = [inputs.uniform_bytes_np(j, 64) for j in range(4)]
+    full = data + oracle.rdp_encode(data)
+    with pytest.raises(OverflowError):
+        oracle.rdp_reconstruct([x.copy() for x in full], [0, 1, 2])
+    for bad in ([0, 0], [6], [-1]):
+        with pytest.raises(ValueError):
+            oracle.rdp_reconstruct([x.copy() for x in full], bad)
