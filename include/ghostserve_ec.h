@@ -58,8 +58,10 @@ enum gs_status {
 
 enum gs_kind {
     GS_CAUCHY = 0,      /* closed form described above                                      */
-    GS_VANDERMONDE = 1  /* systematic form of the Vandermonde matrix over points 0..k+m-1,
+    GS_VANDERMONDE = 1, /* systematic form of the Vandermonde matrix over points 0..k+m-1,
                            with the same normalisation; yields the identical matrix        */
+    GS_RDP = 2          /* row-diagonal parity: XOR-only, exactly two parity shards; see
+                           the RDP section below                                           */
 };
 
 /* Largest code a single kernel launch covers; wider codes run as several
@@ -182,6 +184,33 @@ int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int
                          gs_step_graph **out);
 int gs_step_graph_launch(gs_step_graph *g, void *stream);
 void gs_step_graph_destroy(gs_step_graph *g);
+
+/* ---- RDP (row-diagonal parity) -----------------------------------------------
+ * The third code the paper offers (Section 2, Section 4.1): XOR-only, two
+ * parity shards, any two lost shards recoverable.  gs_make_code(k, 2, GS_RDP),
+ * 1 <= k <= 16.  Geometry as published for RDP: p = smallest prime >= max(3,
+ * k+1); every shard is p-1 equal blocks ("rows"); data shards beyond k up to
+ * p-1 are imaginary zeros; shard ids: 0..k-1 data, k row parity, k+1 diagonal
+ * parity.  Block (i, j) of the first p "disks" (data + row parity) lies on
+ * diagonal (i+j) mod p; diagonal parity block d is the XOR of diagonal d,
+ * d = 0..p-2.
+ * An RDP code works with gs_encode (parity[0] = row parity, parity[1] =
+ * diagonal parity) and gs_reconstruct, with the same argument conventions,
+ * except that shard_bytes must be a multiple of 16*(p-1) (else GS_EINVAL).
+ * Its rows span the whole shard, so it has no paged, chunked-pipeline or
+ * grouped form: those entry points, gs_code_matrix and gs_decode_matrix
+ * return GS_EINVAL for it.  A single lost shard other than the diagonal
+ * parity is rebuilt from the row equations alone (the diagonal parity shard
+ * is then not read and may be NULL). */
+int gs_rdp_prime(const gs_code *code, int *p_out);
+/* The XOR plan the kernels execute (host only; lets the planning be checked
+ * without a GPU).  n_erased = 0 asks for the encode plan.  inputs_out (room
+ * for 18 shard ids) lists the shards that are read, outputs_out (room for 2)
+ * the shards that are written, and mask_out (room for 18*16 words) holds, for
+ * input s and row r, at [s*(p-1)+r], a bit set at position x*(p-1)+q when that
+ * block is part of the XOR that yields block q of outputs_out[x]. */
+int gs_rdp_plan(const gs_code *code, const int *erased, int n_erased, int *inputs_out, int *n_inputs_out,
+                int *outputs_out, int *n_outputs_out, uint32_t *mask_out);
 
 /* ---- many chunks at once ---------------------------------------------------
  * Section 5: recovery reconstructs many chunks concurrently ("each chunk is

@@ -14,10 +14,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libghostserve_ec.so")
 
 GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP = 0, -1, -2, -3, -4, -5
-GS_CAUCHY, GS_VANDERMONDE = 0, 1
+GS_CAUCHY, GS_VANDERMONDE, GS_RDP = 0, 1, 2
 
 EXPORTS = [
-    "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix",
+    "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_rdp_prime", "gs_rdp_plan",
     "gs_encode", "gs_encode_paged", "gs_reconstruct",
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
     "gs_pipe_done_event",
@@ -71,6 +71,8 @@ def lib():
     L.gs_code_params.argtypes = [_vp, _intp, _intp]
     L.gs_code_matrix.argtypes = [_vp, _u8p]
     L.gs_decode_matrix.argtypes = [_vp, _intp, ctypes.c_int, _u8p, _intp]
+    L.gs_rdp_prime.argtypes = [_vp, _intp]
+    L.gs_rdp_plan.argtypes = [_vp, _intp, ctypes.c_int, _intp, _intp, _intp, _intp, ctypes.POINTER(ctypes.c_uint32)]
     L.gs_encode.argtypes = [_vp, _vpp, _vpp, ctypes.c_size_t, _vp]
     L.gs_encode_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
                                   ctypes.c_int, _vpp, _vp]
@@ -188,6 +190,24 @@ def gs_code_matrix(code):
     P = np.zeros((code.m, code.k), np.uint8)
     _check(lib().gs_code_matrix(code.handle, P.ctypes.data_as(_u8p)), "gs_code_matrix")
     return P
+
+
+def gs_rdp_prime(code):
+    p = ctypes.c_int()
+    _check(lib().gs_rdp_prime(code.handle, ctypes.byref(p)), "gs_rdp_prime")
+    return p.value
+
+
+def gs_rdp_plan(code, erased=()):
+    """(inputs, outputs, mask[len(inputs)][p-1]) of the encode plan (no erasures) or a rebuild plan"""
+    er, n = _int_array(erased)
+    ins, outs = (ctypes.c_int * 18)(), (ctypes.c_int * 2)()
+    ni, no = ctypes.c_int(), ctypes.c_int()
+    mask = (ctypes.c_uint32 * (18 * 16))()
+    _check(lib().gs_rdp_plan(code.handle, er, n, ins, ctypes.byref(ni), outs, ctypes.byref(no), mask), "gs_rdp_plan")
+    rows = gs_rdp_prime(code) - 1
+    m = np.array(list(mask[: ni.value * rows]), dtype=np.uint32).reshape(ni.value, rows)
+    return list(ins[: ni.value]), list(outs[: no.value]), m
 
 
 def gs_decode_matrix(code, erased):

@@ -97,6 +97,23 @@ int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vec
     return GS_OK;
 }
 
+static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
+                           size_t shard_bytes, hipStream_t stream)
+{
+    std::vector<uint8_t> lost;
+    const int rc = check_erasures(code, erased, n_erased, lost);
+    if (rc != GS_OK) return rc;
+    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
+    if (shard_bytes % (16u * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    RdpPlan plan;
+    if (!rdp_decode_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+    for (int s : plan.inputs)
+        if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
+    for (int s : plan.outputs)
+        if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
+    return hip_status(launch_rdp_xor(plan, shards, shard_bytes, current_shape(), stream));
+}
+
 }  // namespace gs
 
 using namespace gs;
@@ -108,13 +125,15 @@ int gs_make_code(int k, int m, int kind, gs_code **out)
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (k < 1 || m < 1 || k + m > 256) return GS_EINVAL;
-    if (kind != GS_CAUCHY && kind != GS_VANDERMONDE) return GS_EINVAL;
+    if (kind != GS_CAUCHY && kind != GS_VANDERMONDE && kind != GS_RDP) return GS_EINVAL;
+    if (kind == GS_RDP && (m != 2 || k > kRdpMaxPrime - 1)) return GS_EINVAL;
     gs_code *c = new (std::nothrow) gs_code;
     if (c == nullptr) return GS_ENOMEM;
     c->k = k;
     c->m = m;
     c->kind = kind;
-    c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
+    if (kind == GS_RDP) c->rdp_encode = rdp_encode_plan(k);
+    else c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
     *out = c;
     return GS_OK;
 }
@@ -129,9 +148,39 @@ int gs_code_params(const gs_code *code, int *k, int *m)
     return GS_OK;
 }
 
+int gs_rdp_prime(const gs_code *code, int *p_out)
+{
+    if (code == nullptr || p_out == nullptr || !code->is_rdp()) return GS_EINVAL;
+    *p_out = code->rdp_encode.p;
+    return GS_OK;
+}
+
+int gs_rdp_plan(const gs_code *code, const int *erased, int n_erased, int *inputs_out, int *n_inputs_out,
+                int *outputs_out, int *n_outputs_out, uint32_t *mask_out)
+{
+    if (code == nullptr || !code->is_rdp() || inputs_out == nullptr || n_inputs_out == nullptr ||
+        outputs_out == nullptr || n_outputs_out == nullptr || mask_out == nullptr)
+        return GS_EINVAL;
+    RdpPlan plan;
+    if (n_erased == 0) {
+        plan = code->rdp_encode;
+    } else {
+        std::vector<uint8_t> lost;
+        const int rc = check_erasures(code, erased, n_erased, lost);
+        if (rc != GS_OK) return rc;
+        if (!rdp_decode_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+    }
+    *n_inputs_out = static_cast<int>(plan.inputs.size());
+    *n_outputs_out = static_cast<int>(plan.outputs.size());
+    std::copy(plan.inputs.begin(), plan.inputs.end(), inputs_out);
+    std::copy(plan.outputs.begin(), plan.outputs.end(), outputs_out);
+    std::copy(plan.mask.begin(), plan.mask.end(), mask_out);
+    return GS_OK;
+}
+
 int gs_code_matrix(const gs_code *code, uint8_t *P_out)
 {
-    if (code == nullptr || P_out == nullptr) return GS_EINVAL;
+    if (code == nullptr || P_out == nullptr || code->is_rdp()) return GS_EINVAL;
     std::memcpy(P_out, code->P.data(), code->P.size());
     return GS_OK;
 }
@@ -139,7 +188,7 @@ int gs_code_matrix(const gs_code *code, uint8_t *P_out)
 int gs_decode_matrix(const gs_code *code, const int *erased, int n_erased, uint8_t *R_out,
                      int *survivors_out)
 {
-    if (code == nullptr) return GS_EINVAL;
+    if (code == nullptr || code->is_rdp()) return GS_EINVAL;
     std::vector<uint8_t> R;
     std::vector<int> surv;
     const int rc = decode_matrix(code, erased, n_erased, R, surv);
@@ -158,6 +207,14 @@ int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
         if (data[j] == nullptr || !aligned16(data[j])) return GS_EINVAL;
     for (int i = 0; i < code->m; ++i)
         if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
+    if (code->is_rdp()) {
+        if (shard_bytes % (16u * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+        std::vector<const void *> shards(data, data + code->k);
+        shards.push_back(parity[0]);
+        shards.push_back(parity[1]);
+        return hip_status(launch_rdp_xor(code->rdp_encode, shards.data(), shard_bytes, current_shape(),
+                                         static_cast<hipStream_t>(stream)));
+    }
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,
                         static_cast<hipStream_t>(stream));
 }
@@ -167,6 +224,7 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
                     void *const *parity, void *stream)
 {
     if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
+    if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard; it has no paged form
     if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
     if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
     if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
@@ -194,6 +252,7 @@ int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, 
                    size_t shard_bytes, void *stream)
 {
     if (code == nullptr || shards == nullptr) return GS_EINVAL;
+    if (code->is_rdp()) return rdp_reconstruct(code, shards, erased, n_erased, shard_bytes, static_cast<hipStream_t>(stream));
     std::vector<uint8_t> R;
     std::vector<int> surv;
     const int rc = decode_matrix(code, erased, n_erased, R, surv);

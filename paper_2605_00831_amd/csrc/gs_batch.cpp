@@ -109,7 +109,7 @@ int gs_batch_create(const gs_code *code, int max_chunks, gs_batch **out)
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || max_chunks < 1 || max_chunks > 65535) return GS_EINVAL;
-    if (code->k > kLaunchMaxK || code->m > kLaunchMaxM) return GS_EINVAL;
+    if (code->is_rdp() || code->k > kLaunchMaxK || code->m > kLaunchMaxM) return GS_EINVAL;
     gs_batch *b = new (std::nothrow) gs_batch;
     if (b == nullptr) return GS_ENOMEM;
     b->code = code;

@@ -6,10 +6,13 @@
 
 #include "gs_gf.h"
 #include "gs_launch.h"
+#include "gs_rdp.h"
 
 struct gs_code {
     int k = 0, m = 0, kind = 0;
-    gs::Matrix P;  // m x k parity block, row-major
+    gs::Matrix P;  // m x k parity block, row-major (empty for RDP)
+    gs::RdpPlan rdp_encode;  // RDP only
+    bool is_rdp() const { return kind == 2; }
 };
 
 namespace gs {

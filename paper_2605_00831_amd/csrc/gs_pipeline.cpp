@@ -63,6 +63,7 @@ int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe *
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || chunk_bytes == 0 || chunk_bytes % 16 != 0 || depth < 2 || depth > 64) return GS_EINVAL;
+    if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard: no chunked form
     gs_pipe *p = new (std::nothrow) gs_pipe;
     if (p == nullptr) return GS_ENOMEM;
     p->code = code;
@@ -203,7 +204,7 @@ int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int
 {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
-    if (code == nullptr || n_planes < 1 || pages_per_shard < 1) return GS_EINVAL;
+    if (code == nullptr || n_planes < 1 || pages_per_shard < 1 || code->is_rdp()) return GS_EINVAL;
     gs_step_graph *g = new (std::nothrow) gs_step_graph;
     if (g == nullptr) return GS_ENOMEM;
     hipStream_t s = nullptr;

@@ -1,0 +1,139 @@
+"""GPU parity for the RDP code (XOR-only double parity) against the RDP
+oracle: encode, and reconstruction under every single and double erasure."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+CANARY, PAD = 0xC7, 256
+
+
+@pytest.fixture(scope="module")
+def gs():
+    from paper_2605_00831_amd import binding
+    binding.lib()
+    binding.gs_set_launch_shape()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def out_buf(n):
+    return torch.full((n + PAD,), CANARY, dtype=torch.uint8, device="cuda")
+
+
+def check(buf, want):
+    got = buf.cpu().numpy()
+    assert np.array_equal(got[:want.size], want)
+    assert (got[want.size:] == CANARY).all()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 8, 10, 11, 12, 16])
+def test_rdp_encode_and_every_erasure_pattern(gs, k):
+    code = gs.gs_make_code(k, 2, gs.GS_RDP)
+    p = gs.gs_rdp_prime(code)
+    rows = p - 1
+    for nvb in (1, 63, 64 * 4 * 3 + 5, 64 * 4 * 32 * 2 + 64 * 7 + 3):   # vectors per block: tiny, ragged, several super-tiles
+        S = rows * 16 * nvb
+        if k * S > (48 << 20):
+            continue
+        data_np = [inputs.kv_bytes_np(17 * k + j, S, "bf16", 1.0) for j in range(k)]
+        want = oracle.rdp_encode(data_np)
+        full = data_np + want
+        data = [dev(x) for x in data_np]
+        par = [out_buf(S), out_buf(S)]
+        gs.gs_encode(code, data, par, S)
+        torch.cuda.synchronize()
+        check(par[0], want[0])
+        check(par[1], want[1])
+        pats = list(itertools.combinations(range(k + 2), 1)) + list(itertools.combinations(range(k + 2), 2))
+        if nvb > 1000:
+            pats = pats[:: max(1, len(pats) // 12)]
+        for pat in pats:
+            shards = []
+            for r in range(k + 2):
+                if r in pat:
+                    t = out_buf(S)
+                    t[:S] = 0xA5
+                else:
+                    t = dev(full[r])
+                shards.append(t)
+            gs.gs_reconstruct(code, shards, list(pat), S)
+            torch.cuda.synchronize()
+            for r in range(k + 2):
+                if r in pat:
+                    check(shards[r], full[r])
+                else:
+                    assert np.array_equal(shards[r].cpu().numpy(), full[r])
+            # the oracle's diagonal walk gives the same bytes
+            work = [x.copy() for x in full]
+            for r in pat:
+                work[r][:] = 0xA5
+            oracle.rdp_reconstruct(work, list(pat))
+            for r in pat:
+                assert np.array_equal(work[r], full[r])
+
+
+def test_rdp_length_and_erasure_errors(gs):
+    code = gs.gs_make_code(4, 2, gs.GS_RDP)     # p = 5: shard length must be a multiple of 64
+    d = [torch.zeros(256, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    p = [out_buf(256), out_buf(256)]
+    for bad in (100, 48, 65):
+        with pytest.raises(gs.GsError) as e:
+            gs.gs_encode(code, d, p, bad)
+        assert e.value.status == gs.GS_EINVAL
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_reconstruct(code, d + p, [0, 1, 2], 256)
+    assert e.value.status == gs.GS_ETOOMANY
+    gs.gs_encode(code, d, p, 0)
+    gs.gs_reconstruct(code, d + p, [], 256)
+    # one lost data shard: the diagonal parity is not needed
+    gs.gs_encode(code, d, p, 256)
+    gs.gs_reconstruct(code, d + [p[0], None], [2], 256)
+    torch.cuda.synchronize()
+    assert (p[0].cpu().numpy()[256:] == CANARY).all()
+
+
+def test_rdp_full_shards_of_the_8b_workload_shape(gs):
+    """k=4 shards of 1 GiB bf16 KV (an eighth of the bulk workload), p=5:
+    windows against the oracle are not possible (rows span the shard), so the
+    whole parity is compared with torch XORs of the blocks the definition names."""
+    k, S = 4, 1 << 30
+    code = gs.gs_make_code(k, 2, gs.GS_RDP)
+    p = gs.gs_rdp_prime(code)
+    rows, B = p - 1, S // (p - 1)
+    buf = inputs.kv_bytes_device(inputs.config_seed("llama8b_prefill"), k * S, "bf16", 0.5, "cuda")
+    data = [buf[j * S:(j + 1) * S] for j in range(k)]
+    par = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    gs.gs_encode(code, data, par, S)
+    torch.cuda.synchronize()
+    row = data[0] ^ data[1] ^ data[2] ^ data[3]
+    assert torch.equal(par[0], row)
+    disks = data + [row]
+    diag = torch.zeros(S, dtype=torch.uint8, device="cuda")
+    for i in range(rows):
+        for j in range(p):
+            d = (i + j) % p
+            if d != p - 1:
+                diag[d * B:(d + 1) * B] ^= disks[j][i * B:(i + 1) * B]
+    assert torch.equal(par[1], diag)
+    # a sample of the same stripe through the oracle: take every 2^14-th vector of each block
+    step = 1 << 14
+    sample = lambda t: np.ascontiguousarray(t.view(rows, B // 16, 16)[:, ::step, :].reshape(-1).cpu().numpy())
+    want = oracle.rdp_encode([sample(d) for d in data])
+    assert np.array_equal(sample(par[0]), want[0]) and np.array_equal(sample(par[1]), want[1])
+    keep = [data[0].clone(), data[3].clone()]
+    data[0].fill_(0xA5)
+    data[3].fill_(0xA5)
+    gs.gs_reconstruct(code, data + par, [0, 3], S)
+    torch.cuda.synchronize()
+    assert torch.equal(data[0], keep[0]) and torch.equal(data[3], keep[1])

@@ -1,0 +1,75 @@
+"""CPU-only check of the library's RDP planning (encode masks by the closed
+form, rebuild masks by GF(2) elimination on the parity equations) against the
+RDP oracle (diagonal walk): executing the plan's XORs in numpy on the oracle's
+stripe must give the bytes the oracle gives."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_00831_amd import binding as gs
+from paper_2605_00831_amd import inputs
+
+
+def run_plan(plan, shards, p):
+    ins, outs, mask = plan
+    rows = p - 1
+    B = shards[0].size // rows
+    result = {o: np.zeros(shards[0].size, np.uint8) for o in outs}
+    for s, shard in enumerate(ins):
+        for r in range(rows):
+            blk = shards[shard][r * B:(r + 1) * B]
+            for x, o in enumerate(outs):
+                for q in range(rows):
+                    if mask[s, r] >> (x * rows + q) & 1:
+                        result[o][q * B:(q + 1) * B] ^= blk
+    return result
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 6, 8, 10, 12, 16])
+def test_plans_reproduce_the_oracle(k):
+    code = gs.gs_make_code(k, 2, gs.GS_RDP)
+    p = gs.gs_rdp_prime(code)
+    assert p == oracle.rdp_prime(k)
+    S = (p - 1) * 5
+    data = [inputs.uniform_bytes_np(9 * k + j, S) for j in range(k)]
+    par = oracle.rdp_encode(data)
+    full = data + par
+    enc = run_plan(gs.gs_rdp_plan(code), full, p)
+    assert np.array_equal(enc[k], par[0]) and np.array_equal(enc[k + 1], par[1])
+    pats = list(itertools.combinations(range(k + 2), 1)) + list(itertools.combinations(range(k + 2), 2))
+    for pat in pats:
+        for order in (pat, pat[::-1]):
+            plan = gs.gs_rdp_plan(code, order)
+            assert plan[1] == list(order)
+            assert not set(plan[0]) & set(order)            # lost shards are never read
+            poisoned = [x.copy() for x in full]
+            for r in order:
+                poisoned[r][:] = 0xA5
+            got = run_plan(plan, poisoned, p)
+            for r in order:
+                assert np.array_equal(got[r], full[r]), (k, order, r)
+    # a single lost data or row-parity shard never touches the diagonal parity
+    for r in range(k + 1):
+        assert k + 1 not in gs.gs_rdp_plan(code, [r])[0]
+
+
+def test_rdp_code_rules():
+    for k, m in [(17, 2), (4, 1), (4, 3), (0, 2)]:
+        with pytest.raises(gs.GsError):
+            gs.gs_make_code(k, m, gs.GS_RDP)
+    code = gs.gs_make_code(4, 2, gs.GS_RDP)
+    with pytest.raises(gs.GsError):
+        gs.gs_code_matrix(code)
+    with pytest.raises(gs.GsError):
+        gs.gs_decode_matrix(code, [0])
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_rdp_plan(code, [0, 1, 2])
+    assert e.value.status == gs.GS_ETOOMANY
+    with pytest.raises(gs.GsError):
+        gs.gs_rdp_prime(gs.gs_make_code(4, 2))
+    with pytest.raises(gs.GsError):
+        gs.gs_pipe_create(code, 4096, 2)
+    with pytest.raises(gs.GsError):
+        gs.gs_batch_create(code, 4)
