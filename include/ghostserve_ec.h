@@ -123,6 +123,20 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
                     const int32_t *table, int pages_per_shard,
                     void *const *parity, void *stream);
 
+/* Reconstruct in the same paged geometry (Alg. 2 on a paged KV pool): data
+ * shard j is the pages of table row j; parity shard i is the dense buffer
+ * parity[i] in the layout gs_encode_paged writes.  A lost data shard is
+ * rebuilt INTO the pages its table row names (the pages the restarted engine
+ * allocated for it; entries outside [0, pages_per_plane) are skipped), a lost
+ * parity shard into parity[i].  The k lowest-numbered surviving shards are
+ * read; parity entries that are neither read nor written may be NULL.  Pages
+ * of surviving shards are never written.  Same limits and error rules as
+ * gs_encode_paged and gs_reconstruct. */
+int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int n_planes,
+                         size_t page_bytes, int64_t pages_per_plane,
+                         const int32_t *table, int pages_per_shard,
+                         void *const *parity, const int *erased, int n_erased, void *stream);
+
 /* ---- reconstruct -----------------------------------------------------------
  * Alg. 2, "KV = EC.reconstruct(KV, P)".
  *   shards   HOST array of k+m DEVICE pointers (0..k-1 data, k..k+m-1 parity),

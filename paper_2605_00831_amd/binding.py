@@ -18,7 +18,7 @@ GS_CAUCHY, GS_VANDERMONDE, GS_RDP = 0, 1, 2
 
 EXPORTS = [
     "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_rdp_prime", "gs_rdp_plan",
-    "gs_encode", "gs_encode_paged", "gs_reconstruct",
+    "gs_encode", "gs_encode_paged", "gs_reconstruct", "gs_reconstruct_paged",
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
     "gs_pipe_done_event",
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
@@ -77,6 +77,8 @@ def lib():
     L.gs_encode_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
                                   ctypes.c_int, _vpp, _vp]
     L.gs_reconstruct.argtypes = [_vp, _vpp, _intp, ctypes.c_int, ctypes.c_size_t, _vp]
+    L.gs_reconstruct_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
+                                       ctypes.c_int, _vpp, _intp, ctypes.c_int, _vp]
     L.gs_pipe_create.argtypes = [_vp, ctypes.c_size_t, ctypes.c_int, ctypes.POINTER(_vp)]
     L.gs_pipe_destroy.argtypes = [_vp]
     L.gs_pipe_destroy.restype = None
@@ -232,6 +234,16 @@ def gs_encode_paged(code, plane_base, n_planes, page_bytes, pages_per_plane, tab
     _check(lib().gs_encode_paged(code.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane,
                                  _ptr(table), pages_per_shard, _ptr_array(parity), _stream(stream)),
            "gs_encode_paged")
+
+
+def gs_reconstruct_paged(code, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                         parity, erased, stream=None):
+    if len(parity) != code.m:
+        raise ValueError("need m parity pointers")
+    er, n = _int_array(erased)
+    _check(lib().gs_reconstruct_paged(code.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane,
+                                      _ptr(table), pages_per_shard, _ptr_array(parity), er, n, _stream(stream)),
+           "gs_reconstruct_paged")
 
 
 def gs_reconstruct(code, shards, erased, shard_bytes, stream=None):

@@ -50,6 +50,26 @@ int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, vo
     return GS_OK;
 }
 
+// paged form of apply_matrix: streams are table rows or dense buffers
+static int apply_matrix_paged(int rows, int cols, const uint8_t *C, const void *const *plane_base, int n_planes,
+                              size_t page_bytes, int64_t pages_per_plane, const int32_t *table,
+                              int pages_per_shard, const PagedStream *in, const PagedStream *out,
+                              hipStream_t stream)
+{
+    const LaunchShape shape = current_shape();
+    for (int r0 = 0; r0 < rows; r0 += kLaunchMaxM) {
+        const int nr = std::min(kLaunchMaxM, rows - r0);
+        for (int c0 = 0; c0 < cols; c0 += kLaunchMaxK) {
+            const int nc = std::min(kLaunchMaxK, cols - c0);
+            const hipError_t e = launch_apply_paged(nr, nc, C + static_cast<size_t>(r0) * cols + c0, cols, plane_base,
+                                                    n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                                                    in + c0, out + r0, c0 != 0, shape, stream);
+            if (e != hipSuccess) return hip_status(e);
+        }
+    }
+    return GS_OK;
+}
+
 int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost)
 {
     const int n = code->k + code->m;
@@ -232,20 +252,50 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
     if (pages_per_plane == 0) return GS_EINVAL;
     for (int i = 0; i < code->m; ++i)
         if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
-    const LaunchShape shape = current_shape();
-    const int k = code->k, m = code->m;
-    for (int r0 = 0; r0 < m; r0 += kLaunchMaxM) {
-        const int nr = std::min(kLaunchMaxM, m - r0);
-        for (int c0 = 0; c0 < k; c0 += kLaunchMaxK) {
-            const int nc = std::min(kLaunchMaxK, k - c0);
-            const hipError_t e = launch_apply_paged(
-                nr, nc, code->P.data() + static_cast<size_t>(r0) * k + c0, k, plane_base, n_planes,
-                page_bytes, pages_per_plane, table + static_cast<size_t>(c0) * pages_per_shard,
-                pages_per_shard, parity + r0, c0 != 0, shape, static_cast<hipStream_t>(stream));
-            if (e != hipSuccess) return hip_status(e);
+    std::vector<PagedStream> in(code->k), out(code->m);
+    for (int j = 0; j < code->k; ++j) in[j] = PagedStream{j, nullptr};
+    for (int i = 0; i < code->m; ++i) out[i] = PagedStream{-1, parity[i]};
+    return apply_matrix_paged(code->m, code->k, code->P.data(), plane_base, n_planes, page_bytes, pages_per_plane,
+                              table, pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
+}
+
+int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int n_planes, size_t page_bytes,
+                         int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                         void *const *parity, const int *erased, int n_erased, void *stream)
+{
+    if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
+    if (code->is_rdp()) return GS_EINVAL;
+    if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
+    if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
+    if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc = decode_matrix(code, erased, n_erased, R, surv);
+    if (rc != GS_OK) return rc;
+    if (n_erased == 0 || n_planes == 0 || pages_per_shard == 0) return GS_OK;
+    if (pages_per_plane == 0) return GS_EINVAL;
+    const int k = code->k;
+    std::vector<PagedStream> in(k), out(n_erased);
+    for (int j = 0; j < k; ++j) {
+        if (surv[j] < k) {
+            in[j] = PagedStream{surv[j], nullptr};
+        } else {
+            const void *p = parity[surv[j] - k];
+            if (p == nullptr || !aligned16(p)) return GS_EINVAL;
+            in[j] = PagedStream{-1, p};
         }
     }
-    return GS_OK;
+    for (int x = 0; x < n_erased; ++x) {
+        if (erased[x] < k) {
+            out[x] = PagedStream{erased[x], nullptr};
+        } else {
+            void *p = parity[erased[x] - k];
+            if (p == nullptr || !aligned16(p)) return GS_EINVAL;
+            out[x] = PagedStream{-1, p};
+        }
+    }
+    return apply_matrix_paged(n_erased, k, R.data(), plane_base, n_planes, page_bytes, pages_per_plane, table,
+                              pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
 }
 
 int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,

@@ -57,8 +57,13 @@ struct BatchArgs {
 
 struct PagedArgs {
     const uint8_t *const *plane_base;  // device array [n_planes]
-    const int32_t *table;              // device [k][pps], first row of this launch
+    const int32_t *table;              // device [shards][pps]
+    // every stream is either paged (table row >= 0) or contiguous in the dense
+    // parity layout [plane][slot][page] (row < 0, pointer used)
+    const uint8_t *in_ptr[kLaunchMaxK];
+    int32_t in_row[kLaunchMaxK];
     uint8_t *out[kLaunchMaxM];
+    int32_t out_row[kLaunchMaxM];
     uint32_t tab[kLaunchMaxM][kLaunchMaxK][8];
     uint64_t vecs_per_plane;   // pps * vpp, < 2^32
     uint64_t pages_per_plane;  // valid page ids are [0, pages_per_plane)
@@ -327,21 +332,43 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u) acc[r][u] = Acc4{{0, 0, 0, 0}};
-    if (a.accumulate) {
-#pragma unroll
-        for (int r = 0; r < M; ++r)
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc[r][u] = from_vec(load16<NT>(a.out[r], out_base + v[u]));
-    }
-
-    auto gather = [&](int row, int u) -> u32x4 {
+    // page id of table row `row` at this lane's slot, or -1 if out of range
+    auto page_of = [&](int32_t row, int u) -> int64_t {
         const uint64_t entry = static_cast<uint64_t>(row) * a.pps + slot[u];
         const int64_t page = WAVE_PAGE ? ((ConstTable)a.table)[entry] : a.table[entry];
-        const bool valid = ok[u] && static_cast<uint64_t>(page) < a.pages_per_plane;
+        return static_cast<uint64_t>(page) < a.pages_per_plane ? page : -1;
+    };
+    // stream j at vector u: from its page, or from the dense layout
+    auto gather = [&](int j, int u) -> u32x4 {
+        const int32_t row = a.in_row[j];
+        if (row < 0) {
+            const u32x4 x = load16<NT>(a.in_ptr[j], out_base + v[u]);
+            return ok[u] ? x : u32x4{0, 0, 0, 0};
+        }
+        const int64_t page = page_of(row, u);
+        const bool valid = ok[u] && page >= 0;
         const uint64_t src = valid ? static_cast<uint64_t>(page) * a.vpp + off[u] : 0ull;
         const u32x4 x = load16<NT>(pbase, src);
         return valid ? x : u32x4{0, 0, 0, 0};
     };
+    // where output r of vector u lives; nullptr if it must not be touched
+    auto out_at = [&](int r, int u) -> u32x4 * {
+        const int32_t row = a.out_row[r];
+        if (row < 0) return reinterpret_cast<u32x4 *>(a.out[r]) + out_base + v[u];
+        const int64_t page = page_of(row, u);
+        if (page < 0) return nullptr;
+        return reinterpret_cast<u32x4 *>(const_cast<uint8_t *>(pbase)) + static_cast<uint64_t>(page) * a.vpp + off[u];
+    };
+
+    if (a.accumulate) {
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u32x4 *src = out_at(r, u);
+                if (ok[u] && src != nullptr) acc[r][u] = from_vec(NT ? __builtin_nontemporal_load(src) : *src);
+            }
+    }
 
     int j = 0;
     for (; j + kBatch <= a.k; j += kBatch) {
@@ -363,8 +390,13 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
 #pragma unroll
     for (int r = 0; r < M; ++r)
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(a.out[r], out_base + v[u], to_vec(acc[r][u]));
+        for (int u = 0; u < U; ++u) {
+            u32x4 *dst = out_at(r, u);
+            if (ok[u] && dst != nullptr) {
+                if (NT) __builtin_nontemporal_store(to_vec(acc[r][u]), dst);
+                else *dst = to_vec(acc[r][u]);
+            }
+        }
 }
 
 // Paged gather: blockIdx.y is the plane; blockIdx.x walks the plane's
@@ -608,7 +640,7 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
                               const void *const *plane_base_dev, int n_planes,
                               size_t page_bytes, int64_t pages_per_plane,
                               const int32_t *table_dev, int pages_per_shard,
-                              void *const *out, bool accumulate,
+                              const PagedStream *in, const PagedStream *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream)
 {
     if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
@@ -618,7 +650,16 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     const uint64_t vecs = vpp * static_cast<uint64_t>(pages_per_shard);
     if (vpp >= (1ull << 32) || vecs >= (1ull << 32)) return hipErrorInvalidValue;
     PagedArgs a;
-    const bool row0_xor = fill_rows(a, rows, k, coef, coef_stride, out);
+    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
+    fill_tables(a, p, rows, k, coef, coef_stride);
+    for (int j = 0; j < kLaunchMaxK; ++j) {
+        a.in_row[j] = j < k ? in[j].table_row : -1;
+        a.in_ptr[j] = j < k ? static_cast<const uint8_t *>(in[j].dense) : nullptr;
+    }
+    for (int r = 0; r < kLaunchMaxM; ++r) {
+        a.out_row[r] = r < rows ? out[p.order[r]].table_row : -1;
+        a.out[r] = r < rows ? static_cast<uint8_t *>(const_cast<void *>(out[p.order[r]].dense)) : nullptr;
+    }
     a.plane_base = reinterpret_cast<const uint8_t *const *>(plane_base_dev);
     a.table = table_dev;
     a.vecs_per_plane = vecs;
@@ -626,9 +667,9 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     a.vpp = static_cast<uint32_t>(vpp);
     a.vpp_shift = -1;
     if ((vpp & (vpp - 1)) == 0) {
-        int s = 0;
-        while ((1ull << s) < vpp) ++s;
-        a.vpp_shift = s;
+        int sft = 0;
+        while ((1ull << sft) < vpp) ++sft;
+        a.vpp_shift = sft;
     }
     a.pps = static_cast<uint32_t>(pages_per_shard);
     a.k = k;
@@ -642,7 +683,7 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    return dispatch<PagedLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a,
+    return dispatch<PagedLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
                                    dim3(wgs, static_cast<uint32_t>(n_planes)), stream);
 }
 

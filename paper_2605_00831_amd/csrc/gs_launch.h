@@ -23,12 +23,20 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
                         const void *const *in, void *const *out, size_t bytes,
                         bool accumulate, const LaunchShape &shape, hipStream_t stream);
 
-// One launch of the paged gather variant for table rows [j0, j0+k).
+// A stream of the paged variant: the pages named by row `table_row` of the
+// block table (table_row >= 0), or a dense device buffer laid out
+// [plane][slot][page bytes] like the parity buffers (table_row < 0).
+struct PagedStream {
+    int table_row;
+    const void *dense;
+};
+
+// One launch of the paged variant: k input streams, `rows` output streams.
 hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
                               const void *const *plane_base_dev, int n_planes,
                               size_t page_bytes, int64_t pages_per_plane,
                               const int32_t *table_dev, int pages_per_shard,
-                              void *const *out, bool accumulate,
+                              const PagedStream *in, const PagedStream *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream);
 
 // Batched form: n_chunks independent stream sets in one launch (blockIdx.y =
