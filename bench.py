@@ -253,7 +253,46 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     res["decode_step"] = decode_steps(torch, gs, inputs, log)
     # ---- many small chunks: one launch per chunk, a stream per chunk, or one grouped launch
     res["many_chunks"] = many_chunks(torch, gs, log)
+    # ---- per-chunk latency breakdown against chunk size (the shape of the paper's kernel microbenchmark)
+    res["chunk_sweep"] = chunk_sweep(torch, gs, inputs, log)
     return res
+
+
+def chunk_sweep(torch, gs, inputs, log):
+    """70B-shaped KV, batch 16, 8:2 code: for each chunk size the time of the
+    encode kernel, of the reconstruct kernel (two shards lost) and of the
+    parity D2H of one chunk; events on the launch stream, median of 7."""
+    k, m, batch = 8, 2, 16
+    per_tok = inputs.bytes_per_token(80)
+    code = gs.gs_make_code(k, m)
+    rows = []
+    max_S = 4096 * batch * per_tok // k
+    buf = torch.empty((k + m) * max_S, dtype=torch.uint8, device="cuda")
+    buf.random_(0, 256)
+    host = torch.empty(m * max_S, dtype=torch.uint8, pin_memory=True)
+
+    def med(fn):
+        ts = []
+        for _ in range(9):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return sorted(ts[2:])[3]
+
+    for tokens in (256, 512, 1024, 2048, 4096):
+        S = tokens * batch * per_tok // k
+        shards = [buf[r * max_S: r * max_S + S] for r in range(k + m)]
+        enc = med(lambda: gs.gs_encode(code, shards[:k], shards[k:], S))
+        rec = med(lambda: gs.gs_reconstruct(code, shards, [1, 3], S))
+        d2h = med(lambda: [host[i * S:(i + 1) * S].copy_(shards[k + i], non_blocking=True) for i in range(m)])
+        rows.append({"chunk_tokens": tokens, "data_bytes": k * S, "encode_ms": round(enc, 4),
+                     "reconstruct_ms": round(rec, 4), "parity_d2h_ms": round(d2h, 3),
+                     "encode_frac_of_d2h": round(enc / d2h, 4)})
+    log("[bench] chunk sweep: " + json.dumps(rows))
+    return rows
 
 
 def many_chunks(torch, gs, log):
