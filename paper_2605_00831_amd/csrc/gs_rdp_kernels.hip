@@ -47,11 +47,11 @@ __device__ __forceinline__ void xor_tile(const XorArgs &a, uint64_t v)
 #pragma unroll
     for (int o = 0; o < kOut; ++o) acc[o] = vec(0);
 
-    for (uint32_t s = 0; s < a.n_in; ++s) {
-        const vec *base = reinterpret_cast<const vec *>(a.in[s]) + vv;
-        vec x[kRows];
-#pragma unroll
-        for (int row = 0; row < kRows; ++row) x[row] = __builtin_nontemporal_load(base + row * a.nvb);
+    // Loads of several shards are issued together (about 16 per lane in flight)
+    // before their masks are applied: with one shard at a time a lane has only
+    // p-1 small loads outstanding, too few to cover HBM latency.
+    constexpr int kShards = P <= 5 ? 4 : (P <= 11 ? 2 : 1);
+    auto apply = [&](const vec(&x)[kRows], uint32_t s) {
 #pragma unroll
         for (int row = 0; row < kRows; ++row) {
             const uint32_t m = a.mask[s * kRows + row];
@@ -59,6 +59,25 @@ __device__ __forceinline__ void xor_tile(const XorArgs &a, uint64_t v)
             for (int o = 0; o < kOut; ++o)
                 if (m >> o & 1u) acc[o] ^= x[row];
         }
+    };
+    uint32_t s = 0;
+    for (; s + kShards <= a.n_in; s += kShards) {
+        vec x[kShards][kRows];
+#pragma unroll
+        for (int b = 0; b < kShards; ++b) {
+            const vec *base = reinterpret_cast<const vec *>(a.in[s + b]) + vv;
+#pragma unroll
+            for (int row = 0; row < kRows; ++row) x[b][row] = __builtin_nontemporal_load(base + row * a.nvb);
+        }
+#pragma unroll
+        for (int b = 0; b < kShards; ++b) apply(x[b], s + b);
+    }
+    for (; s < a.n_in; ++s) {
+        const vec *base = reinterpret_cast<const vec *>(a.in[s]) + vv;
+        vec x[kRows];
+#pragma unroll
+        for (int row = 0; row < kRows; ++row) x[row] = __builtin_nontemporal_load(base + row * a.nvb);
+        apply(x, s);
     }
     if (ok) {
 #pragma unroll
