@@ -60,8 +60,12 @@ enum gs_kind {
     GS_CAUCHY = 0,      /* closed form described above                                      */
     GS_VANDERMONDE = 1, /* systematic form of the Vandermonde matrix over points 0..k+m-1,
                            with the same normalisation; yields the identical matrix        */
-    GS_RDP = 2          /* row-diagonal parity: XOR-only, exactly two parity shards; see
+    GS_RDP = 2,         /* row-diagonal parity: XOR-only, exactly two parity shards; see
                            the RDP section below                                           */
+    GS_POWER = 3        /* P[i][j] = 2^(i*j): row 0 is XOR parity, row 1 the classic second
+                           ("Q") syndrome with generator 2.  A different code from GS_CAUCHY
+                           (different parity bytes); MDS only for m <= 3, so m is limited
+                           to 3.  Works with every entry point.                            */
 };
 
 /* Largest code a single kernel launch covers; wider codes run as several

@@ -68,6 +68,7 @@ def lib():
         L.gso_reconstruct.argtypes = [ctypes.c_int, ctypes.c_int, _u8p, _u8pp, _intp,
                                       ctypes.c_int, ctypes.c_size_t]
         L.gso_recompute_units.argtypes = [ctypes.c_int, ctypes.POINTER(_Costs), ctypes.POINTER(ctypes.c_double)]
+        L.gso_power_generator.argtypes = [ctypes.c_int, ctypes.c_int, _u8p]
         L.gso_rdp_prime.argtypes = [ctypes.c_int]
         L.gso_rdp_encode.argtypes = [ctypes.c_int, _u8pp, ctypes.c_size_t]
         L.gso_rdp_reconstruct.argtypes = [ctypes.c_int, _u8pp, _intp, ctypes.c_int, ctypes.c_size_t]
@@ -128,6 +129,14 @@ def generator(k, m):
     rc = lib().gso_generator(k, m, _p(P))
     if rc:
         raise ValueError("bad code parameters k=%d m=%d" % (k, m))
+    return P
+
+
+def power_generator(k, m):
+    """Parity block of the power code, P[i][j] = 2^(i*j), m <= 3."""
+    P = np.zeros((m, k), np.uint8)
+    if lib().gso_power_generator(k, m, _p(P)):
+        raise ValueError("bad power-code parameters k=%d m=%d" % (k, m))
     return P
 
 

@@ -412,3 +412,18 @@ int gso_recompute_units(int n, const struct gso_costs *c, double *makespan_out)
     if (makespan_out) *makespan_out = best_t < 0.0 ? 0.0 : best_t;
     return best;
 }
+
+/* ---- the power code, an alternative generator -------------------------------
+ * P[i][j] = 2^(i*j) (exponent taken mod 255): parity row i is the evaluation
+ * of the data polynomial at 2^i.  Row 0 is XOR parity; rows 0 and 1 are the
+ * familiar P and Q syndromes.  Every square minor on rows {0,1,2} is of
+ * Vandermonde type in the distinct elements 2^j, hence non-zero, so the code
+ * is MDS for m <= 3; with four rows it is not (2^(3*85) = 2^(3*0)). */
+int gso_power_generator(int k, int m, uint8_t *P)
+{
+    gso_init();
+    if (k < 1 || k > 255 || m < 1 || m > 3) return -1;
+    for (int i = 0; i < m; i++)
+        for (int j = 0; j < k; j++) P[i * k + j] = g_exp[(i * j) % 255];
+    return 0;
+}

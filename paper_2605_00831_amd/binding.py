@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libghostserve_ec.so")
 
 GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP = 0, -1, -2, -3, -4, -5
-GS_CAUCHY, GS_VANDERMONDE, GS_RDP = 0, 1, 2
+GS_CAUCHY, GS_VANDERMONDE, GS_RDP, GS_POWER = 0, 1, 2, 3
 
 EXPORTS = [
     "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_rdp_prime", "gs_rdp_plan",

@@ -145,14 +145,16 @@ int gs_make_code(int k, int m, int kind, gs_code **out)
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (k < 1 || m < 1 || k + m > 256) return GS_EINVAL;
-    if (kind != GS_CAUCHY && kind != GS_VANDERMONDE && kind != GS_RDP) return GS_EINVAL;
+    if (kind != GS_CAUCHY && kind != GS_VANDERMONDE && kind != GS_RDP && kind != GS_POWER) return GS_EINVAL;
     if (kind == GS_RDP && (m != 2 || k > kRdpMaxPrime - 1)) return GS_EINVAL;
+    if (kind == GS_POWER && m > 3) return GS_EINVAL;  // beyond that the power matrix is not MDS
     gs_code *c = new (std::nothrow) gs_code;
     if (c == nullptr) return GS_ENOMEM;
     c->k = k;
     c->m = m;
     c->kind = kind;
     if (kind == GS_RDP) c->rdp_encode = rdp_encode_plan(k);
+    else if (kind == GS_POWER) c->P = power_parity_block(k, m);
     else c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
     *out = c;
     return GS_OK;

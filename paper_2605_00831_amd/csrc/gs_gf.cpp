@@ -52,6 +52,22 @@ Matrix vandermonde_parity_block(int k, int m)
     return p;
 }
 
+Matrix power_parity_block(int k, int m)
+{
+    // row i holds the powers of g_i = 2^i: 1, g_i, g_i^2, ...
+    Matrix p(static_cast<size_t>(m) * k);
+    uint8_t g = 1;  // 2^i
+    for (int i = 0; i < m; ++i) {
+        uint8_t v = 1;
+        for (int j = 0; j < k; ++j) {
+            p[i * k + j] = v;
+            v = gf_mul(v, g);
+        }
+        g = gf_mul(g, 2);
+    }
+    return p;
+}
+
 bool invert_in_place(int n, Matrix &a)
 {
     // augmented elimination: w = [A | I], n x 2n

@@ -42,6 +42,9 @@ Matrix cauchy_parity_block(int k, int m);
 // Parity block (m x k) from the systematic form of the Vandermonde matrix
 // over points 0..k+m-1, with the same normalisation.
 Matrix vandermonde_parity_block(int k, int m);
+// Parity block (m x k) of the power code: P[i][j] = 2^(i*j).  Row 0 and
+// column 0 are all ones.  MDS for every k <= 255 only when m <= 3.
+Matrix power_parity_block(int k, int m);
 // In-place inversion of an n x n matrix by elimination on [A | I].
 // Returns false if A is singular.
 bool invert_in_place(int n, Matrix &a);
