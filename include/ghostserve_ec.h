@@ -205,22 +205,29 @@ void gs_step_graph_destroy(gs_step_graph *g);
 
 /* ---- RDP (row-diagonal parity) -----------------------------------------------
  * The third code the paper offers (Section 2, Section 4.1): XOR-only, two
- * parity shards, any two lost shards recoverable.  gs_make_code(k, 2, GS_RDP),
- * 1 <= k <= 16.  Geometry as published for RDP: p = smallest prime >= max(3,
- * k+1); every shard is p-1 equal blocks ("rows"); data shards beyond k up to
- * p-1 are imaginary zeros; shard ids: 0..k-1 data, k row parity, k+1 diagonal
- * parity.  Block (i, j) of the first p "disks" (data + row parity) lies on
- * diagonal (i+j) mod p; diagonal parity block d is the XOR of diagonal d,
- * d = 0..p-2.
+ * parity shards, any two lost shards recoverable.  1 <= k <= 16.  Geometry as
+ * published for RDP: p = smallest prime >= max(3, k+1); a stripe is p-1 rows
+ * of one cell per shard; data shards beyond k up to p-1 are imaginary zeros;
+ * shard ids: 0..k-1 data, k row parity, k+1 diagonal parity.  Cell (i, j) of
+ * the first p "disks" (data + row parity) lies on diagonal (i+j) mod p;
+ * diagonal parity cell d is the XOR of diagonal d, d = 0..p-2.  As on a disk
+ * array a shard holds consecutive, independent stripes: stripe s is the
+ * (p-1)*cell_bytes bytes at offset s*(p-1)*cell_bytes of every shard, its
+ * cell i is row i (the paper does not say how its RDP lays the KV bytes out;
+ * this is the library's reading).  cell_bytes is a power of two >= 16;
+ * gs_make_code(k, 2, GS_RDP) uses GS_RDP_DEFAULT_CELL, which keeps the rows of
+ * a stripe inside the period of the kernels' piece interleave.
  * An RDP code works with gs_encode (parity[0] = row parity, parity[1] =
  * diagonal parity) and gs_reconstruct, with the same argument conventions,
- * except that shard_bytes must be a multiple of 16*(p-1) (else GS_EINVAL).
- * Its rows span the whole shard, so it has no paged, chunked-pipeline or
- * grouped form: those entry points, gs_code_matrix and gs_decode_matrix
- * return GS_EINVAL for it.  A single lost shard other than the diagonal
+ * except that shard_bytes must be a whole number of stripes (else GS_EINVAL).
+ * It has no paged, chunked-pipeline or grouped form: those entry points,
+ * gs_code_matrix and gs_decode_matrix return GS_EINVAL for it.  A single lost shard other than the diagonal
  * parity is rebuilt from the row equations alone (the diagonal parity shard
  * is then not read and may be NULL). */
+#define GS_RDP_DEFAULT_CELL 32768
+int gs_make_rdp_code(int k, size_t cell_bytes, gs_code **out);
 int gs_rdp_prime(const gs_code *code, int *p_out);
+int gs_rdp_cell_bytes(const gs_code *code, size_t *cell_out);
 /* The XOR plan the kernels execute (host only; lets the planning be checked
  * without a GPU).  n_erased = 0 asks for the encode plan.  inputs_out (room
  * for 18 shard ids) lists the shards that are read, outputs_out (room for 2)

@@ -70,8 +70,9 @@ def lib():
         L.gso_recompute_units.argtypes = [ctypes.c_int, ctypes.POINTER(_Costs), ctypes.POINTER(ctypes.c_double)]
         L.gso_power_generator.argtypes = [ctypes.c_int, ctypes.c_int, _u8p]
         L.gso_rdp_prime.argtypes = [ctypes.c_int]
-        L.gso_rdp_encode.argtypes = [ctypes.c_int, _u8pp, ctypes.c_size_t]
-        L.gso_rdp_reconstruct.argtypes = [ctypes.c_int, _u8pp, _intp, ctypes.c_int, ctypes.c_size_t]
+        L.gso_rdp_encode.argtypes = [ctypes.c_int, _u8pp, ctypes.c_size_t, ctypes.c_size_t]
+        L.gso_rdp_reconstruct.argtypes = [ctypes.c_int, _u8pp, _intp, ctypes.c_int, ctypes.c_size_t,
+                                          ctypes.c_size_t]
         L.gso_init()
         _lib = L
     return _lib
@@ -227,28 +228,35 @@ def rdp_prime(k):
     return lib().gso_rdp_prime(k)
 
 
-def rdp_encode(data):
-    """data: list of k equal-length uint8 arrays (length a multiple of p-1)
+def rdp_encode(data, cell_bytes=None):
+    """data: list of k equal-length uint8 arrays holding whole stripes of p-1
+    cells of cell_bytes (default: one stripe, cell = length / (p-1))
     -> [row parity, diagonal parity]."""
     k, S = len(data), data[0].size
+    if cell_bytes is None:
+        cell_bytes = S // (rdp_prime(k) - 1)
+        if cell_bytes * (rdp_prime(k) - 1) != S:
+            raise ValueError("bad RDP geometry: k=%d S=%d" % (k, S))
     for d in data:
         _check_u8(d, "data shard")
         assert d.size == S
     par = [np.zeros(S, np.uint8), np.zeros(S, np.uint8)]
-    if lib().gso_rdp_encode(k, _ptr_array(list(data) + par), S):
+    if cell_bytes < 1 or lib().gso_rdp_encode(k, _ptr_array(list(data) + par), S, cell_bytes):
         raise ValueError("bad RDP geometry: k=%d S=%d" % (k, S))
     return par
 
 
-def rdp_reconstruct(shards, erased):
+def rdp_reconstruct(shards, erased, cell_bytes=None):
     """shards: k data + row parity + diagonal parity; erased ones are rebuilt in place."""
     k, S = len(shards) - 2, shards[0].size
+    if cell_bytes is None:
+        cell_bytes = max(1, S // (rdp_prime(k) - 1))
     for s in shards:
         _check_u8(s, "shard")
         assert s.size == S
     e = len(erased)
     er = (ctypes.c_int * max(e, 1))(*erased)
-    rc = lib().gso_rdp_reconstruct(k, _ptr_array(shards), er, e, S)
+    rc = lib().gso_rdp_reconstruct(k, _ptr_array(shards), er, e, S, cell_bytes)
     if rc == -3:
         raise OverflowError("RDP tolerates two erasures")
     if rc:

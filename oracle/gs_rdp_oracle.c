@@ -13,9 +13,13 @@
  *                            are imaginary all-zero disks when k < p-1)
  *   disk  p-1        row parity
  *   disk  p          diagonal parity
- * A shard of S bytes is cut into p-1 equal blocks of B = S/(p-1) bytes; block
- * i of a shard is row i.  Block (i, j), j <= p-1, lies on diagonal (i+j) mod p;
- * diagonal p-1 is the one diagonal that is not stored.
+ * A disk block ("cell") is B bytes.  As on a disk array, a shard holds many
+ * stripes one after the other: stripe s of a shard is the (p-1)*B bytes at
+ * offset s*(p-1)*B, and its cell i is row i.  Stripes are independent.  (The
+ * paper does not say how its RDP maps the KV bytes to stripes; consecutive
+ * stripes of fixed-size cells is this build's reading, and the cell size is a
+ * parameter.)  Block (i, j), j <= p-1, lies on diagonal (i+j) mod p; diagonal
+ * p-1 is the one diagonal that is not stored.
  *   row parity      R[i] = XOR_{j<=p-2} D[i][j]
  *   diagonal parity Q[d] = XOR of all blocks (i, j), i <= p-2, j <= p-1, with
  *                          (i+j) mod p = d,          for d = 0 .. p-2
@@ -66,16 +70,12 @@ static uint8_t *blk(uint8_t *const *disk, int k, int p, size_t B, int i, int j)
     return disk[k + (j - (p - 1))] + (size_t)i * B;       /* row / diagonal parity */
 }
 
-/* disk[0..k-1] data, disk[k] row parity, disk[k+1] diagonal parity; S bytes each.
- * Returns 0, -1 if S is not a multiple of p-1 or k is out of range. */
-int gso_rdp_encode(int k, uint8_t *const *disk, size_t S)
+/* one stripe: disk[0..k-1] data, disk[k] row parity, disk[k+1] diagonal parity,
+ * each (p-1)*B bytes */
+static void encode_stripe(int k, int p, uint8_t *const *disk, size_t B)
 {
-    if (k < 1 || k > 254) return -1;
-    int p = gso_rdp_prime(k);
-    if (S % (size_t)(p - 1)) return -1;
-    size_t B = S / (size_t)(p - 1);
-    memset(disk[k], 0, S);
-    memset(disk[k + 1], 0, S);
+    memset(disk[k], 0, (size_t)(p - 1) * B);
+    memset(disk[k + 1], 0, (size_t)(p - 1) * B);
     for (int i = 0; i < p - 1; i++)
         for (int j = 0; j < k; j++) xor_into(blk(disk, k, p, B, i, p - 1), blk(disk, k, p, B, i, j), B);
     for (int i = 0; i < p - 1; i++)
@@ -85,6 +85,21 @@ int gso_rdp_encode(int k, uint8_t *const *disk, size_t S)
             if (d == p - 1 || b == NULL) continue;
             xor_into(blk(disk, k, p, B, d, p), b, B);
         }
+}
+
+/* Shards of S bytes = S / ((p-1)*B) stripes of cells of B bytes.
+ * Returns 0, -1 if S is not a whole number of stripes or k is out of range. */
+int gso_rdp_encode(int k, uint8_t *const *disk, size_t S, size_t B)
+{
+    if (k < 1 || k > 254 || B == 0) return -1;
+    int p = gso_rdp_prime(k);
+    size_t stripe = (size_t)(p - 1) * B;
+    if (S % stripe) return -1;
+    uint8_t *at[256];
+    for (size_t off = 0; off < S; off += stripe) {
+        for (int j = 0; j < k + 2; j++) at[j] = disk[j] + off;
+        encode_stripe(k, p, at, B);
+    }
     return 0;
 }
 
@@ -114,25 +129,9 @@ static void from_diagonal(uint8_t *const *disk, int k, int p, size_t B, int i, i
     }
 }
 
-/* erased: shard indices in [0, k+2) (k = row parity, k+1 = diagonal parity).
- * Returns 0; -1 bad arguments; -3 more than two erasures. */
-int gso_rdp_reconstruct(int k, uint8_t *const *disk, const int *erased, int e, size_t S)
+/* one stripe; lost[] holds stripe disk numbers among 0..p-1 */
+static void reconstruct_stripe(int k, int p, uint8_t *const *disk, size_t B, const int *lost, int n, int diag_lost)
 {
-    if (k < 1 || k > 254 || e < 0) return -1;
-    int p = gso_rdp_prime(k);
-    if (S % (size_t)(p - 1)) return -1;
-    size_t B = S / (size_t)(p - 1);
-    int lost[2] = {-1, -1}, n = 0, diag_lost = 0;
-    for (int x = 0; x < e; x++) {
-        if (erased[x] < 0 || erased[x] > k + 1) return -1;
-        for (int y = 0; y < x; y++)
-            if (erased[y] == erased[x]) return -1;
-    }
-    if (e > 2) return -3;
-    for (int x = 0; x < e; x++) {
-        if (erased[x] == k + 1) diag_lost = 1;
-        else lost[n++] = erased[x] < k ? erased[x] : p - 1;   /* stripe disk number */
-    }
     if (n == 1) {
         for (int i = 0; i < p - 1; i++) from_row(disk, k, p, B, i, lost[0]);
     } else if (n == 2) {
@@ -152,7 +151,7 @@ int gso_rdp_reconstruct(int k, uint8_t *const *disk, const int *erased, int e, s
     }
     if (diag_lost) {
         /* re-encode the diagonal parity from the (now complete) stripe */
-        memset(disk[k + 1], 0, S);
+        memset(disk[k + 1], 0, (size_t)(p - 1) * B);
         for (int i = 0; i < p - 1; i++)
             for (int j = 0; j <= p - 1; j++) {
                 int d = (i + j) % p;
@@ -160,6 +159,32 @@ int gso_rdp_reconstruct(int k, uint8_t *const *disk, const int *erased, int e, s
                 if (d == p - 1 || b == NULL) continue;
                 xor_into(blk(disk, k, p, B, d, p), b, B);
             }
+    }
+}
+
+/* erased: shard indices in [0, k+2) (k = row parity, k+1 = diagonal parity).
+ * Returns 0; -1 bad arguments; -3 more than two erasures. */
+int gso_rdp_reconstruct(int k, uint8_t *const *disk, const int *erased, int e, size_t S, size_t B)
+{
+    if (k < 1 || k > 254 || e < 0 || B == 0) return -1;
+    int p = gso_rdp_prime(k);
+    size_t stripe = (size_t)(p - 1) * B;
+    if (S % stripe) return -1;
+    int lost[2] = {-1, -1}, n = 0, diag_lost = 0;
+    for (int x = 0; x < e; x++) {
+        if (erased[x] < 0 || erased[x] > k + 1) return -1;
+        for (int y = 0; y < x; y++)
+            if (erased[y] == erased[x]) return -1;
+    }
+    if (e > 2) return -3;
+    for (int x = 0; x < e; x++) {
+        if (erased[x] == k + 1) diag_lost = 1;
+        else lost[n++] = erased[x] < k ? erased[x] : p - 1;   /* stripe disk number */
+    }
+    uint8_t *at[256];
+    for (size_t off = 0; off < S; off += stripe) {
+        for (int j = 0; j < k + 2; j++) at[j] = disk[j] + off;
+        reconstruct_stripe(k, p, at, B, lost, n, diag_lost);
     }
     return 0;
 }

@@ -17,7 +17,7 @@ GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP = 0, -1, -2, -3,
 GS_CAUCHY, GS_VANDERMONDE, GS_RDP, GS_POWER = 0, 1, 2, 3
 
 EXPORTS = [
-    "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_rdp_prime", "gs_rdp_plan",
+    "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_make_rdp_code", "gs_rdp_prime", "gs_rdp_cell_bytes", "gs_rdp_plan",
     "gs_encode", "gs_encode_paged", "gs_reconstruct", "gs_reconstruct_paged",
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
     "gs_pipe_done_event",
@@ -72,6 +72,8 @@ def lib():
     L.gs_code_matrix.argtypes = [_vp, _u8p]
     L.gs_decode_matrix.argtypes = [_vp, _intp, ctypes.c_int, _u8p, _intp]
     L.gs_rdp_prime.argtypes = [_vp, _intp]
+    L.gs_make_rdp_code.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]
+    L.gs_rdp_cell_bytes.argtypes = [_vp, ctypes.POINTER(ctypes.c_size_t)]
     L.gs_rdp_plan.argtypes = [_vp, _intp, ctypes.c_int, _intp, _intp, _intp, _intp, ctypes.POINTER(ctypes.c_uint32)]
     L.gs_encode.argtypes = [_vp, _vpp, _vpp, ctypes.c_size_t, _vp]
     L.gs_encode_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
@@ -192,6 +194,18 @@ def gs_code_matrix(code):
     P = np.zeros((code.m, code.k), np.uint8)
     _check(lib().gs_code_matrix(code.handle, P.ctypes.data_as(_u8p)), "gs_code_matrix")
     return P
+
+
+def gs_make_rdp_code(k, cell_bytes):
+    h = _vp()
+    _check(lib().gs_make_rdp_code(k, cell_bytes, ctypes.byref(h)), "gs_make_rdp_code")
+    return Code(h, k, 2)
+
+
+def gs_rdp_cell_bytes(code):
+    c = ctypes.c_size_t()
+    _check(lib().gs_rdp_cell_bytes(code.handle, ctypes.byref(c)), "gs_rdp_cell_bytes")
+    return c.value
 
 
 def gs_rdp_prime(code):

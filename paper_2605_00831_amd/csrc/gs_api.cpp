@@ -124,14 +124,14 @@ static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *
     const int rc = check_erasures(code, erased, n_erased, lost);
     if (rc != GS_OK) return rc;
     if (n_erased == 0 || shard_bytes == 0) return GS_OK;
-    if (shard_bytes % (16u * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    if (shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
     RdpPlan plan;
     if (!rdp_decode_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
     for (int s : plan.inputs)
         if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
     for (int s : plan.outputs)
         if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
-    return hip_status(launch_rdp_xor(plan, shards, shard_bytes, current_shape(), stream));
+    return hip_status(launch_rdp_xor(plan, shards, shard_bytes, code->rdp_cell, current_shape(), stream));
 }
 
 }  // namespace gs
@@ -153,7 +153,10 @@ int gs_make_code(int k, int m, int kind, gs_code **out)
     c->k = k;
     c->m = m;
     c->kind = kind;
-    if (kind == GS_RDP) c->rdp_encode = rdp_encode_plan(k);
+    if (kind == GS_RDP) {
+        c->rdp_encode = rdp_encode_plan(k);
+        c->rdp_cell = GS_RDP_DEFAULT_CELL;
+    }
     else if (kind == GS_POWER) c->P = power_parity_block(k, m);
     else c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
     *out = c;
@@ -167,6 +170,23 @@ int gs_code_params(const gs_code *code, int *k, int *m)
     if (code == nullptr) return GS_EINVAL;
     if (k) *k = code->k;
     if (m) *m = code->m;
+    return GS_OK;
+}
+
+int gs_make_rdp_code(int k, size_t cell_bytes, gs_code **out)
+{
+    if (out == nullptr) return GS_EINVAL;
+    *out = nullptr;
+    if (cell_bytes < 16 || (cell_bytes & (cell_bytes - 1)) != 0) return GS_EINVAL;
+    const int rc = gs_make_code(k, 2, GS_RDP, out);
+    if (rc == GS_OK) (*out)->rdp_cell = cell_bytes;
+    return rc;
+}
+
+int gs_rdp_cell_bytes(const gs_code *code, size_t *cell_out)
+{
+    if (code == nullptr || cell_out == nullptr || !code->is_rdp()) return GS_EINVAL;
+    *cell_out = code->rdp_cell;
     return GS_OK;
 }
 
@@ -230,11 +250,11 @@ int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
     for (int i = 0; i < code->m; ++i)
         if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
     if (code->is_rdp()) {
-        if (shard_bytes % (16u * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+        if (shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
         std::vector<const void *> shards(data, data + code->k);
         shards.push_back(parity[0]);
         shards.push_back(parity[1]);
-        return hip_status(launch_rdp_xor(code->rdp_encode, shards.data(), shard_bytes, current_shape(),
+        return hip_status(launch_rdp_xor(code->rdp_encode, shards.data(), shard_bytes, code->rdp_cell, current_shape(),
                                          static_cast<hipStream_t>(stream)));
     }
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,

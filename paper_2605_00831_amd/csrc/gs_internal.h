@@ -12,6 +12,7 @@ struct gs_code {
     int k = 0, m = 0, kind = 0;
     gs::Matrix P;  // m x k parity block, row-major (empty for RDP)
     gs::RdpPlan rdp_encode;  // RDP only
+    size_t rdp_cell = 0;     // RDP only: bytes per cell
     bool is_rdp() const { return kind == 2; }
 };
 

@@ -50,10 +50,11 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
                               int n_chunks, size_t max_bytes, const LaunchShape &shape, hipStream_t stream);
 
 struct RdpPlan;
-// RDP: every output block of the plan = XOR of the masked input blocks.
-// shards[] is indexed by shard id (0..k-1 data, k row parity, k+1 diagonal
-// parity); shard_bytes must be a multiple of 16*(p-1).
+// RDP: every output row of the plan = XOR of the masked input rows, stripe by
+// stripe.  shards[] is indexed by shard id (0..k-1 data, k row parity, k+1
+// diagonal parity); cell_bytes is a power of two >= 16 and shard_bytes a
+// multiple of (p-1)*cell_bytes.
 hipError_t launch_rdp_xor(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
-                          const LaunchShape &shape, hipStream_t stream);
+                          size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
 
 }  // namespace gs

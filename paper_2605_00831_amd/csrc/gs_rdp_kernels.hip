@@ -1,12 +1,15 @@
 // HIP kernel for gfx950: masked XOR of blocks, the one operation both RDP
 // encoding and RDP reconstruction reduce to.
 //
-// A shard of S bytes is p-1 blocks ("rows") of B = S/(p-1) bytes.  Every
-// output block is the XOR of a set of input blocks taken at the same offset
-// inside the block; the sets arrive as one 32-bit mask per input block (bit o
-// = this block is part of output o).  A lane handles one 16-byte vector offset
-// v inside the block: it reads that vector from every row of every input
-// shard and XORs it into the accumulators the mask names.  The masks are
+// A shard is a sequence of stripes; a stripe is p-1 cells ("rows") of
+// cell_bytes each.  Every output cell is the XOR of a set of input cells of
+// the same stripe, taken at the same offset inside the cell; the sets arrive
+// as one 32-bit mask per input row (bit o = this row is part of output o).  A
+// lane handles one vector offset of one stripe: it reads that vector from
+// every row of every input shard and XORs it into the accumulators the mask
+// names.  With cells that are a multiple of the piece interleave period the
+// rows of a stripe sit next to each other in memory (one TLB page, one
+// residue class of pieces per XCD), unlike whole-shard rows.  The masks are
 // wavefront-uniform, so the selection is a scalar bit test and branch around
 // four XORs.  Offsets are dealt to workgroups in the same interleaved 1 KiB
 // pieces as the GF(2^8) kernels (a given XCD keeps to one residue class of
@@ -24,9 +27,10 @@ struct XorArgs {
     const uint8_t *in[kRdpMaxInputs];
     uint8_t *out[2];
     uint32_t mask[kRdpMaxInputs * kRdpMaxRows];
-    uint64_t nvb;       // 16-byte vectors per block
+    uint64_t nvb;       // vectors per row summed over all stripes: shard_bytes / (p-1) / vector bytes
     uint32_t n_in;      // shards read
     uint32_t nx_shift;  // log2 of the piece interleave modulus
+    uint32_t cell_shift;  // log2 of the vectors per cell
 };
 
 // W = dwords per lane and vector (4 = 16 bytes, 2 = 8 bytes).  The number of
@@ -43,6 +47,10 @@ __device__ __forceinline__ void xor_tile(const XorArgs &a, uint64_t v)
     constexpr int kRows = P - 1, kOut = E * kRows;
     const bool ok = FULL || v < a.nvb;
     const uint64_t vv = ok ? v : 0;  // always a valid address; the value is dropped
+    // row r of this lane's stripe, at this lane's offset inside the cell
+    const uint64_t cell_mask = (1ull << a.cell_shift) - 1;
+    const uint64_t row0 = (((vv >> a.cell_shift) * kRows) << a.cell_shift) + (vv & cell_mask);
+    const uint64_t row_step = 1ull << a.cell_shift;
     vec acc[kOut];
 #pragma unroll
     for (int o = 0; o < kOut; ++o) acc[o] = vec(0);
@@ -65,24 +73,24 @@ __device__ __forceinline__ void xor_tile(const XorArgs &a, uint64_t v)
         vec x[kShards][kRows];
 #pragma unroll
         for (int b = 0; b < kShards; ++b) {
-            const vec *base = reinterpret_cast<const vec *>(a.in[s + b]) + vv;
+            const vec *base = reinterpret_cast<const vec *>(a.in[s + b]) + row0;
 #pragma unroll
-            for (int row = 0; row < kRows; ++row) x[b][row] = __builtin_nontemporal_load(base + row * a.nvb);
+            for (int row = 0; row < kRows; ++row) x[b][row] = __builtin_nontemporal_load(base + row * row_step);
         }
 #pragma unroll
         for (int b = 0; b < kShards; ++b) apply(x[b], s + b);
     }
     for (; s < a.n_in; ++s) {
-        const vec *base = reinterpret_cast<const vec *>(a.in[s]) + vv;
+        const vec *base = reinterpret_cast<const vec *>(a.in[s]) + row0;
         vec x[kRows];
 #pragma unroll
-        for (int row = 0; row < kRows; ++row) x[row] = __builtin_nontemporal_load(base + row * a.nvb);
+        for (int row = 0; row < kRows; ++row) x[row] = __builtin_nontemporal_load(base + row * row_step);
         apply(x, s);
     }
     if (ok) {
 #pragma unroll
         for (int o = 0; o < kOut; ++o) {
-            vec *dst = reinterpret_cast<vec *>(a.out[o / kRows]) + (o % kRows) * a.nvb + v;
+            vec *dst = reinterpret_cast<vec *>(a.out[o / kRows]) + row0 + (o % kRows) * row_step;
             __builtin_nontemporal_store(acc[o], dst);
         }
     }
@@ -110,12 +118,13 @@ static hipError_t launch_p(const XorArgs &a, int n_out, dim3 grid, hipStream_t s
 }
 
 hipError_t launch_rdp_xor(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
-                          const LaunchShape &shape, hipStream_t stream)
+                          size_t cell_bytes, const LaunchShape &shape, hipStream_t stream)
 {
     const int rows = plan.p - 1;
+    if (cell_bytes < 16 || (cell_bytes & (cell_bytes - 1)) != 0) return hipErrorInvalidValue;
     const int n_in = static_cast<int>(plan.inputs.size()), n_out = static_cast<int>(plan.outputs.size());
     if (n_in < 1 || n_in > kRdpMaxInputs || n_out < 1 || n_out > 2 || plan.p > kRdpMaxPrime) return hipErrorInvalidValue;
-    if (shard_bytes == 0 || shard_bytes % (16u * rows) != 0) return hipErrorInvalidValue;
+    if (shard_bytes == 0 || shard_bytes % (cell_bytes * rows) != 0) return hipErrorInvalidValue;
     XorArgs a;
     for (int s = 0; s < kRdpMaxInputs; ++s) a.in[s] = s < n_in ? static_cast<const uint8_t *>(shards[plan.inputs[s]]) : nullptr;
     for (int x = 0; x < 2; ++x)
@@ -125,6 +134,8 @@ hipError_t launch_rdp_xor(const RdpPlan &plan, const void *const *shards, size_t
     // (fewer registers per accumulator); 16-byte vectors stay selectable for sweeps
     const int w = shape.unroll == 4 ? 4 : 2;  // dwords per lane
     a.nvb = shard_bytes / rows / (4u * w);
+    a.cell_shift = 0;
+    while ((static_cast<size_t>(4u * w) << a.cell_shift) < cell_bytes) ++a.cell_shift;
     a.n_in = static_cast<uint32_t>(n_in);
     uint32_t nx_shift = shape.interleave_shift >= 0 && shape.interleave_shift <= 10
                             ? static_cast<uint32_t>(shape.interleave_shift) : 5u;

@@ -39,15 +39,18 @@ def check(buf, want):
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 8, 10, 11, 12, 16])
 def test_rdp_encode_and_every_erasure_pattern(gs, k):
-    code = gs.gs_make_code(k, 2, gs.GS_RDP)
-    p = gs.gs_rdp_prime(code)
+    p = oracle.rdp_prime(k)
     rows = p - 1
-    for nvb in (1, 63, 64 * 4 * 3 + 5, 64 * 4 * 32 * 2 + 64 * 7 + 3):   # vectors per block: tiny, ragged, several super-tiles
-        S = rows * 16 * nvb
+    # (cell bytes, stripes): one tiny stripe, ragged stripe counts, several super-tiles of pieces
+    for cell, stripes in ((16, 1), (16, 63), (64, 64 * 3 + 5), (4096, 2 * 32 + 7), (32768, 3)):
+        S = rows * cell * stripes
         if k * S > (48 << 20):
             continue
+        code = gs.gs_make_rdp_code(k, cell)
+        assert gs.gs_rdp_prime(code) == p
+        nvb = S // rows // 16
         data_np = [inputs.kv_bytes_np(17 * k + j, S, "bf16", 1.0) for j in range(k)]
-        want = oracle.rdp_encode(data_np)
+        want = oracle.rdp_encode(data_np, cell)
         full = data_np + want
         data = [dev(x) for x in data_np]
         par = [out_buf(S), out_buf(S)]
@@ -78,13 +81,13 @@ def test_rdp_encode_and_every_erasure_pattern(gs, k):
             work = [x.copy() for x in full]
             for r in pat:
                 work[r][:] = 0xA5
-            oracle.rdp_reconstruct(work, list(pat))
+            oracle.rdp_reconstruct(work, list(pat), cell)
             for r in pat:
                 assert np.array_equal(work[r], full[r])
 
 
 def test_rdp_length_and_erasure_errors(gs):
-    code = gs.gs_make_code(4, 2, gs.GS_RDP)     # p = 5: shard length must be a multiple of 64
+    code = gs.gs_make_rdp_code(4, 16)           # p = 5, 16-byte cells: whole stripes of 64 bytes
     d = [torch.zeros(256, dtype=torch.uint8, device="cuda") for _ in range(4)]
     p = [out_buf(256), out_buf(256)]
     for bad in (100, 48, 65):
@@ -104,33 +107,26 @@ def test_rdp_length_and_erasure_errors(gs):
 
 
 def test_rdp_full_shards_of_the_8b_workload_shape(gs):
-    """k=4 shards of 1 GiB bf16 KV (an eighth of the bulk workload), p=5:
-    windows against the oracle are not possible (rows span the shard), so the
-    whole parity is compared with torch XORs of the blocks the definition names."""
+    """k=4 shards of 1 GiB bf16 KV (an eighth of the bulk workload), p=5,
+    default 32 KiB cells: row parity against a torch XOR of the whole shards,
+    and seeded windows of whole stripes against the oracle."""
     k, S = 4, 1 << 30
     code = gs.gs_make_code(k, 2, gs.GS_RDP)
-    p = gs.gs_rdp_prime(code)
-    rows, B = p - 1, S // (p - 1)
+    p, cell = gs.gs_rdp_prime(code), gs.gs_rdp_cell_bytes(code)
+    stripe = (p - 1) * cell
     buf = inputs.kv_bytes_device(inputs.config_seed("llama8b_prefill"), k * S, "bf16", 0.5, "cuda")
     data = [buf[j * S:(j + 1) * S] for j in range(k)]
     par = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(2)]
     gs.gs_encode(code, data, par, S)
     torch.cuda.synchronize()
-    row = data[0] ^ data[1] ^ data[2] ^ data[3]
-    assert torch.equal(par[0], row)
-    disks = data + [row]
-    diag = torch.zeros(S, dtype=torch.uint8, device="cuda")
-    for i in range(rows):
-        for j in range(p):
-            d = (i + j) % p
-            if d != p - 1:
-                diag[d * B:(d + 1) * B] ^= disks[j][i * B:(i + 1) * B]
-    assert torch.equal(par[1], diag)
-    # a sample of the same stripe through the oracle: take every 2^14-th vector of each block
-    step = 1 << 14
-    sample = lambda t: np.ascontiguousarray(t.view(rows, B // 16, 16)[:, ::step, :].reshape(-1).cpu().numpy())
-    want = oracle.rdp_encode([sample(d) for d in data])
-    assert np.array_equal(sample(par[0]), want[0]) and np.array_equal(sample(par[1]), want[1])
+    assert torch.equal(par[0], data[0] ^ data[1] ^ data[2] ^ data[3])
+    n_stripes = S // stripe
+    rng = np.random.default_rng(inputs.config_seed("llama8b_prefill"))
+    for first in [0, n_stripes - 3] + [int(x) for x in rng.integers(0, n_stripes - 3, size=6)]:
+        lo, hi = first * stripe, (first + 3) * stripe
+        want = oracle.rdp_encode([np.ascontiguousarray(d[lo:hi].cpu().numpy()) for d in data], cell)
+        assert np.array_equal(par[0][lo:hi].cpu().numpy(), want[0])
+        assert np.array_equal(par[1][lo:hi].cpu().numpy(), want[1])
     keep = [data[0].clone(), data[3].clone()]
     data[0].fill_(0xA5)
     data[3].fill_(0xA5)

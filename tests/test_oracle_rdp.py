@@ -124,6 +124,30 @@ def test_round_trip_every_single_and_double_erasure(k):
                 assert np.array_equal(work[r], full[r]), (k, order, r)
 
 
+@pytest.mark.parametrize("k,cell", [(4, 16), (8, 8), (3, 1), (10, 32)])
+def test_stripes_are_independent_and_laid_out_one_after_the_other(k, cell):
+    """A shard of T stripes encodes to the concatenation of the T one-stripe
+    encodings, and reconstructs stripe by stripe."""
+    p = oracle.rdp_prime(k)
+    T, stripe = 5, (p - 1) * cell
+    data = [inputs.uniform_bytes_np(7 * k + j, T * stripe) for j in range(k)]
+    par = oracle.rdp_encode(data, cell)
+    for t in range(T):
+        one = oracle.rdp_encode([np.ascontiguousarray(d[t * stripe:(t + 1) * stripe]) for d in data])
+        assert np.array_equal(par[0][t * stripe:(t + 1) * stripe], one[0])
+        assert np.array_equal(par[1][t * stripe:(t + 1) * stripe], one[1])
+    full = data + par
+    for pat in [(0, 1), (k - 1, k), (0, k + 1), (k, k + 1), (k - 1,)]:
+        work = [x.copy() for x in full]
+        for r in pat:
+            work[r][:] = 0xA5
+        oracle.rdp_reconstruct(work, list(pat), cell)
+        for r in range(k + 2):
+            assert np.array_equal(work[r], full[r]), (pat, r)
+    with pytest.raises(ValueError):
+        oracle.rdp_encode([d[:-1].copy() for d in data], cell)
+
+
 def test_reconstruct_errors():
     data = [inputs.uniform_bytes_np(j, 64) for j in range(4)]
     full = data + oracle.rdp_encode(data)

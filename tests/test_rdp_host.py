@@ -32,7 +32,8 @@ def test_plans_reproduce_the_oracle(k):
     code = gs.gs_make_code(k, 2, gs.GS_RDP)
     p = gs.gs_rdp_prime(code)
     assert p == oracle.rdp_prime(k)
-    S = (p - 1) * 5
+    assert gs.gs_rdp_cell_bytes(code) == 32768 and gs.gs_rdp_cell_bytes(gs.gs_make_rdp_code(k, 64)) == 64
+    S = (p - 1) * 5                                         # one stripe of 5-byte cells
     data = [inputs.uniform_bytes_np(9 * k + j, S) for j in range(k)]
     par = oracle.rdp_encode(data)
     full = data + par
@@ -59,6 +60,9 @@ def test_rdp_code_rules():
     for k, m in [(17, 2), (4, 1), (4, 3), (0, 2)]:
         with pytest.raises(gs.GsError):
             gs.gs_make_code(k, m, gs.GS_RDP)
+    for cell in (0, 8, 48, 1000):
+        with pytest.raises(gs.GsError):
+            gs.gs_make_rdp_code(4, cell)
     code = gs.gs_make_code(4, 2, gs.GS_RDP)
     with pytest.raises(gs.GsError):
         gs.gs_code_matrix(code)
