@@ -228,14 +228,18 @@ void gs_step_graph_destroy(gs_step_graph *g);
 int gs_make_rdp_code(int k, size_t cell_bytes, gs_code **out);
 int gs_rdp_prime(const gs_code *code, int *p_out);
 int gs_rdp_cell_bytes(const gs_code *code, size_t *cell_out);
-/* The XOR plan the kernels execute (host only; lets the planning be checked
- * without a GPU).  n_erased = 0 asks for the encode plan.  inputs_out (room
- * for 18 shard ids) lists the shards that are read, outputs_out (room for 2)
- * the shards that are written, and mask_out (room for 18*16 words) holds, for
- * input s and row r, at [s*(p-1)+r], a bit set at position x*(p-1)+q when that
- * block is part of the XOR that yields block q of outputs_out[x]. */
-int gs_rdp_plan(const gs_code *code, const int *erased, int n_erased, int *inputs_out, int *n_inputs_out,
-                int *outputs_out, int *n_outputs_out, uint32_t *mask_out);
+/* The plan the kernels execute (host only; lets the planning be checked
+ * without a GPU).  The device first accumulates, per stripe, the syndromes
+ * SR[i] = XOR of row i over the shards read among data and row parity, and
+ * SD[d] = XOR of diagonal d over those shards plus diagonal-parity cell d (if
+ * read); every missing cell is then the XOR of a set of syndromes.
+ * n_missing = 0 asks for the encode plan (both parity shards missing).
+ * read_out (room for 18 shard ids) lists the shards that are read;
+ * syndrome_mask_out (room for 32 words) holds, for missing shard x (in the
+ * order given) and row q, at [x*(p-1)+q], bit i (< p-1) set when SR[i] is part
+ * of the cell and bit p-1+d when SD[d] is. */
+int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *read_out, int *n_read_out,
+                uint32_t *syndrome_mask_out);
 
 /* ---- many chunks at once ---------------------------------------------------
  * Section 5: recovery reconstructs many chunks concurrently ("each chunk is

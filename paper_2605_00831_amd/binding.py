@@ -74,7 +74,7 @@ def lib():
     L.gs_rdp_prime.argtypes = [_vp, _intp]
     L.gs_make_rdp_code.argtypes = [ctypes.c_int, ctypes.c_size_t, ctypes.POINTER(_vp)]
     L.gs_rdp_cell_bytes.argtypes = [_vp, ctypes.POINTER(ctypes.c_size_t)]
-    L.gs_rdp_plan.argtypes = [_vp, _intp, ctypes.c_int, _intp, _intp, _intp, _intp, ctypes.POINTER(ctypes.c_uint32)]
+    L.gs_rdp_plan.argtypes = [_vp, _intp, ctypes.c_int, _intp, _intp, ctypes.POINTER(ctypes.c_uint32)]
     L.gs_encode.argtypes = [_vp, _vpp, _vpp, ctypes.c_size_t, _vp]
     L.gs_encode_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
                                   ctypes.c_int, _vpp, _vp]
@@ -214,16 +214,17 @@ def gs_rdp_prime(code):
     return p.value
 
 
-def gs_rdp_plan(code, erased=()):
-    """(inputs, outputs, mask[len(inputs)][p-1]) of the encode plan (no erasures) or a rebuild plan"""
-    er, n = _int_array(erased)
-    ins, outs = (ctypes.c_int * 18)(), (ctypes.c_int * 2)()
-    ni, no = ctypes.c_int(), ctypes.c_int()
-    mask = (ctypes.c_uint32 * (18 * 16))()
-    _check(lib().gs_rdp_plan(code.handle, er, n, ins, ctypes.byref(ni), outs, ctypes.byref(no), mask), "gs_rdp_plan")
+def gs_rdp_plan(code, missing=()):
+    """(shards read, syndrome masks [len(missing) or 2][p-1]) of the encode plan
+    (nothing missing = both parity shards are produced) or of a rebuild plan"""
+    er, n = _int_array(missing)
+    read = (ctypes.c_int * 18)()
+    nr = ctypes.c_int()
+    mask = (ctypes.c_uint32 * 32)()
+    _check(lib().gs_rdp_plan(code.handle, er, n, read, ctypes.byref(nr), mask), "gs_rdp_plan")
     rows = gs_rdp_prime(code) - 1
-    m = np.array(list(mask[: ni.value * rows]), dtype=np.uint32).reshape(ni.value, rows)
-    return list(ins[: ni.value]), list(outs[: no.value]), m
+    n_out = n if n else 2
+    return list(read[: nr.value]), np.array(list(mask[: n_out * rows]), dtype=np.uint32).reshape(n_out, rows)
 
 
 def gs_decode_matrix(code, erased):

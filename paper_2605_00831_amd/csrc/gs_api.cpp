@@ -126,12 +126,14 @@ static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *
     if (n_erased == 0 || shard_bytes == 0) return GS_OK;
     if (shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
     RdpPlan plan;
-    if (!rdp_decode_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
-    for (int s : plan.inputs)
-        if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
+    if (!rdp_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+    for (int j = 0; j <= plan.p; ++j) {
+        const int s = plan.shard_of_disk[j];
+        if (s >= 0 && (shards[s] == nullptr || !aligned16(shards[s]))) return GS_EINVAL;
+    }
     for (int s : plan.outputs)
         if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
-    return hip_status(launch_rdp_xor(plan, shards, shard_bytes, code->rdp_cell, current_shape(), stream));
+    return hip_status(launch_rdp(plan, shards, shard_bytes, code->rdp_cell, current_shape(), stream));
 }
 
 }  // namespace gs
@@ -154,7 +156,8 @@ int gs_make_code(int k, int m, int kind, gs_code **out)
     c->m = m;
     c->kind = kind;
     if (kind == GS_RDP) {
-        c->rdp_encode = rdp_encode_plan(k);
+        const int parity_ids[2] = {k, k + 1};
+        rdp_plan(k, parity_ids, 2, c->rdp_encode);
         c->rdp_cell = GS_RDP_DEFAULT_CELL;
     }
     else if (kind == GS_POWER) c->P = power_parity_block(k, m);
@@ -197,26 +200,26 @@ int gs_rdp_prime(const gs_code *code, int *p_out)
     return GS_OK;
 }
 
-int gs_rdp_plan(const gs_code *code, const int *erased, int n_erased, int *inputs_out, int *n_inputs_out,
-                int *outputs_out, int *n_outputs_out, uint32_t *mask_out)
+int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *read_out, int *n_read_out,
+                uint32_t *syndrome_mask_out)
 {
-    if (code == nullptr || !code->is_rdp() || inputs_out == nullptr || n_inputs_out == nullptr ||
-        outputs_out == nullptr || n_outputs_out == nullptr || mask_out == nullptr)
+    if (code == nullptr || !code->is_rdp() || read_out == nullptr || n_read_out == nullptr ||
+        syndrome_mask_out == nullptr)
         return GS_EINVAL;
     RdpPlan plan;
-    if (n_erased == 0) {
+    if (n_missing == 0) {
         plan = code->rdp_encode;
     } else {
         std::vector<uint8_t> lost;
-        const int rc = check_erasures(code, erased, n_erased, lost);
+        const int rc = check_erasures(code, missing, n_missing, lost);
         if (rc != GS_OK) return rc;
-        if (!rdp_decode_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+        if (!rdp_plan(code->k, missing, n_missing, plan)) return GS_ESINGULAR;
     }
-    *n_inputs_out = static_cast<int>(plan.inputs.size());
-    *n_outputs_out = static_cast<int>(plan.outputs.size());
-    std::copy(plan.inputs.begin(), plan.inputs.end(), inputs_out);
-    std::copy(plan.outputs.begin(), plan.outputs.end(), outputs_out);
-    std::copy(plan.mask.begin(), plan.mask.end(), mask_out);
+    int n = 0;
+    for (int j = 0; j <= plan.p; ++j)
+        if (plan.shard_of_disk[j] >= 0) read_out[n++] = plan.shard_of_disk[j];
+    *n_read_out = n;
+    std::copy(plan.syndrome_mask.begin(), plan.syndrome_mask.end(), syndrome_mask_out);
     return GS_OK;
 }
 
@@ -254,7 +257,7 @@ int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
         std::vector<const void *> shards(data, data + code->k);
         shards.push_back(parity[0]);
         shards.push_back(parity[1]);
-        return hip_status(launch_rdp_xor(code->rdp_encode, shards.data(), shard_bytes, code->rdp_cell, current_shape(),
+        return hip_status(launch_rdp(code->rdp_encode, shards.data(), shard_bytes, code->rdp_cell, current_shape(),
                                          static_cast<hipStream_t>(stream)));
     }
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,

@@ -50,11 +50,11 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
                               int n_chunks, size_t max_bytes, const LaunchShape &shape, hipStream_t stream);
 
 struct RdpPlan;
-// RDP: every output row of the plan = XOR of the masked input rows, stripe by
-// stripe.  shards[] is indexed by shard id (0..k-1 data, k row parity, k+1
-// diagonal parity); cell_bytes is a power of two >= 16 and shard_bytes a
-// multiple of (p-1)*cell_bytes.
-hipError_t launch_rdp_xor(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
-                          size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
+// RDP: accumulate the stripe syndromes from the shards the plan reads and
+// form the plan's outputs from them, stripe by stripe.  shards[] is indexed
+// by shard id (0..k-1 data, k row parity, k+1 diagonal parity); cell_bytes is
+// a power of two >= 16 and shard_bytes a multiple of (p-1)*cell_bytes.
+hipError_t launch_rdp(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
+                      size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
 
 }  // namespace gs

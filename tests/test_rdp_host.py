@@ -12,18 +12,35 @@ from paper_2605_00831_amd import binding as gs
 from paper_2605_00831_amd import inputs
 
 
-def run_plan(plan, shards, p):
-    ins, outs, mask = plan
+def run_plan(plan, outputs, shards, k, p):
+    """numpy model of the device: syndromes of the one stripe, then masked XORs"""
+    read, mask = plan
     rows = p - 1
-    B = shards[0].size // rows
-    result = {o: np.zeros(shards[0].size, np.uint8) for o in outs}
-    for s, shard in enumerate(ins):
+    size = next(x.size for x in shards if x is not None)
+    B = size // rows
+    disk_of = lambda shard: shard if shard < k else (p - 1 if shard == k else p)
+    sr = [np.zeros(B, np.uint8) for _ in range(rows)]
+    sd = [np.zeros(B, np.uint8) for _ in range(rows)]
+    for shard in read:
+        j = disk_of(shard)
         for r in range(rows):
-            blk = shards[shard][r * B:(r + 1) * B]
-            for x, o in enumerate(outs):
-                for q in range(rows):
-                    if mask[s, r] >> (x * rows + q) & 1:
-                        result[o][q * B:(q + 1) * B] ^= blk
+            cell = shards[shard][r * B:(r + 1) * B]
+            if j == p:
+                sd[r] ^= cell
+            else:
+                sr[r] ^= cell
+                if (r + j) % p != p - 1:
+                    sd[(r + j) % p] ^= cell
+    result = {}
+    for x, o in enumerate(outputs):
+        buf = np.zeros(size, np.uint8)
+        for q in range(rows):
+            for i in range(rows):
+                if mask[x, q] >> i & 1:
+                    buf[q * B:(q + 1) * B] ^= sr[i]
+                if mask[x, q] >> (rows + i) & 1:
+                    buf[q * B:(q + 1) * B] ^= sd[i]
+        result[o] = buf
     return result
 
 
@@ -37,18 +54,17 @@ def test_plans_reproduce_the_oracle(k):
     data = [inputs.uniform_bytes_np(9 * k + j, S) for j in range(k)]
     par = oracle.rdp_encode(data)
     full = data + par
-    enc = run_plan(gs.gs_rdp_plan(code), full, p)
+    enc = run_plan(gs.gs_rdp_plan(code), [k, k + 1], full[:k] + [None, None], k, p)
     assert np.array_equal(enc[k], par[0]) and np.array_equal(enc[k + 1], par[1])
     pats = list(itertools.combinations(range(k + 2), 1)) + list(itertools.combinations(range(k + 2), 2))
     for pat in pats:
         for order in (pat, pat[::-1]):
             plan = gs.gs_rdp_plan(code, order)
-            assert plan[1] == list(order)
-            assert not set(plan[0]) & set(order)            # lost shards are never read
+            assert not set(plan[0]) & set(order)            # missing shards are never read
             poisoned = [x.copy() for x in full]
             for r in order:
-                poisoned[r][:] = 0xA5
-            got = run_plan(plan, poisoned, p)
+                poisoned[r] = None
+            got = run_plan(plan, list(order), poisoned, k, p)
             for r in order:
                 assert np.array_equal(got[r], full[r]), (k, order, r)
     # a single lost data or row-parity shard never touches the diagonal parity
