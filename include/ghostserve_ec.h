@@ -220,7 +220,8 @@ void gs_step_graph_destroy(gs_step_graph *g);
  * An RDP code works with gs_encode (parity[0] = row parity, parity[1] =
  * diagonal parity) and gs_reconstruct, with the same argument conventions,
  * except that shard_bytes must be a whole number of stripes (else GS_EINVAL).
- * It has no paged, chunked-pipeline or grouped form: those entry points,
+ * The checkpoint / restore pipelines accept it when chunk_bytes is a whole
+ * number of stripes.  It has no paged or grouped form: those entry points,
  * gs_code_matrix and gs_decode_matrix return GS_EINVAL for it.  A single lost shard other than the diagonal
  * parity is rebuilt from the row equations alone (the diagonal parity shard
  * is then not read and may be NULL). */

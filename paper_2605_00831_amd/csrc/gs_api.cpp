@@ -117,6 +117,23 @@ int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vec
     return GS_OK;
 }
 
+int shards_read(const gs_code *code, const int *erased, int n_erased, std::vector<int> &read)
+{
+    read.clear();
+    if (code->is_rdp()) {
+        std::vector<uint8_t> lost;
+        const int rc = check_erasures(code, erased, n_erased, lost);
+        if (rc != GS_OK || n_erased == 0) return rc;
+        RdpPlan plan;
+        if (!rdp_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+        for (int j = 0; j <= plan.p; ++j)
+            if (plan.shard_of_disk[j] >= 0) read.push_back(plan.shard_of_disk[j]);
+        return GS_OK;
+    }
+    std::vector<uint8_t> R;
+    return decode_matrix(code, erased, n_erased, R, read);
+}
+
 static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
                            size_t shard_bytes, hipStream_t stream)
 {

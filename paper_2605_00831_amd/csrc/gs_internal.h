@@ -25,6 +25,8 @@ LaunchShape current_shape();
 int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, void *const *out,
                  size_t bytes, hipStream_t stream);
 int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost);
+// shard ids a rebuild of `erased` reads (any code kind); validates the list
+int shards_read(const gs_code *code, const int *erased, int n_erased, std::vector<int> &read);
 int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &R,
                   std::vector<int> &survivors);
 

@@ -63,7 +63,8 @@ int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe *
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || chunk_bytes == 0 || chunk_bytes % 16 != 0 || depth < 2 || depth > 64) return GS_EINVAL;
-    if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard: no chunked form
+    // RDP chunks must hold whole stripes
+    if (code->is_rdp() && chunk_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
     gs_pipe *p = new (std::nothrow) gs_pipe;
     if (p == nullptr) return GS_ENOMEM;
     p->code = code;
@@ -111,7 +112,7 @@ int gs_checkpoint(gs_pipe *p, const void *const *data, size_t shard_bytes, void 
         if (p->used[slot]) GS_TRY(hipStreamWaitEvent(cs, p->drained[slot], 0));
         for (int j = 0; j < k; ++j) in[j] = static_cast<const uint8_t *>(data[j]) + off;
         for (int i = 0; i < m; ++i) out[i] = p->slot_buf(slot, i);
-        const int rc = apply_matrix(m, k, p->code->P.data(), in.data(), out.data(), len, cs);
+        const int rc = gs_encode(p->code, in.data(), out.data(), len, cs);
         if (rc != GS_OK) return rc;
         GS_TRY(hipEventRecord(p->filled[slot], cs));
         GS_TRY(hipStreamWaitEvent(p->copy_stream, p->filled[slot], 0));
@@ -130,14 +131,13 @@ int gs_restore(gs_pipe *p, void *const *shards, void *const *host_parity, const 
                int n_erased, size_t shard_bytes, void *compute_stream)
 {
     if (p == nullptr || shards == nullptr || host_parity == nullptr) return GS_EINVAL;
-    const int k = p->code->k;
-    std::vector<uint8_t> R;
-    std::vector<int> surv;
-    const int rc0 = decode_matrix(p->code, erased, n_erased, R, surv);
+    const int k = p->code->k, m = p->code->m;
+    std::vector<int> read;  // shard ids the rebuild reads
+    const int rc0 = shards_read(p->code, erased, n_erased, read);
     if (rc0 != GS_OK) return rc0;
     if (n_erased == 0 || shard_bytes == 0) return GS_OK;
-    for (int j = 0; j < k; ++j) {
-        const int s = surv[j];
+    if (p->code->is_rdp() && shard_bytes % (p->code->rdp_cell * (p->code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    for (int s : read) {
         if (s < k) {
             if (shards[s] == nullptr || (reinterpret_cast<uintptr_t>(shards[s]) & 15u)) return GS_EINVAL;
         } else if (host_parity[s - k] == nullptr) {
@@ -147,29 +147,28 @@ int gs_restore(gs_pipe *p, void *const *shards, void *const *host_parity, const 
     for (int x = 0; x < n_erased; ++x)
         if (shards[erased[x]] == nullptr || (reinterpret_cast<uintptr_t>(shards[erased[x]]) & 15u)) return GS_EINVAL;
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-    std::vector<const void *> in(k);
-    std::vector<void *> out(n_erased);
+    std::vector<void *> view(k + m);  // the stripe as the rebuild of one chunk sees it
     const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
     for (size_t c = 0; c < nchunks; ++c) {
         const int slot = static_cast<int>(c % p->depth);
         const size_t off = c * p->chunk_bytes;
         const size_t len = std::min(p->chunk_bytes, shard_bytes - off);
         if (p->used[slot]) GS_TRY(hipStreamWaitEvent(p->copy_stream, p->drained[slot], 0));
-        for (int j = 0; j < k; ++j) {
-            const int s = surv[j];
+        for (int r = 0; r < k + m; ++r) view[r] = nullptr;
+        for (int s : read) {
             if (s < k) {
-                in[j] = static_cast<const uint8_t *>(shards[s]) + off;
+                view[s] = static_cast<uint8_t *>(shards[s]) + off;
             } else {
                 uint8_t *stage = p->slot_buf(slot, s - k);
                 GS_TRY(hipMemcpyAsync(stage, static_cast<const uint8_t *>(host_parity[s - k]) + off, len,
                                       hipMemcpyHostToDevice, p->copy_stream));
-                in[j] = stage;
+                view[s] = stage;
             }
         }
+        for (int x = 0; x < n_erased; ++x) view[erased[x]] = static_cast<uint8_t *>(shards[erased[x]]) + off;
         GS_TRY(hipEventRecord(p->filled[slot], p->copy_stream));
         GS_TRY(hipStreamWaitEvent(cs, p->filled[slot], 0));
-        for (int x = 0; x < n_erased; ++x) out[x] = static_cast<uint8_t *>(shards[erased[x]]) + off;
-        const int rc = apply_matrix(n_erased, k, R.data(), in.data(), out.data(), len, cs);
+        const int rc = gs_reconstruct(p->code, view.data(), erased, n_erased, len, cs);
         if (rc != GS_OK) return rc;
         GS_TRY(hipEventRecord(p->drained[slot], cs));
         p->used[slot] = 1;

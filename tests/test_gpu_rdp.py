@@ -133,3 +133,40 @@ def test_rdp_full_shards_of_the_8b_workload_shape(gs):
     gs.gs_reconstruct(code, data + par, [0, 3], S)
     torch.cuda.synchronize()
     assert torch.equal(data[0], keep[0]) and torch.equal(data[3], keep[1])
+
+
+def test_rdp_checkpoint_and_restore_pipelines(gs):
+    """RDP through the chunked pipelines: parity lands in pinned host memory,
+    then two lost data shards come back with both parities read H2D."""
+    k, cell, stripes_per_chunk, chunks = 4, 4096, 3, 5
+    code = gs.gs_make_rdp_code(k, cell)
+    stripe = (gs.gs_rdp_prime(code) - 1) * cell
+    chunk = stripes_per_chunk * stripe
+    S = chunks * chunk - stripe                       # ragged last chunk (still whole stripes)
+    data_np = [inputs.kv_bytes_np(300 + j, S, "fp16", 1.0) for j in range(k)]
+    want = oracle.rdp_encode(data_np, cell)
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    data = [dev(x) for x in data_np]
+    host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    for h in host:
+        h.fill_(0x5A)
+    torch.cuda.synchronize()
+    gs.gs_checkpoint(pipe, data, S, host)
+    gs.gs_pipe_sync(pipe)
+    assert np.array_equal(host[0].numpy(), want[0]) and np.array_equal(host[1].numpy(), want[1])
+    for pat in ([0, 2], [3], [1, 5], [4, 5]):
+        shards = []
+        for r in range(k + 2):
+            if r in pat:
+                shards.append(torch.full((S,), 0xA5, dtype=torch.uint8, device="cuda"))
+            else:
+                shards.append(data[r] if r < k else None)
+        gs.gs_restore(pipe, shards, host, pat, S)
+        gs.gs_pipe_sync(pipe)
+        torch.cuda.synchronize()
+        full = data_np + want
+        for r in pat:
+            assert np.array_equal(shards[r].cpu().numpy(), full[r]), (pat, r)
+    with pytest.raises(gs.GsError):
+        gs.gs_pipe_create(code, stripe + 16, 2)        # chunks must hold whole stripes
+    gs.gs_pipe_destroy(pipe)

@@ -90,6 +90,6 @@ def test_rdp_code_rules():
     with pytest.raises(gs.GsError):
         gs.gs_rdp_prime(gs.gs_make_code(4, 2))
     with pytest.raises(gs.GsError):
-        gs.gs_pipe_create(code, 4096, 2)
+        gs.gs_pipe_create(code, 4096, 2)                    # not a whole number of 4 x 32 KiB stripes
     with pytest.raises(gs.GsError):
         gs.gs_batch_create(code, 4)
