@@ -229,6 +229,32 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     log("[bench] restore %.1f ms" % (min(lat) * 1e3))
     gs.gs_pipe_destroy(pipe)
 
+    # ---- the XOR-only RDP code on the same shards (needs k <= 16 and whole stripes)
+    if k <= 16 and m >= 2:
+        rdp = gs.gs_make_code(k, 2, gs.GS_RDP)
+        stripe = (gs.gs_rdp_prime(rdp) - 1) * gs.gs_rdp_cell_bytes(rdp)
+        Sr = S // stripe * stripe
+        if Sr:
+            def ev_ms(fn, n=5):
+                ts = []
+                for _ in range(n + 1):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    fn()
+                    b.record()
+                    torch.cuda.synchronize()
+                    ts.append(a.elapsed_time(b))
+                return sorted(ts[1:])[n // 2]
+            enc = ev_ms(lambda: gs.gs_encode(rdp, data, parity[:2], Sr))
+            rec = ev_ms(lambda: gs.gs_reconstruct(rdp, data + parity[:2], erased[:2], Sr))
+            res["rdp"] = {"prime": gs.gs_rdp_prime(rdp), "cell_bytes": gs.gs_rdp_cell_bytes(rdp), "shard_bytes": Sr,
+                          "encode_ms": round(enc, 4), "encode_hbm_frac": round((k + 2) * Sr / enc / 1e6 / HBM_PEAK_GBPS, 4),
+                          "reconstruct_ms": round(rec, 4),
+                          "reconstruct_hbm_frac": round((k + len(erased[:2])) * Sr / rec / 1e6 / HBM_PEAK_GBPS, 4)}
+            log("[bench] rdp: " + json.dumps(res["rdp"]))
+            gs.gs_encode(code, data, parity, S)   # put the Reed-Solomon parity back
+            torch.cuda.synchronize()
+
     # ---- CPU oracle on the same bytes (bounded sample), all host cores
     import oracle
     nthreads = min(os.cpu_count() or 1, 16)
