@@ -74,6 +74,7 @@ struct PagedArgs {
     int32_t accumulate;
     uint32_t tiles_per_wg;
     uint32_t nx_shift;         // log2 of the piece interleave modulus
+    uint32_t mixed;            // 0: inputs are consecutive table rows, outputs dense
 };
 
 template <bool NT>
@@ -307,7 +308,11 @@ void apply_batch_kernel(const BatchArgs a)
 // the vector table loads off the critical path.
 typedef const int32_t __attribute__((address_space(4))) *ConstTable;
 
-template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE>
+// MIXED: streams may be table rows or dense buffers on either side (paged
+// reconstruct).  Without it (paged encode) input j is table row in_row[0]+j
+// and every output is dense, which keeps the per-stream kind tests and one
+// dependent scalar load off the latency-bound decode-step path.
+template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE, bool MIXED>
 __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint64_t out_base,
                                            const uint64_t (&vv)[U])
 {
@@ -339,9 +344,10 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
         return static_cast<uint64_t>(page) < a.pages_per_plane ? page : -1;
     };
     // stream j at vector u: from its page, or from the dense layout
+    const int32_t first_row = a.in_row[0];
     auto gather = [&](int j, int u) -> u32x4 {
-        const int32_t row = a.in_row[j];
-        if (row < 0) {
+        const int32_t row = MIXED ? a.in_row[j] : first_row + j;
+        if (MIXED && row < 0) {
             const u32x4 x = load16<NT>(a.in_ptr[j], out_base + v[u]);
             return ok[u] ? x : u32x4{0, 0, 0, 0};
         }
@@ -353,7 +359,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     };
     // where output r of vector u lives; nullptr if it must not be touched
     auto out_at = [&](int r, int u) -> u32x4 * {
-        const int32_t row = a.out_row[r];
+        const int32_t row = MIXED ? a.out_row[r] : -1;
         if (row < 0) return reinterpret_cast<u32x4 *>(a.out[r]) + out_base + v[u];
         const int64_t page = page_of(row, u);
         if (page < 0) return nullptr;
@@ -404,7 +410,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
 // contiguous kernel (gridDim.x is a multiple of the interleave modulus, so the
 // piece residue still names the XCD).  Each lane finds its page slot, looks
 // the page id up in every shard's table row, and reads from that page.
-template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE>
+template <int M, bool ROW0_XOR, int U, bool WAVE_PAGE, bool MIXED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
 void apply_paged_kernel(const PagedArgs a)
 {
@@ -423,7 +429,7 @@ void apply_paged_kernel(const PagedArgs a)
         uint64_t v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
-        paged_tile<M, ROW0_XOR, U, NT, WAVE_PAGE>(a, pbase, out_base, v);
+        paged_tile<M, ROW0_XOR, U, true, WAVE_PAGE, MIXED>(a, pbase, out_base, v);
     }
 }
 
@@ -522,14 +528,19 @@ struct ContigLauncher {
     }
 };
 
+// the paged kernels always use the streaming cache policy (NT is ignored)
 template <int M, bool X, int U, bool NT>
 struct PagedLauncher {
+    template <bool WAVE_PAGE, bool MIXED>
+    static void launch(const PagedArgs &a, dim3 grid, hipStream_t stream)
+    {
+        hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED>), grid, dim3(kThreads), 0, stream, a);
+    }
     static hipError_t go(const PagedArgs &a, dim3 grid, hipStream_t stream)
     {
-        if (a.vpp % 64 == 0)
-            hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT, true>), grid, dim3(kThreads), 0, stream, a);
-        else
-            hipLaunchKernelGGL((apply_paged_kernel<M, X, U, NT, false>), grid, dim3(kThreads), 0, stream, a);
+        const bool wave_page = a.vpp % 64 == 0;
+        if (a.mixed) wave_page ? launch<true, true>(a, grid, stream) : launch<false, true>(a, grid, stream);
+        else wave_page ? launch<true, false>(a, grid, stream) : launch<false, false>(a, grid, stream);
         return hipGetLastError();
     }
 };
@@ -660,6 +671,10 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
         a.out_row[r] = r < rows ? out[p.order[r]].table_row : -1;
         a.out[r] = r < rows ? static_cast<uint8_t *>(const_cast<void *>(out[p.order[r]].dense)) : nullptr;
     }
+    bool plain = true;  // the paged-encode shape: consecutive table rows in, dense buffers out
+    for (int j = 0; j < k; ++j) plain = plain && in[j].table_row >= 0 && in[j].table_row == in[0].table_row + j;
+    for (int r = 0; r < rows; ++r) plain = plain && out[r].table_row < 0;
+    a.mixed = plain ? 0u : 1u;
     a.plane_base = reinterpret_cast<const uint8_t *const *>(plane_base_dev);
     a.table = table_dev;
     a.vecs_per_plane = vecs;
