@@ -157,3 +157,41 @@ def test_step_graph_replays_track_the_block_table(gs):
             assert np.array_equal(host[i].numpy()[:out_bytes], want[i]), step
             assert torch.equal(eager[i], par[i])
     gs.gs_step_graph_destroy(graph)
+
+
+def test_core_entry_points_can_be_captured_in_a_graph(gs):
+    """gs_encode / gs_reconstruct allocate nothing and only enqueue on the
+    given stream, so a caller may capture them.  The graph is replayed several
+    times, with eager work and synchronisation in between, on changing data."""
+    k, m, S = 4, 2, (1 << 20) + 48
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    data = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(k)]
+    par = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    rebuilt = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    view = [data[0], rebuilt[0], data[2], rebuilt[1], par[0], par[1]]   # shards 1 and 3 are rebuilt elsewhere
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gs.gs_encode(code, data, par, S)                      # warm-up outside the capture
+        gs.gs_reconstruct(code, view, [1, 3], S)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gs.gs_encode(code, data, par, S)
+        gs.gs_reconstruct(code, view, [1, 3], S)
+    for rep in range(4):
+        data_np = [inputs.kv_bytes_np(900 + 10 * rep + j, S, "bf16", 1.0) for j in range(k)]
+        for j in range(k):
+            data[j].copy_(torch.from_numpy(data_np[j]))      # eager work between replays
+        for t in par + rebuilt:
+            t.fill_(0xEE)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.encode(P, data_np, nthreads=8)
+        for i in range(m):
+            assert np.array_equal(par[i].cpu().numpy(), want[i]), (rep, i)
+        assert np.array_equal(rebuilt[0].cpu().numpy(), data_np[1]), rep
+        assert np.array_equal(rebuilt[1].cpu().numpy(), data_np[3]), rep
