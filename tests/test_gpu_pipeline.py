@@ -195,3 +195,52 @@ def test_core_entry_points_can_be_captured_in_a_graph(gs):
             assert np.array_equal(par[i].cpu().numpy(), want[i]), (rep, i)
         assert np.array_equal(rebuilt[0].cpu().numpy(), data_np[1]), rep
         assert np.array_equal(rebuilt[1].cpu().numpy(), data_np[3]), rep
+
+
+def test_concurrent_host_threads_on_their_own_streams(gs):
+    """A gs_code is shared between threads; each thread encodes and rebuilds on
+    its own stream (ctypes releases the GIL during the calls)."""
+    import threading
+    k, m, S = 8, 2, (1 << 19) + 37
+    code = gs.gs_make_code(k, m)
+    P = oracle.generator(k, m)
+    n_threads, rounds = 6, 8
+    jobs = []
+    for t in range(n_threads):
+        data_np = [inputs.uniform_bytes_np(4000 + 50 * t + j, S) for j in range(k)]
+        jobs.append((data_np, oracle.encode(P, data_np, nthreads=8), [dev(x) for x in data_np],
+                     [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(m)], torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(t):
+        data_np, want, data, par, stream = jobs[t]
+        try:
+            for _ in range(rounds):
+                for p in par:
+                    p.zero_()
+                torch.cuda.synchronize()
+                gs.gs_encode(code, data, par, S, stream)
+                lost = [t % k, (t + 3) % k]
+                keep = [data[r].clone() for r in lost]
+                stream.synchronize()
+                for r in lost:
+                    data[r].fill_(0xA5)
+                torch.cuda.synchronize()
+                gs.gs_reconstruct(code, data + par, lost, S, stream)
+                stream.synchronize()
+                for i in range(m):
+                    if not np.array_equal(par[i].cpu().numpy(), want[i]):
+                        errors.append((t, "parity", i))
+                for r, orig in zip(lost, keep):
+                    if not torch.equal(data[r], orig):
+                        errors.append((t, "rebuild", r))
+        except Exception as exc:  # noqa: BLE001
+            errors.append((t, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
