@@ -11,6 +11,9 @@
 //   * the path is HBM-bound, so every lane moves 16-byte vectors with
 //     consecutive lanes on consecutive addresses (1 KiB per wavefront per
 //     load); a tile is 256 lanes x U vectors per stream;
+//   * the 1 KiB pieces of a shard are dealt to workgroups with an interleave
+//     that keeps every XCD on one residue class of pieces (see "Work
+//     distribution" below) -- worth 8-10 points of HBM peak on MI355X;
 //   * several streams' loads are issued before any arithmetic so that each
 //     lane keeps 4*U 16-byte loads in flight;
 //   * multiplication by a constant is linear over GF(2), so it is evaluated
