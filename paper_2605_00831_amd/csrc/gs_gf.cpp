@@ -68,8 +68,25 @@ Matrix power_parity_block(int k, int m)
     return p;
 }
 
+// full product table for the matrix routines, filled once from the bitwise multiply
+struct ProductTable {
+    uint8_t v[256][256];
+    ProductTable()
+    {
+        for (int a = 0; a < 256; ++a)
+            for (int b = 0; b < 256; ++b) v[a][b] = gf_mul(static_cast<uint8_t>(a), static_cast<uint8_t>(b));
+    }
+};
+
+static const ProductTable &products()
+{
+    static const ProductTable t;
+    return t;
+}
+
 bool invert_in_place(int n, Matrix &a)
 {
+    const ProductTable &pt = products();
     // augmented elimination: w = [A | I], n x 2n
     const int w2 = 2 * n;
     Matrix w(static_cast<size_t>(n) * w2, 0);
@@ -85,11 +102,11 @@ bool invert_in_place(int n, Matrix &a)
             for (int c = 0; c < w2; ++c) { uint8_t t = w[col * w2 + c]; w[col * w2 + c] = w[piv * w2 + c]; w[piv * w2 + c] = t; }
         const uint8_t s = gf_inv(w[col * w2 + col]);
         if (s != 1)
-            for (int c = col; c < w2; ++c) w[col * w2 + c] = gf_mul(w[col * w2 + c], s);
+            for (int c = col; c < w2; ++c) w[col * w2 + c] = pt.v[s][w[col * w2 + c]];
         for (int r = 0; r < n; ++r) {
             const uint8_t f = w[r * w2 + col];
             if (r == col || f == 0) continue;
-            for (int c = col; c < w2; ++c) w[r * w2 + c] ^= gf_mul(f, w[col * w2 + c]);
+            for (int c = col; c < w2; ++c) w[r * w2 + c] ^= pt.v[f][w[col * w2 + c]];
         }
     }
     for (int r = 0; r < n; ++r)
