@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -28,6 +29,17 @@ int hip_status(hipError_t e)
     if (e == hipSuccess) return GS_OK;
     g_last_hip_error = static_cast<int>(e);
     return e == hipErrorOutOfMemory ? GS_ENOMEM : GS_EHIP;
+}
+
+int caught()
+{
+    try {
+        throw;
+    } catch (const std::bad_alloc &) {
+        return GS_ENOMEM;
+    } catch (...) {
+        return GS_EINVAL;
+    }
 }
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -160,15 +172,14 @@ using namespace gs;
 extern "C" {
 
 int gs_make_code(int k, int m, int kind, gs_code **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (k < 1 || m < 1 || k + m > 256) return GS_EINVAL;
     if (kind != GS_CAUCHY && kind != GS_VANDERMONDE && kind != GS_RDP && kind != GS_POWER) return GS_EINVAL;
     if (kind == GS_RDP && (m != 2 || k > kRdpMaxPrime - 1)) return GS_EINVAL;
     if (kind == GS_POWER && m > 3) return GS_EINVAL;  // beyond that the power matrix is not MDS
-    gs_code *c = new (std::nothrow) gs_code;
-    if (c == nullptr) return GS_ENOMEM;
+    std::unique_ptr<gs_code> c(new gs_code);
     c->k = k;
     c->m = m;
     c->kind = kind;
@@ -179,8 +190,11 @@ int gs_make_code(int k, int m, int kind, gs_code **out)
     }
     else if (kind == GS_POWER) c->P = power_parity_block(k, m);
     else c->P = kind == GS_CAUCHY ? cauchy_parity_block(k, m) : vandermonde_parity_block(k, m);
-    *out = c;
+    *out = c.release();
     return GS_OK;
+}
+catch (...) {
+    return caught();
 }
 
 void gs_free_code(gs_code *code) { delete code; }
@@ -194,13 +208,16 @@ int gs_code_params(const gs_code *code, int *k, int *m)
 }
 
 int gs_make_rdp_code(int k, size_t cell_bytes, gs_code **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (cell_bytes < 16 || (cell_bytes & (cell_bytes - 1)) != 0) return GS_EINVAL;
     const int rc = gs_make_code(k, 2, GS_RDP, out);
     if (rc == GS_OK) (*out)->rdp_cell = cell_bytes;
     return rc;
+}
+catch (...) {
+    return caught();
 }
 
 int gs_rdp_cell_bytes(const gs_code *code, size_t *cell_out)
@@ -219,7 +236,7 @@ int gs_rdp_prime(const gs_code *code, int *p_out)
 
 int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *read_out, int *n_read_out,
                 uint32_t *syndrome_mask_out)
-{
+try {
     if (code == nullptr || !code->is_rdp() || read_out == nullptr || n_read_out == nullptr ||
         syndrome_mask_out == nullptr)
         return GS_EINVAL;
@@ -239,6 +256,9 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
     std::copy(plan.syndrome_mask.begin(), plan.syndrome_mask.end(), syndrome_mask_out);
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_code_matrix(const gs_code *code, uint8_t *P_out)
 {
@@ -249,7 +269,7 @@ int gs_code_matrix(const gs_code *code, uint8_t *P_out)
 
 int gs_decode_matrix(const gs_code *code, const int *erased, int n_erased, uint8_t *R_out,
                      int *survivors_out)
-{
+try {
     if (code == nullptr || code->is_rdp()) return GS_EINVAL;
     std::vector<uint8_t> R;
     std::vector<int> surv;
@@ -259,10 +279,13 @@ int gs_decode_matrix(const gs_code *code, const int *erased, int n_erased, uint8
     if (survivors_out) std::copy(surv.begin(), surv.end(), survivors_out);
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_encode(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes,
               void *stream)
-{
+try {
     if (code == nullptr || data == nullptr || parity == nullptr) return GS_EINVAL;
     if (shard_bytes == 0) return GS_OK;
     for (int j = 0; j < code->k; ++j)
@@ -280,11 +303,14 @@ int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,
                         static_cast<hipStream_t>(stream));
 }
+catch (...) {
+    return caught();
+}
 
 int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_planes, size_t page_bytes,
                     int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
                     void *const *parity, void *stream)
-{
+try {
     if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
     if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard; it has no paged form
     if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
@@ -300,11 +326,14 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
     return apply_matrix_paged(code->m, code->k, code->P.data(), plane_base, n_planes, page_bytes, pages_per_plane,
                               table, pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
 }
+catch (...) {
+    return caught();
+}
 
 int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int n_planes, size_t page_bytes,
                          int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
                          void *const *parity, const int *erased, int n_erased, void *stream)
-{
+try {
     if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
     if (code->is_rdp()) return GS_EINVAL;
     if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
@@ -339,10 +368,13 @@ int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int
     return apply_matrix_paged(n_erased, k, R.data(), plane_base, n_planes, page_bytes, pages_per_plane, table,
                               pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
 }
+catch (...) {
+    return caught();
+}
 
 int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
                    size_t shard_bytes, void *stream)
-{
+try {
     if (code == nullptr || shards == nullptr) return GS_EINVAL;
     if (code->is_rdp()) return rdp_reconstruct(code, shards, erased, n_erased, shard_bytes, static_cast<hipStream_t>(stream));
     std::vector<uint8_t> R;
@@ -362,6 +394,9 @@ int gs_reconstruct(const gs_code *code, void *const *shards, const int *erased, 
     }
     return apply_matrix(n_erased, code->k, R.data(), in.data(), out.data(), shard_bytes,
                         static_cast<hipStream_t>(stream));
+}
+catch (...) {
+    return caught();
 }
 
 const char *gs_strerror(int status)

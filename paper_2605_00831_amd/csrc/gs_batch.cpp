@@ -79,15 +79,14 @@ static int fan_out(gs_pool *p, int n_chunks, hipStream_t stream, PerChunk per_ch
     const int active = std::min(ns, n_chunks);
     GS_TRY(hipEventRecord(p->fork, stream));
     for (int s = 0; s < active; ++s) GS_TRY(hipStreamWaitEvent(p->streams[s], p->fork, 0));
-    for (int c = 0; c < n_chunks; ++c) {
-        const int rc = per_chunk(c, p->streams[c % ns]);
-        if (rc != GS_OK) return rc;
-    }
+    int rc = GS_OK;
+    for (int c = 0; c < n_chunks && rc == GS_OK; ++c) rc = per_chunk(c, p->streams[c % ns]);
+    // join also after a failed chunk, so `stream` still follows what was enqueued
     for (int s = 0; s < active; ++s) {
         GS_TRY(hipEventRecord(p->join[s], p->streams[s]));
         GS_TRY(hipStreamWaitEvent(stream, p->join[s], 0));
     }
-    return GS_OK;
+    return rc;
 }
 
 extern "C" {
@@ -105,7 +104,7 @@ void gs_batch_destroy(gs_batch *b)
 }
 
 int gs_batch_create(const gs_code *code, int max_chunks, gs_batch **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || max_chunks < 1 || max_chunks > 65535) return GS_EINVAL;
@@ -127,10 +126,13 @@ int gs_batch_create(const gs_code *code, int max_chunks, gs_batch **out)
     *out = b;
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_encode_batch(gs_batch *b, int n_chunks, const void *const *data, void *const *parity,
                     const size_t *shard_bytes, void *stream)
-{
+try {
     if (b == nullptr || n_chunks < 0 || n_chunks > b->max_chunks) return GS_EINVAL;
     if (n_chunks == 0) return GS_OK;
     if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
@@ -145,10 +147,13 @@ int gs_encode_batch(gs_batch *b, int n_chunks, const void *const *data, void *co
     return run_batch(b, m, b->code->P.data(), n_chunks, data, k, parity, m, shard_bytes,
                      static_cast<hipStream_t>(stream));
 }
+catch (...) {
+    return caught();
+}
 
 int gs_reconstruct_batch(gs_batch *b, int n_chunks, void *const *shards, const int *erased, int n_erased,
                          const size_t *shard_bytes, void *stream)
-{
+try {
     if (b == nullptr || n_chunks < 0 || n_chunks > b->max_chunks) return GS_EINVAL;
     std::vector<uint8_t> R;
     std::vector<int> surv;
@@ -174,6 +179,9 @@ int gs_reconstruct_batch(gs_batch *b, int n_chunks, void *const *shards, const i
     return run_batch(b, n_erased, R.data(), n_chunks, in.data(), k, out.data(), n_erased, shard_bytes,
                      static_cast<hipStream_t>(stream));
 }
+catch (...) {
+    return caught();
+}
 
 // ---- one stream per chunk (Section 5, "CUDA Streams"; continuous batching) ----
 
@@ -187,14 +195,19 @@ void gs_pool_destroy(gs_pool *p)
 }
 
 int gs_pool_create(int n_streams, gs_pool **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (n_streams < 1 || n_streams > 64) return GS_EINVAL;
     gs_pool *p = new (std::nothrow) gs_pool;
     if (p == nullptr) return GS_ENOMEM;
-    p->streams.assign(n_streams, nullptr);
-    p->join.assign(n_streams, nullptr);
+    try {
+        p->streams.assign(n_streams, nullptr);
+        p->join.assign(n_streams, nullptr);
+    } catch (...) {
+        delete p;
+        throw;
+    }
     int rc = GS_OK;
     auto step = [&](hipError_t e) { if (rc == GS_OK && e != hipSuccess) rc = hip_status(e); };
     for (int s = 0; s < n_streams && rc == GS_OK; ++s) {
@@ -209,10 +222,13 @@ int gs_pool_create(int n_streams, gs_pool **out)
     *out = p;
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_encode_streams(const gs_code *code, gs_pool *pool, int n_chunks, const void *const *data,
                       void *const *parity, const size_t *shard_bytes, void *stream)
-{
+try {
     if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
     if (n_chunks == 0) return GS_OK;
     if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
@@ -222,10 +238,13 @@ int gs_encode_streams(const gs_code *code, gs_pool *pool, int n_chunks, const vo
                          shard_bytes[c], s);
     });
 }
+catch (...) {
+    return caught();
+}
 
 int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, void *const *shards,
                            const int *erased, int n_erased, const size_t *shard_bytes, void *stream)
-{
+try {
     if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
     std::vector<uint8_t> lost;
     const int rc = check_erasures(code, erased, n_erased, lost);
@@ -236,6 +255,9 @@ int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, voi
     return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
         return gs_reconstruct(code, shards + static_cast<size_t>(c) * n, erased, n_erased, shard_bytes[c], s);
     });
+}
+catch (...) {
+    return caught();
 }
 
 }  // extern "C"

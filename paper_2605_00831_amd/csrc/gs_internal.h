@@ -20,6 +20,9 @@ namespace gs {
 
 extern thread_local int g_last_hip_error;
 int hip_status(hipError_t e);
+// status for the exception in flight (call inside a catch block): no C++
+// exception may cross the C boundary
+int caught();
 LaunchShape current_shape();
 
 int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, void *const *out,

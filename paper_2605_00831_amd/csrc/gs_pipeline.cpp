@@ -59,7 +59,7 @@ void gs_pipe_destroy(gs_pipe *p)
 }
 
 int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || chunk_bytes == 0 || chunk_bytes % 16 != 0 || depth < 2 || depth > 64) return GS_EINVAL;
@@ -70,9 +70,14 @@ int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe *
     p->code = code;
     p->chunk_bytes = chunk_bytes;
     p->depth = depth;
-    p->filled.assign(depth, nullptr);
-    p->drained.assign(depth, nullptr);
-    p->used.assign(depth, 0);
+    try {
+        p->filled.assign(depth, nullptr);
+        p->drained.assign(depth, nullptr);
+        p->used.assign(depth, 0);
+    } catch (...) {
+        delete p;
+        throw;
+    }
     int rc = GS_OK;
     auto step = [&](hipError_t e) { if (rc == GS_OK && e != hipSuccess) rc = hip_status(e); };
     step(hipMalloc(reinterpret_cast<void **>(&p->staging), static_cast<size_t>(depth) * code->m * chunk_bytes));
@@ -90,10 +95,13 @@ int gs_pipe_create(const gs_code *code, size_t chunk_bytes, int depth, gs_pipe *
     *out = p;
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_checkpoint(gs_pipe *p, const void *const *data, size_t shard_bytes, void *const *host_parity,
                   void *compute_stream)
-{
+try {
     if (p == nullptr || data == nullptr || host_parity == nullptr) return GS_EINVAL;
     const int k = p->code->k, m = p->code->m;
     for (int j = 0; j < k; ++j)
@@ -126,10 +134,13 @@ int gs_checkpoint(gs_pipe *p, const void *const *data, size_t shard_bytes, void 
     p->any = true;
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_restore(gs_pipe *p, void *const *shards, void *const *host_parity, const int *erased,
                int n_erased, size_t shard_bytes, void *compute_stream)
-{
+try {
     if (p == nullptr || shards == nullptr || host_parity == nullptr) return GS_EINVAL;
     const int k = p->code->k, m = p->code->m;
     std::vector<int> read;  // shard ids the rebuild reads
@@ -177,6 +188,9 @@ int gs_restore(gs_pipe *p, void *const *shards, void *const *host_parity, const 
     p->any = true;
     return GS_OK;
 }
+catch (...) {
+    return caught();
+}
 
 int gs_pipe_sync(gs_pipe *p)
 {
@@ -200,7 +214,7 @@ int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int
                          size_t page_bytes, int64_t pages_per_plane, const int32_t *table,
                          int pages_per_shard, void *const *parity, void *const *host_parity,
                          gs_step_graph **out)
-{
+try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || n_planes < 1 || pages_per_shard < 1 || code->is_rdp()) return GS_EINVAL;
@@ -241,6 +255,9 @@ int gs_step_graph_create(const gs_code *code, const void *const *plane_base, int
     }
     *out = g;
     return GS_OK;
+}
+catch (...) {
+    return caught();
 }
 
 int gs_step_graph_launch(gs_step_graph *g, void *stream)
