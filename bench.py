@@ -186,6 +186,13 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     parity[0].copy_(host[0], non_blocking=True)
     torch.cuda.synchronize()
     h2d = S / (time.perf_counter() - t0) / 1e9
+    # context: shipping the data itself (full replication) instead of the parity
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(k):
+        host[j % m].copy_(data[j], non_blocking=True)
+    torch.cuda.synchronize()
+    replication = time.perf_counter() - t0
     pipe = gs.gs_pipe_create(code, chunk, 2)
     lat = []
     for _ in range(3):
@@ -211,9 +218,43 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
         "frac_of_plain_d2h": round(m * S / ck / 1e9 / d2h, 3),
         "unpipelined_encode_then_copy_ms": round(serial * 1e3, 2),
         "data_GBps_pcie_inclusive": round(k * S / ck / 1e9, 1),
+        "full_replication_d2h_ms": round(replication * 1e3, 2),
+        "replication_over_checkpoint": round(replication / ck, 2),
     }
     log("[bench] checkpoint %.1f ms (parity %.1f GB/s, plain D2H %.1f GB/s, unpipelined %.1f ms)"
         % (ck * 1e3, m * S / ck / 1e9, d2h, serial * 1e3))
+
+    # ---- what the checkpoint costs other GPU work: a stream of HBM-bound 1 GiB device copies
+    # (stand-in for serving kernels), timed alone and while a checkpoint runs beside it
+    a_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    side, cstream = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def side_copies(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            e0.record(side)
+            for _ in range(n):
+                b_buf.copy_(a_buf)
+            e1.record(side)
+        return e0, e1
+
+    e0, e1 = side_copies(50)
+    torch.cuda.synchronize()
+    n_side = max(10, int(0.8 * ck * 1e3 / (e0.elapsed_time(e1) / 50)))
+    e0, e1 = side_copies(n_side)
+    torch.cuda.synchronize()
+    alone_ms = e0.elapsed_time(e1)
+    gs.gs_checkpoint(pipe, data, S, host, cstream.cuda_stream)
+    e0, e1 = side_copies(n_side)
+    gs.gs_pipe_sync(pipe)
+    torch.cuda.synchronize()
+    beside_ms = e0.elapsed_time(e1)
+    res["checkpoint"]["concurrent_work"] = {
+        "what": "%d device copies of 1 GiB on another stream" % n_side, "alone_ms": round(alone_ms, 2),
+        "beside_checkpoint_ms": round(beside_ms, 2), "slowdown": round(beside_ms / alone_ms, 4)}
+    log("[bench] concurrent work: alone %.1f ms, beside a checkpoint %.1f ms" % (alone_ms, beside_ms))
+    del a_buf, b_buf
 
     # ---- restore latency: parity H2D overlapped with reconstruct
     lat = []
@@ -228,6 +269,25 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
                       "parity_h2d_GBps": round(n_par * S / min(lat) / 1e9, 2)}
     log("[bench] restore %.1f ms" % (min(lat) * 1e3))
     gs.gs_pipe_destroy(pipe)
+
+    # ---- hybrid recovery plan from the rates measured above: how many of the leading chunks to
+    # recompute, for recompute costs given as multiples of one chunk's restore time
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    gs.gs_reconstruct(code, shards, erased, S)
+    b.record()
+    torch.cuda.synchronize()
+    n_chunks = (S + chunk - 1) // chunk
+    h2d_s = n_par * chunk / (h2d * 1e9)
+    rec_s = a.elapsed_time(b) * 1e-3 * chunk / S
+    stage = max(h2d_s, rec_s)
+    plan = {}
+    for mult in (0.25, 0.5, 1.0, 2.0, 4.0):
+        r, t = gs.gs_recompute_units(n_chunks, mult * stage, 0.0, 0.0, h2d_s, rec_s)
+        plan["recompute_cost_x%g" % mult] = {"recompute_chunks": r, "makespan_ms": round(t * 1e3, 2)}
+    res["recovery_plan"] = {"n_chunks": n_chunks, "h2d_ms_per_chunk": round(h2d_s * 1e3, 3),
+                            "reconstruct_ms_per_chunk": round(rec_s * 1e3, 3), "plans": plan}
+    log("[bench] recovery plan: " + json.dumps(res["recovery_plan"]))
 
     # ---- the XOR-only RDP code on the same shards (needs k <= 16 and whole stripes)
     if k <= 16 and m >= 2:
@@ -273,7 +333,15 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
                                      % (Ss >> 20, k, k * Ss / 2**30, cpu_s),
                            "gpu_parity_matches_oracle_on_sample": bool(same)}
     log("[bench] oracle on %d threads: %.3f GB/s; GPU parity equal on sample: %s" % (nthreads, k * Ss / cpu_s / 1e9, same))
-    del host_data, want
+    # the same oracle on one thread, on a sixteenth of that sample
+    S1 = max(16, Ss // 16)
+    one = [d[:S1] for d in host_data]
+    t0 = time.perf_counter()
+    oracle.encode(P, one, nthreads=1)
+    one_s = time.perf_counter() - t0
+    res["cpu_baseline"]["one_thread_GBps"] = round(k * S1 / one_s / 1e9, 3)
+    log("[bench] oracle on 1 thread: %.3f GB/s (%.1f s)" % (k * S1 / one_s / 1e9, one_s))
+    del host_data, want, one
 
     # ---- streaming decode-step checkpoint (paged, k=4, m=1), latency over 1000 steps
     res["decode_step"] = decode_steps(torch, gs, inputs, log)

@@ -23,8 +23,12 @@
  *     gs_pipe owns its staging buffers, events and copy stream.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise unless stated.
- *   - Every entry point returns GS_OK (0) or a negative gs_status.  On any
- *     error nothing has been enqueued and no buffer is written.
+ *   - Every entry point returns GS_OK (0) or a negative gs_status; no C++
+ *     exception leaves the library.  Arguments are checked before anything
+ *     is enqueued: after GS_EINVAL, GS_ETOOMANY or GS_ESINGULAR no buffer is
+ *     written.  GS_EHIP / GS_ENOMEM come from the runtime in mid-call: a call
+ *     that issues several launches or copies (wide codes, pipelines, stream
+ *     pools) may by then have enqueued some of them.
  *   - Shard base pointers must be 16-byte aligned; shard_bytes may be any
  *     value (the partial last chunk is masked by bounds, Section 4.2).  Bytes
  *     at offsets >= shard_bytes are neither read nor written.

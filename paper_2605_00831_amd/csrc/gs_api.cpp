@@ -146,6 +146,29 @@ int shards_read(const gs_code *code, const int *erased, int n_erased, std::vecto
     return decode_matrix(code, erased, n_erased, R, read);
 }
 
+int check_encode_args(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes)
+{
+    if (shard_bytes == 0) return GS_OK;
+    for (int j = 0; j < code->k; ++j)
+        if (data[j] == nullptr || !aligned16(data[j])) return GS_EINVAL;
+    for (int i = 0; i < code->m; ++i)
+        if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
+    if (code->is_rdp() && shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    return GS_OK;
+}
+
+int check_rebuild_args(const gs_code *code, void *const *shards, const std::vector<int> &read, const int *erased,
+                       int n_erased, size_t shard_bytes)
+{
+    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
+    for (int s : read)
+        if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
+    for (int x = 0; x < n_erased; ++x)
+        if (shards[erased[x]] == nullptr || !aligned16(shards[erased[x]])) return GS_EINVAL;
+    if (code->is_rdp() && shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    return GS_OK;
+}
+
 static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
                            size_t shard_bytes, hipStream_t stream)
 {
@@ -288,12 +311,9 @@ int gs_encode(const gs_code *code, const void *const *data, void *const *parity,
 try {
     if (code == nullptr || data == nullptr || parity == nullptr) return GS_EINVAL;
     if (shard_bytes == 0) return GS_OK;
-    for (int j = 0; j < code->k; ++j)
-        if (data[j] == nullptr || !aligned16(data[j])) return GS_EINVAL;
-    for (int i = 0; i < code->m; ++i)
-        if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
+    const int rc = check_encode_args(code, data, parity, shard_bytes);
+    if (rc != GS_OK) return rc;
     if (code->is_rdp()) {
-        if (shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
         std::vector<const void *> shards(data, data + code->k);
         shards.push_back(parity[0]);
         shards.push_back(parity[1]);

@@ -233,6 +233,12 @@ try {
     if (n_chunks == 0) return GS_OK;
     if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
     const int k = code->k, m = code->m;
+    // every chunk is checked before the first one is enqueued
+    for (int c = 0; c < n_chunks; ++c) {
+        const int rc = check_encode_args(code, data + static_cast<size_t>(c) * k, parity + static_cast<size_t>(c) * m,
+                                         shard_bytes[c]);
+        if (rc != GS_OK) return rc;
+    }
     return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
         return gs_encode(code, data + static_cast<size_t>(c) * k, parity + static_cast<size_t>(c) * m,
                          shard_bytes[c], s);
@@ -246,12 +252,16 @@ int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, voi
                            const int *erased, int n_erased, const size_t *shard_bytes, void *stream)
 try {
     if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
-    std::vector<uint8_t> lost;
-    const int rc = check_erasures(code, erased, n_erased, lost);
+    std::vector<int> read;
+    const int rc = shards_read(code, erased, n_erased, read);
     if (rc != GS_OK) return rc;
     if (n_chunks == 0 || n_erased == 0) return GS_OK;
     if (shards == nullptr || shard_bytes == nullptr) return GS_EINVAL;
     const int n = code->k + code->m;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int rcc = check_rebuild_args(code, shards + static_cast<size_t>(c) * n, read, erased, n_erased, shard_bytes[c]);
+        if (rcc != GS_OK) return rcc;
+    }
     return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
         return gs_reconstruct(code, shards + static_cast<size_t>(c) * n, erased, n_erased, shard_bytes[c], s);
     });

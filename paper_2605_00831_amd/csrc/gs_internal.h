@@ -30,6 +30,10 @@ int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, vo
 int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost);
 // shard ids a rebuild of `erased` reads (any code kind); validates the list
 int shards_read(const gs_code *code, const int *erased, int n_erased, std::vector<int> &read);
+// pointer / alignment / stripe checks of one encode or one rebuild (`read` from shards_read)
+int check_encode_args(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes);
+int check_rebuild_args(const gs_code *code, void *const *shards, const std::vector<int> &read, const int *erased,
+                       int n_erased, size_t shard_bytes);
 int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &R,
                   std::vector<int> &survivors);
 

@@ -151,3 +151,27 @@ def test_batch_argument_errors(gs):
             assert (t.cpu().numpy() == CANARY).all()
     with pytest.raises(gs.GsError):
         gs.gs_pool_create(0)
+
+
+def test_streams_check_every_chunk_before_enqueueing(gs):
+    """A misaligned pointer in the last chunk: the call fails and the earlier chunks were not run."""
+    k, m, S, n = 4, 2, 4096, 3
+    code = gs.gs_make_code(k, m)
+    pool = gs.gs_pool_create(2)
+    data = [[dev(inputs.uniform_bytes_np(900 + 10 * c + j, S + 16)) for j in range(k)] for c in range(n)]
+    par = [[out_buf(S) for _ in range(m)] for _ in range(n)]
+    bad = [row[:] for row in data]
+    bad[2][1] = data[2][1][1:]                             # base no longer 16-byte aligned
+    torch.cuda.synchronize()
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_encode_streams(code, pool, bad, par, [S] * n)
+    assert e.value.status == gs.GS_EINVAL
+    shards = [d + p for d, p in zip(data, par)]
+    shards[2][0] = data[2][0][1:]
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_reconstruct_streams(code, pool, shards, [4, 5], [S] * n)
+    assert e.value.status == gs.GS_EINVAL
+    torch.cuda.synchronize()
+    for row in par:
+        for t in row:
+            assert (t.cpu().numpy() == CANARY).all()
