@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_prefill",
                     choices=["llama8b_prefill", "llama70b_longctx", "tiny"])
+    ap.add_argument("--code", default="cauchy", choices=["cauchy", "power", "power-tables"],
+                    help="code of the timed step: the canonical Cauchy code (default), the power code "
+                         "(Horner encode kernel), or the power code through the general table kernel")
     ap.add_argument("--no-extras", action="store_true", help="skip PCIe pipelines, paged steps and CPU baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 8 GiB device-to-device copy kernel (counter calibration under rocprofv3 --pmc)")
@@ -83,8 +86,11 @@ def main():
     log("[bench] inputs generated in %.1f s" % (time.perf_counter() - t0))
     shards = data + parity
 
+    kind = gs.GS_CAUCHY if args.code == "cauchy" else gs.GS_POWER
+    gs.gs_set_power_horner(args.code != "power-tables")
+
     def step(ev=None):
-        code = gs.gs_make_code(k, m)
+        code = gs.gs_make_code(k, m, kind)
         gs.gs_decode_matrix(code, erased)
         if ev:
             ev[0].record()
@@ -135,14 +141,16 @@ def main():
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": args.workload, "k": k, "m": m, "shard_bytes": S, "kv_dtype": cfg["dtype"],
-                   "erased": erased, "launch": "gs_encode + gs_reconstruct, default launch shape"},
+                   "erased": erased, "code": args.code,
+                   "launch": "gs_encode + gs_reconstruct, default launch shape"},
         "encode_GBps_data": round(k * S / (enc_avg * 1e-3) / 1e9, 1),
         "reconstruct_GBps_data": round(k * S / (rec_avg * 1e-3) / 1e9, 1),
         "encode_ms": round(enc_avg, 4),
         "reconstruct_ms": round(rec_avg, 4),
         "reconstruct_hbm_frac": round(rec_alg_bytes / (rec_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "roofline": {
-            "kernel": "apply_contig_kernel (encode, k=%d m=%d)" % (k, m),
+            "kernel": "%s (encode, k=%d m=%d)" % ("horner_contig_kernel" if args.code == "power" and m >= 2
+                                                   else "apply_contig_kernel", k, m),
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,

@@ -327,6 +327,12 @@ int gs_coef_words(int c, uint32_t *words_out);
  *                     pieces, default 5; at most 10)
  * Results are identical for every setting. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
+/* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
+ * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0
+ * with g = 2^r; one packed multiply-by-2 per stream and row, no table
+ * lookups).  enable = 0 sends those encodes through the general matrix kernel
+ * instead; the parity bytes are the same either way.  Default: enabled. */
+int gs_set_power_horner(int enable);
 
 #ifdef __cplusplus
 }

@@ -25,7 +25,7 @@ EXPORTS = [
     "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
     "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
     "gs_recompute_units",
-    "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape",
+    "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape", "gs_set_power_horner",
 ]
 
 _vp = ctypes.c_void_p
@@ -112,6 +112,7 @@ def lib():
     L.gs_last_hip_error.argtypes = []
     L.gs_coef_words.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
     L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.gs_set_power_horner.argtypes = [ctypes.c_int]
     _lib = L
     return L
 
@@ -425,6 +426,10 @@ def gs_coef_words(c):
     w = (ctypes.c_uint32 * 5)()
     _check(lib().gs_coef_words(c, w), "gs_coef_words")
     return list(w)
+
+
+def gs_set_power_horner(enable=True):
+    _check(lib().gs_set_power_horner(1 if enable else 0), "gs_set_power_horner")
 
 
 def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1, interleave_shift=-1):

@@ -24,6 +24,9 @@ static LaunchShape g_shape = g_default_shape;
 
 LaunchShape current_shape() { return g_shape; }
 
+// power-code encodes go through the Horner kernel unless switched off
+static bool g_power_horner = true;
+
 int hip_status(hipError_t e)
 {
     if (e == hipSuccess) return GS_OK;
@@ -320,6 +323,9 @@ try {
         return hip_status(launch_rdp(code->rdp_encode, shards.data(), shard_bytes, code->rdp_cell, current_shape(),
                                          static_cast<hipStream_t>(stream)));
     }
+    if (code->kind == GS_POWER && g_power_horner && code->m >= 2 && code->k <= kLaunchMaxK)
+        return hip_status(launch_horner(code->m, code->k, code->P.data(), code->k, data, parity, shard_bytes,
+                                        current_shape(), static_cast<hipStream_t>(stream)));
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,
                         static_cast<hipStream_t>(stream));
 }
@@ -456,6 +462,12 @@ int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int inter
         s.interleave_shift = interleave_shift;
     }
     g_shape = s;
+    return GS_OK;
+}
+
+int gs_set_power_horner(int enable)
+{
+    g_power_horner = enable != 0;
     return GS_OK;
 }
 

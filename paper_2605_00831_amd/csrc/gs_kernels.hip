@@ -22,7 +22,10 @@
 //     the instruction's two source registers); the tables arrive as kernel
 //     arguments and are read with scalar loads;
 //   * a matrix row of all ones (row 0 of the parity block; the one-parity
-//     code) is a plain XOR and skips the lookups.
+//     code) is a plain XOR and skips the lookups;
+//   * the power code P[r][j] = 2^(r*j) has a second encode kernel that
+//     evaluates its rows by Horner's rule with a packed multiply-by-2 and no
+//     tables (fewer vector instructions; the same HBM-bound launch time).
 #include <hip/hip_runtime.h>
 #include "gs_gf.h"
 #include "gs_launch.h"
@@ -153,6 +156,38 @@ __device__ __forceinline__ void mac(Acc4 (&acc)[M][U], const u32x4 (&x)[U],
     }
 }
 
+// 2 (x) each of the four bytes of x: shift left inside every byte and fold the
+// bit shifted out of a byte back in as the field polynomial's low part, 0x1D.
+__device__ __forceinline__ uint32_t times2(uint32_t x)
+{
+    const uint32_t hi = x & 0x80808080u;
+    return ((x ^ hi) << 1) ^ ((hi >> 7) * 0x1Du);
+}
+
+// One Horner step of the power code P[r][j] = 2^(r*j), streams taken from the
+// last to the first: acc[r] = 2^r (x) acc[r] ^ x.  No tables, and the work per
+// row does not depend on the coefficients.
+template <int M, int U>
+__device__ __forceinline__ void horner_step(Acc4 (&acc)[M][U], const u32x4 (&x)[U])
+{
+    static_assert(M >= 2 && M <= 3, "power code rows");
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t d = x[u][c];
+            acc[0][u].c[c] ^= d;
+            pin(acc[0][u].c[c]);
+            acc[1][u].c[c] = times2(acc[1][u].c[c]) ^ d;
+            pin(acc[1][u].c[c]);
+            if (M > 2) {
+                acc[2][u].c[c] = times2(times2(acc[2][u].c[c])) ^ d;
+                pin(acc[2][u].c[c]);
+            }
+        }
+    }
+}
+
 constexpr int kBatch = 4;  // streams whose loads are issued together
 
 // One tile over contiguous streams: each lane handles the U vectors v[0..U).
@@ -160,7 +195,9 @@ constexpr int kBatch = 4;  // streams whose loads are issued together
 // that reach past the end of the shard take the predicated form.
 // S names where the stream pointers and the length live: the kernel arguments
 // (ApplyArgs) or a per-chunk descriptor in device memory (BatchDesc).
-template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, class S>
+// HORNER: the matrix is the power code's and is evaluated by horner_step over
+// the streams in descending order instead of through the tables.
+template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, bool HORNER, class S>
 __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
                                             int k, int accumulate, const uint64_t (&v)[U])
 {
@@ -185,7 +222,7 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
     for (; j + kBatch <= k; j += kBatch) {
         const uint8_t *src[kBatch];
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) src[b] = s.in[j + b];
+        for (int b = 0; b < kBatch; ++b) src[b] = s.in[HORNER ? k - 1 - (j + b) : j + b];
         u32x4 x[kBatch][U];
 #pragma unroll
         for (int b = 0; b < kBatch; ++b)
@@ -195,17 +232,21 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
                 if (ok[u]) x[b][u] = load16<NT>(src[b], v[u]);
             }
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], tab, j + b);
+        for (int b = 0; b < kBatch; ++b) {
+            if constexpr (HORNER) horner_step<M, U>(acc, x[b]);
+            else mac<M, ROW0_XOR, U>(acc, x[b], tab, j + b);
+        }
     }
     for (; j < k; ++j) {
-        const uint8_t *src = s.in[j];
+        const uint8_t *src = s.in[HORNER ? k - 1 - j : j];
         u32x4 x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u] = u32x4{0, 0, 0, 0};
             if (ok[u]) x[u] = load16<NT>(src, v[u]);
         }
-        mac<M, ROW0_XOR, U>(acc, x, tab, j);
+        if constexpr (HORNER) horner_step<M, U>(acc, x);
+        else mac<M, ROW0_XOR, U>(acc, x, tab, j);
     }
 
 #pragma unroll
@@ -234,7 +275,7 @@ constexpr int kWavesPerEu()
 // i.e. every NX-th piece inside a super-tile of NX*4U pieces, wavefront w
 // taking q = w*U .. w*U+U-1.  All NX tiles of a super-tile together cover it
 // exactly once.  nx_shift = 0 gives plain consecutive tiles.
-template <int M, bool ROW0_XOR, int U, bool NT, class S>
+template <int M, bool ROW0_XOR, int U, bool NT, bool HORNER, class S>
 __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
                                                int k, int accumulate, uint32_t tiles_per_wg, bool last_wg)
 {
@@ -256,8 +297,8 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
 #pragma unroll
         for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << nx_shift) + r) << 6) + lane;
         const uint64_t super_end = (((g + 1) * kPieces) << nx_shift) * 64;
-        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true>(s, tab, k, accumulate, v);
-        else contig_tile<M, ROW0_XOR, U, NT, false>(s, tab, k, accumulate, v);
+        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER>(s, tab, k, accumulate, v);
+        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER>(s, tab, k, accumulate, v);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
@@ -282,7 +323,17 @@ template <int M, bool ROW0_XOR, int U, bool NT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
 void apply_contig_kernel(const ApplyArgs a)
 {
-    contig_streams<M, ROW0_XOR, U, NT>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, U, NT, false>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+}
+
+// Power-code encode by Horner's rule (rows 1, 2^j, 4^j): same tiles, same
+// loads and stores, no table lookups.  The tables are still passed: the up to
+// 15 bytes after the last whole vector go through the per-byte path.
+template <int M, int U, bool NT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, true, U>(), 8)))
+void horner_contig_kernel(const ApplyArgs a)
+{
+    contig_streams<M, true, U, NT, true>(a, a.tab, a.k, 0, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
 }
 
 // Many independent chunks in one launch (one request's chunk, or one chunk of
@@ -296,7 +347,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWaves
 void apply_batch_kernel(const BatchArgs a)
 {
     ConstDesc d = (ConstDesc)a.descs + blockIdx.y;
-    contig_streams<M, ROW0_XOR, U, NT>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, U, NT, false>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
 }
 
 // One tile of the paged gather.  A lane whose vector index is past the end of
@@ -602,6 +653,47 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
     return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), stream);
+}
+
+hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, const void *const *in,
+                         void *const *out, size_t bytes, const LaunchShape &shape, hipStream_t stream)
+{
+    if (rows < 2 || rows > 3 || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
+    // the kernel hard-wires the matrix: refuse anything but 2^(r*j)
+    for (int r = 0; r < rows; ++r) {
+        uint8_t g = 1, want = 1;
+        for (int i = 0; i < r; ++i) g = gf_mul(g, 2);
+        for (int j = 0; j < k; ++j) {
+            if (coef[r * coef_stride + j] != want) return hipErrorInvalidValue;
+            want = gf_mul(want, g);
+        }
+    }
+    if (bytes == 0) return hipSuccess;
+    ApplyArgs a;
+    fill_rows(a, rows, k, coef, coef_stride, out);  // row 0 is all ones, so the row order is kept
+    for (int j = 0; j < kLaunchMaxK; ++j) a.in[j] = j < k ? static_cast<const uint8_t *>(in[j]) : nullptr;
+    a.nvec = bytes / 16;
+    a.tail = static_cast<uint32_t>(bytes % 16);
+    a.k = k;
+    a.accumulate = 0;
+    const int unroll = sane_unroll(shape.unroll, rows);
+    uint32_t nx_shift;
+    uint64_t tiles;
+    interleave_for(a.nvec, unroll, shape.interleave_shift, nx_shift, tiles);
+    uint32_t tpw = shape.tiles_per_wg > 0 ? static_cast<uint32_t>(shape.tiles_per_wg) : 1u, wgs = 1;
+    grid_for(tiles, tpw, wgs);
+    a.tiles_per_wg = tpw;
+    a.nx_shift = nx_shift;
+    const bool nt = shape.nontemporal != 0;
+#define GS_HORNER(M_, U_)                                                                                     \
+    if (rows == M_ && unroll == U_) {                                                                         \
+        if (nt) hipLaunchKernelGGL((horner_contig_kernel<M_, U_, true>), dim3(wgs), dim3(kThreads), 0, stream, a); \
+        else hipLaunchKernelGGL((horner_contig_kernel<M_, U_, false>), dim3(wgs), dim3(kThreads), 0, stream, a);   \
+        return hipGetLastError();                                                                             \
+    }
+    GS_HORNER(2, 1) GS_HORNER(2, 2) GS_HORNER(3, 1) GS_HORNER(3, 2)
+#undef GS_HORNER
+    return hipErrorInvalidValue;
 }
 
 template <int M, bool X, int U, bool NT>

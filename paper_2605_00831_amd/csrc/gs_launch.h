@@ -23,6 +23,11 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
                         const void *const *in, void *const *out, size_t bytes,
                         bool accumulate, const LaunchShape &shape, hipStream_t stream);
 
+// Encode of the power code (coef must be P[r][j] = 2^(r*j), 2 <= rows <= 3,
+// k <= kLaunchMaxK) by Horner's rule instead of table lookups; same bytes out.
+hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, const void *const *in,
+                         void *const *out, size_t bytes, const LaunchShape &shape, hipStream_t stream);
+
 // A stream of the paged variant: the pages named by row `table_row` of the
 // block table (table_row >= 0), or a dense device buffer laid out
 // [plane][slot][page bytes] like the parity buffers (table_row < 0).

@@ -98,3 +98,57 @@ def test_power_code_on_the_gpu():
         oracle.reconstruct(P, work, lost)
         for r in lost:
             assert np.array_equal(work[r], data_np[r])
+
+
+HORNER_SIZES = [1, 15, 16, 17, 4095, 8192, 70001, 256 * 32 * 32 * 2 + 48 + 7, (3 << 20) + 5]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("k,m", [(1, 2), (2, 2), (4, 2), (5, 3), (8, 3), (13, 2), (16, 3)])
+def test_horner_encode_equals_oracle_and_matrix_kernel(k, m):
+    """The Horner kernel (default for power codes with m >= 2, k <= 16) against the oracle's
+    matrix encode, at sizes from one byte to several interleaved super-tiles with ragged ends,
+    for one and two vectors per lane; canaries after every parity buffer; and the same bytes
+    from the general matrix kernel with the Horner path switched off."""
+    torch = pytest.importorskip("torch")
+    code = gs.gs_make_code(k, m, gs.GS_POWER)
+    P = oracle.power_generator(k, m)
+    pad, canary = 64, 0x3C
+    try:
+        for S in HORNER_SIZES:
+            data_np = [inputs.uniform_bytes_np(7000 + 17 * k + j, S) for j in range(k)]
+            want = oracle.encode(P, data_np, nthreads=8)
+            data = [torch.from_numpy(np.concatenate([x, np.zeros((-S) % 16, np.uint8)])).cuda() for x in data_np]
+            for unroll in (1, 2):
+                gs.gs_set_launch_shape(unroll=unroll)
+                for horner in (True, False):
+                    gs.gs_set_power_horner(horner)
+                    par = [torch.full((S + pad,), canary, dtype=torch.uint8, device="cuda") for _ in range(m)]
+                    gs.gs_encode(code, data, par, S)
+                    torch.cuda.synchronize()
+                    for i in range(m):
+                        got = par[i].cpu().numpy()
+                        assert np.array_equal(got[:S], want[i]), (k, m, S, unroll, horner, i)
+                        assert (got[S:] == canary).all(), (k, m, S, unroll, horner, i)
+    finally:
+        gs.gs_set_power_horner(True)
+        gs.gs_set_launch_shape()
+
+
+@pytest.mark.gpu
+def test_horner_in_the_checkpoint_pipeline():
+    """gs_checkpoint encodes through gs_encode, so a power code takes the Horner kernel there too."""
+    torch = pytest.importorskip("torch")
+    k, m, S, chunk = 8, 2, (5 << 16) + 4096 + 80, 1 << 16
+    code = gs.gs_make_code(k, m, gs.GS_POWER)
+    P = oracle.power_generator(k, m)
+    data_np = [inputs.uniform_bytes_np(8100 + j, S) for j in range(k)]
+    want = oracle.encode(P, data_np, nthreads=8)
+    data = [torch.from_numpy(x).cuda() for x in data_np]
+    host = [torch.zeros(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    gs.gs_checkpoint(pipe, data, S, host)
+    gs.gs_pipe_sync(pipe)
+    for i in range(m):
+        assert np.array_equal(host[i].numpy(), want[i])
+    gs.gs_pipe_destroy(pipe)
