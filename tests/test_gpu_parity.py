@@ -470,3 +470,43 @@ def test_paged_reconstruct_errors_and_noop(gs):
     assert not plane.cpu().numpy().any()
     for b in par:
         assert (b.cpu().numpy() == CANARY).all()
+
+
+def test_one_code_shared_by_host_threads(gs):
+    """A gs_code is immutable: four host threads encode and rebuild through the same handle,
+    each on a stream of its own (ctypes drops the interpreter lock during the calls)."""
+    import threading
+    k, m, S, rounds = 8, 3, (1 << 18) + 4096 + 21, 6
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    errors = []
+
+    def worker(tid):
+        try:
+            stream = torch.cuda.Stream()
+            for rnd in range(rounds):
+                data_np = [inputs.uniform_bytes_np(40000 + 1000 * tid + 10 * rnd + j, S) for j in range(k)]
+                with torch.cuda.stream(stream):
+                    data = [torch.from_numpy(x).cuda() for x in data_np]
+                    par = [torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(m)]
+                    gs.gs_encode(code, data, par, S, stream=stream)
+                    pat = [(tid + rnd) % k, k + (rnd % m), (tid + rnd + 3) % k]
+                    pat = sorted(set(pat))
+                    for r in pat:
+                        (data + par)[r].fill_(0x5A)
+                    gs.gs_reconstruct(code, data + par, pat, S, stream=stream)
+                    stream.synchronize()
+                    want = oracle.encode(P, data_np)
+                    full = data_np + want
+                    for r in range(k + m):
+                        if not np.array_equal((data + par)[r].cpu().numpy(), full[r]):
+                            errors.append((tid, rnd, r))
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append((tid, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
