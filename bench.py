@@ -491,6 +491,9 @@ def decode_steps(torch, gs, inputs, log):
         for i in range(m):
             host[i].copy_(par[i], non_blocking=True)
     res["eager_encode_d2h"] = run(eager_d2h)
+    # the kernel writes its parity straight into pinned host memory: no staging buffer, no copy
+    res["eager_encode_into_pinned_host"] = run(lambda: gs.gs_encode_paged(
+        code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, host))
     g0 = gs.gs_step_graph_create(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, par, None)
     res["graph_encode_only"] = run(lambda: gs.gs_step_graph_launch(g0))
     g1 = gs.gs_step_graph_create(code, base, n_planes, slot_bytes, pages_per_plane, table, seqs_per_shard, par, host)

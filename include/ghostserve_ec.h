@@ -14,9 +14,15 @@
  * are all ones.  With m = 1 that is exactly XOR parity.
  *
  * General conventions
- *   - "DEVICE" pointers are HIP device addresses on the current device,
+ *   - "DEVICE" pointers are addresses the current device can access,
  *     "HOST" pointers are ordinary host addresses, "PINNED" host pointers come
- *     from hipHostMalloc (or an equivalent page-locked allocation).
+ *     from hipHostMalloc (or an equivalent page-locked allocation).  Pinned
+ *     memory is mapped into the device's address space, so a PINNED pointer
+ *     is accepted wherever a DEVICE pointer is: an encode whose parity[]
+ *     entries are pinned buffers writes the parity over PCIe from the kernel
+ *     itself, with no staging buffer and no copy.  That saves a copy launch
+ *     per small step; for bulk data the pipelines below keep the kernel short
+ *     and leave the transfer to the copy engine.
  *   - Pointer arrays (data[], parity[], shards[]) are HOST arrays holding
  *     DEVICE pointers; they are read during the call and may be freed on return.
  *   - The caller owns every buffer.  A gs_code owns no device memory; a

@@ -244,3 +244,43 @@ def test_concurrent_host_threads_on_their_own_streams(gs):
     for th in threads:
         th.join()
     assert not errors, errors
+
+
+def test_kernels_write_parity_straight_into_pinned_host_memory(gs):
+    """Pinned host buffers passed as parity[] (contiguous and paged encode) and as the erased
+    entry of a rebuild: the kernels write them over PCIe themselves; bytes past the end stay."""
+    k, m, S = 4, 2, (1 << 18) + 4096 + 13
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    data_np = [inputs.uniform_bytes_np(61000 + j, S) for j in range(k)]
+    want = oracle.encode(P, data_np)
+    data = [dev(x) for x in data_np]
+    host = [pinned(S) for _ in range(m)]
+    gs.gs_encode(code, data, host, S)
+    torch.cuda.synchronize()
+    for i in range(m):
+        assert np.array_equal(host[i].numpy()[:S], want[i])
+        assert (host[i].numpy()[S:] == 0x5A).all()
+    # rebuild data shard 2 and parity 1 from device data and the pinned parity 0
+    lost = pinned(S)
+    shards = data[:2] + [lost] + data[3:] + [host[0], pinned(S)]
+    gs.gs_reconstruct(code, shards, [2, 5], S)
+    torch.cuda.synchronize()
+    assert np.array_equal(lost.numpy()[:S], data_np[2]) and (lost.numpy()[S:] == 0x5A).all()
+    assert np.array_equal(shards[5].numpy()[:S], want[1])
+
+    # paged decode-step shape
+    n_planes, pps, page, n_pages = 6, 5, 2048, 64
+    planes_np = [inputs.kv_bytes_np(62000 + p, n_pages * page, "bf16", 1.0) for p in range(n_planes)]
+    planes = [dev(x) for x in planes_np]
+    base = torch.tensor([x.data_ptr() for x in planes], dtype=torch.int64, device="cuda")
+    table_np = np.random.default_rng(9).permutation(n_pages)[: k * pps].reshape(k, pps).astype(np.int32)
+    table = torch.from_numpy(table_np).cuda()
+    out_bytes = n_planes * pps * page
+    hp = [pinned(out_bytes) for _ in range(m)]
+    gs.gs_encode_paged(code, base, n_planes, page, n_pages, table, pps, hp)
+    torch.cuda.synchronize()
+    wantp = oracle.encode_paged(P, planes_np, page, table_np)
+    for i in range(m):
+        assert np.array_equal(hp[i].numpy()[:out_bytes], wantp[i])
+        assert (hp[i].numpy()[out_bytes:] == 0x5A).all()
