@@ -451,7 +451,8 @@ def decode_steps(torch, gs, inputs, log):
     n_planes = c["layers"] * 2
     block_tokens, slot_bytes = c["block_tokens"], 8 * 128 * 2
     seqs_per_shard = c["batch"] // k
-    n_blocks = c["batch"] * 8  # a few blocks per sequence in the pool
+    blocks_per_seq = (steps + 20 + block_tokens - 1) // block_tokens  # every step writes a fresh token slot
+    n_blocks = c["batch"] * blocks_per_seq
     pages_per_plane = n_blocks * block_tokens
     dev = "cuda:0"
     pool = inputs.kv_bytes_device(inputs.config_seed("decode_paged"), n_planes * pages_per_plane * slot_bytes,
@@ -459,9 +460,11 @@ def decode_steps(torch, gs, inputs, log):
     plane_bytes = pages_per_plane * slot_bytes
     base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(n_planes)], dtype=torch.int64, device=dev)
     rng = np.random.default_rng(inputs.config_seed("decode_paged") + inputs.TABLE_SEED_OFFSET)
-    blocks = rng.permutation(n_blocks)[: c["batch"]].reshape(k, seqs_per_shard)
-    tables = torch.from_numpy(np.stack([(blocks * block_tokens + (s % block_tokens)).astype(np.int32)
-                                        for s in range(block_tokens)])).to(dev)
+    # sequence q owns blocks_per_seq blocks scattered over the pool; at step s it writes slot
+    # s mod 16 of its block s div 16, so no page is touched twice during the run
+    blocks = rng.permutation(n_blocks).reshape(blocks_per_seq, k, seqs_per_shard)
+    tables = torch.from_numpy(np.stack([(blocks[s // block_tokens] * block_tokens + (s % block_tokens)).astype(np.int32)
+                                        for s in range(steps + 20)])).to(dev)
     table = tables[0].clone()
     out_bytes = n_planes * seqs_per_shard * slot_bytes
     par = [torch.empty(out_bytes, dtype=torch.uint8, device=dev) for _ in range(m)]
@@ -472,7 +475,7 @@ def decode_steps(torch, gs, inputs, log):
     def run(fn):
         lat = []
         for s in range(steps + 20):
-            table.copy_(tables[s % block_tokens])  # the engine moves every sequence to its next slot
+            table.copy_(tables[s])  # the engine moves every sequence to its next slot
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             fn()
