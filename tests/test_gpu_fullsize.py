@@ -1,7 +1,10 @@
 """GPU parity at the full sizes of the measured workloads, in the launch
 configuration bench.py times (default launch shape, one launch per call).
 
-The oracle cannot encode 32-40 GiB in seconds, so these tests check
+These tests check
+  - every parity byte of the 32 GiB and 40 GiB workloads against the oracle,
+    streamed through the host in 256 MiB pieces (about 15 s per workload on
+    16 host threads);
   - sampled windows (shard starts and ends, both sides of the 4 GiB offset,
     seeded random offsets with odd lengths) byte for byte against the oracle
     on the same bytes copied to the host;
@@ -76,6 +79,19 @@ def check_folds(P, data, parity):
         assert np.array_equal(xor_fold(parity[i]), want[i]), "fold of parity %d differs" % i
 
 
+def check_every_byte(P, data, parity, S, piece=256 << 20):
+    """The whole parity against the oracle, piece by piece: the data piece goes to the host,
+    the oracle encodes it on the host cores, the result must equal the GPU's parity piece."""
+    m = P.shape[0]
+    for off in range(0, S, piece):
+        n = min(piece, S - off)
+        host = [np.ascontiguousarray(d[off:off + n].cpu().numpy()) for d in data]
+        want = oracle.encode(P, host, nthreads=16)
+        for i in range(m):
+            got = parity[i][off:off + n].cpu().numpy()
+            assert np.array_equal(got, want[i]), "parity %d differs in the piece at %d" % (i, off)
+
+
 def run_bulk(gs, name):
     cfg = inputs.CONFIGS[name]
     k, m = cfg["k"], cfg["m"]
@@ -95,6 +111,7 @@ def run_bulk(gs, name):
     torch.cuda.synchronize()
     check_windows(P, data, parity, S, inputs.config_seed(name))
     check_folds(P, data, parity)
+    check_every_byte(P, data, parity, S)
     # lose two data shards (failure = flushed buffers), rebuild in place, compare
     lost = [1, k - 1]
     keep = [data[r].clone() for r in lost]
