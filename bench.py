@@ -29,8 +29,10 @@ PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 # HBM traffic of one encode launch measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE, scaled by a plain copy kernel of known size; see
 # profiles/encode_contig_llama8b_prefill.md.  Bytes per launch, or None.
-MEASURED_TRAFFIC_BYTES = {
-    "llama8b_prefill": 51539161269,   # FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000, KiB -> bytes
+MEASURED_TRAFFIC_BYTES = {   # (workload, code): FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000, KiB -> bytes
+    ("llama8b_prefill", "cauchy"): 51539161269,
+    ("llama8b_prefill", "power"): 51539042211,    # profiles/horner_power_code_llama8b_prefill.md
+    ("llama70b_longctx", "cauchy"): 53686381435,  # profiles/kernels_other_workloads.md
 }
 
 
@@ -156,7 +158,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.code)),
             "algorithmic_bytes_per_launch": enc_alg_bytes,
             "avg_launch_ms": round(enc_avg, 4),
         },
