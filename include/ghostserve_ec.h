@@ -331,7 +331,9 @@ int gs_coef_words(int c, uint32_t *words_out);
  *   interleave_shift  log2 of the modulus with which the contiguous kernel
  *                     deals 1 KiB pieces to workgroups (0 = consecutive
  *                     pieces, default 5; at most 10)
- * Results are identical for every setting. */
+ * Results are identical for every setting.  Process-wide and unsynchronised
+ * (as is gs_set_power_horner): set them while no other thread is inside the
+ * library. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
 /* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
  * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0
