@@ -262,7 +262,11 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
  * pointers and lengths travel in a descriptor array that the gs_batch owns
  * (device buffer + pinned host mirror, a ring of 4 slots so that consecutive
  * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only,
- * max_chunks <= 65535.  One gs_batch serves one thread at a time.
+ * max_chunks <= 65535.  One gs_batch serves one thread at a time.  The
+ * descriptor slot is filled by the host at call time and may make the host
+ * wait for the launch that used it four calls earlier, so these two calls
+ * must not be made on a stream that is being captured into a graph (the
+ * single-chunk entry points and the stream-pool form can be).
  *   data     HOST array of n_chunks*k DEVICE pointers, chunk-major
  *   parity   HOST array of n_chunks*m DEVICE pointers, chunk-major
  *   shards   HOST array of n_chunks*(k+m) DEVICE pointers, chunk-major, same
