@@ -266,7 +266,7 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
  * descriptor slot is filled by the host at call time and may make the host
  * wait for the launch that used it four calls earlier, so these two calls
  * must not be made on a stream that is being captured into a graph (the
- * single-chunk entry points and the stream-pool form can be).
+ * single-chunk entry points can be).
  *   data     HOST array of n_chunks*k DEVICE pointers, chunk-major
  *   parity   HOST array of n_chunks*m DEVICE pointers, chunk-major
  *   shards   HOST array of n_chunks*(k+m) DEVICE pointers, chunk-major, same
