@@ -164,6 +164,13 @@ def main():
         },
     }
 
+    # the paper's own headline figures, on its hardware: context, not a target and not comparable
+    out["paper_context"] = {
+        "checkpoint_latency_gain_vs_cpu_replication": "2.7x (prefill, average; Section 6.2)",
+        "recovery_latency_gain": "2.1x (single batch; abstract and Section 6.2; the conclusion swaps the two figures)",
+        "hardware": "8x NVIDIA H200 over NVLink, host link PCIe Gen 4; end-to-end serving latencies, "
+                    "no kernel GB/s is printed in the paper's text",
+    }
     if not args.no_extras:
         out.update(extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log))
 
