@@ -219,6 +219,12 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
         gs.gs_pipe_sync(pipe)
         lat.append(time.perf_counter() - t0)
     ck = min(lat)
+    # the same pipeline once more with its per-chunk timing on: when each chunk's encode ran and
+    # when its parity had landed in host memory (ms since the call began)
+    gs.gs_pipe_set_timing(pipe, True)
+    gs.gs_checkpoint(pipe, data, S, host)
+    timeline = gs.gs_pipe_chunk_times(pipe)
+    gs.gs_pipe_set_timing(pipe, False)
     # serial reference: encode everything, then copy everything
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -235,6 +241,9 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
         "frac_of_plain_d2h": round(m * S / ck / 1e9 / d2h, 3),
         "unpipelined_encode_then_copy_ms": round(serial * 1e3, 2),
         "data_GBps_pcie_inclusive": round(k * S / ck / 1e9, 1),
+        "timeline_ms": [{"chunk": c, "encode": [round(kb, 2), round(ke, 2)], "parity_in_host_memory": round(ce, 2)}
+                        for c, (kb, ke, ce) in enumerate(timeline)],
+        "encode_busy_ms": round(sum(ke - kb for kb, ke, _ in timeline), 2),
         "full_replication_d2h_ms": round(replication * 1e3, 2),
         "replication_over_checkpoint": round(replication / ck, 2),
     }

@@ -198,6 +198,19 @@ int gs_restore(gs_pipe *pipe, void *const *shards, void *const *host_parity,
 int gs_pipe_sync(gs_pipe *pipe);
 /* hipEvent_t (as void*) recorded after the last operation enqueued so far */
 void *gs_pipe_done_event(gs_pipe *pipe);
+/* Per-chunk timeline of a pipe (off by default).  With timing enabled, every
+ * later gs_checkpoint / gs_restore call records timing events around each
+ * chunk's kernel on the compute stream and after each chunk's copies on the
+ * copy stream.  gs_pipe_chunk_times waits for the last call to finish and
+ * returns, for its first min(n_chunks, max_chunks) chunks, milliseconds since
+ * the call began on the compute stream: when the chunk's encode / reconstruct
+ * kernel began and ended, and when its parity copy (D2H for a checkpoint, H2D
+ * for a restore) ended.  Any of the three arrays may be NULL; *n_chunks_out is
+ * the number of chunks of that call (0 if none was timed).  This is how the
+ * overlap of Alg. 1's encode with its asynchronous PCIe copy is observed. */
+int gs_pipe_set_timing(gs_pipe *pipe, int enable);
+int gs_pipe_chunk_times(gs_pipe *pipe, int max_chunks, float *kernel_begin_ms, float *kernel_end_ms,
+                        float *copy_end_ms, int *n_chunks_out);
 
 /* ---- captured per-step checkpoint (Section 5: graphs for fixed-size chunks)
  * Captures gs_encode_paged (+ optional D2H of the m parity buffers into

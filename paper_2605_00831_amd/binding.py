@@ -20,7 +20,7 @@ EXPORTS = [
     "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_make_rdp_code", "gs_rdp_prime", "gs_rdp_cell_bytes", "gs_rdp_plan",
     "gs_encode", "gs_encode_paged", "gs_reconstruct", "gs_reconstruct_paged",
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
-    "gs_pipe_done_event",
+    "gs_pipe_done_event", "gs_pipe_set_timing", "gs_pipe_chunk_times",
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
     "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
     "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
@@ -89,6 +89,9 @@ def lib():
     L.gs_pipe_sync.argtypes = [_vp]
     L.gs_pipe_done_event.argtypes = [_vp]
     L.gs_pipe_done_event.restype = _vp
+    _fp = ctypes.POINTER(ctypes.c_float)
+    L.gs_pipe_set_timing.argtypes = [_vp, ctypes.c_int]
+    L.gs_pipe_chunk_times.argtypes = [_vp, ctypes.c_int, _fp, _fp, _fp, _intp]
     L.gs_step_graph_create.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp,
                                        ctypes.c_int, _vpp, _vpp, ctypes.POINTER(_vp)]
     L.gs_step_graph_launch.argtypes = [_vp, _vp]
@@ -297,6 +300,20 @@ def gs_pipe_sync(pipe):
 
 def gs_pipe_done_event(pipe):
     return lib().gs_pipe_done_event(pipe.handle)
+
+
+def gs_pipe_set_timing(pipe, enable=True):
+    _check(lib().gs_pipe_set_timing(pipe.handle, 1 if enable else 0), "gs_pipe_set_timing")
+
+
+def gs_pipe_chunk_times(pipe, max_chunks=4096):
+    """[(kernel_begin_ms, kernel_end_ms, copy_end_ms)] per chunk of the last timed call"""
+    a = (ctypes.c_float * max_chunks)()
+    b = (ctypes.c_float * max_chunks)()
+    c = (ctypes.c_float * max_chunks)()
+    n = ctypes.c_int()
+    _check(lib().gs_pipe_chunk_times(pipe.handle, max_chunks, a, b, c, ctypes.byref(n)), "gs_pipe_chunk_times")
+    return [(a[i], b[i], c[i]) for i in range(min(n.value, max_chunks))]
 
 
 def gs_pipe_destroy(pipe):

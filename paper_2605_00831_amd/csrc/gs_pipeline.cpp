@@ -26,6 +26,11 @@ struct gs_pipe {
     hipStream_t copy_stream = nullptr;
     hipEvent_t done = nullptr;
     bool any = false;
+    // optional per-chunk timing of the last gs_checkpoint / gs_restore call
+    bool timing = false;
+    hipEvent_t t_origin = nullptr;
+    std::vector<hipEvent_t> t_kernel_begin, t_kernel_end, t_copy_end;
+    size_t timed_chunks = 0;
 
     uint8_t *slot_buf(int slot, int row) const
     {
@@ -37,6 +42,24 @@ struct gs_step_graph {
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
 };
+
+// timing events for chunks [0, n), created on first use and kept
+static hipError_t grow_timing(gs_pipe *p, size_t n)
+{
+    if (p->t_origin == nullptr) {
+        const hipError_t e = hipEventCreate(&p->t_origin);
+        if (e != hipSuccess) return e;
+    }
+    for (std::vector<hipEvent_t> *v : {&p->t_kernel_begin, &p->t_kernel_end, &p->t_copy_end}) {
+        while (v->size() < n) {
+            hipEvent_t ev = nullptr;
+            const hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) return e;
+            v->push_back(ev);
+        }
+    }
+    return hipSuccess;
+}
 
 #define GS_TRY(expr)                                 \
     do {                                             \
@@ -53,6 +76,9 @@ void gs_pipe_destroy(gs_pipe *p)
     for (hipEvent_t e : p->filled) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : p->drained) if (e) (void)hipEventDestroy(e);
     if (p->done) (void)hipEventDestroy(p->done);
+    if (p->t_origin) (void)hipEventDestroy(p->t_origin);
+    for (std::vector<hipEvent_t> *v : {&p->t_kernel_begin, &p->t_kernel_end, &p->t_copy_end})
+        for (hipEvent_t e : *v) (void)hipEventDestroy(e);
     if (p->copy_stream) (void)hipStreamDestroy(p->copy_stream);
     if (p->staging) (void)hipFree(p->staging);
     delete p;
@@ -113,6 +139,11 @@ try {
     std::vector<const void *> in(k);
     std::vector<void *> out(m);
     const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    p->timed_chunks = 0;
+    if (p->timing) {
+        GS_TRY(grow_timing(p, nchunks));
+        GS_TRY(hipEventRecord(p->t_origin, cs));
+    }
     for (size_t c = 0; c < nchunks; ++c) {
         const int slot = static_cast<int>(c % p->depth);
         const size_t off = c * p->chunk_bytes;
@@ -120,16 +151,20 @@ try {
         if (p->used[slot]) GS_TRY(hipStreamWaitEvent(cs, p->drained[slot], 0));
         for (int j = 0; j < k; ++j) in[j] = static_cast<const uint8_t *>(data[j]) + off;
         for (int i = 0; i < m; ++i) out[i] = p->slot_buf(slot, i);
+        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_begin[c], cs));
         const int rc = gs_encode(p->code, in.data(), out.data(), len, cs);
         if (rc != GS_OK) return rc;
+        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_end[c], cs));
         GS_TRY(hipEventRecord(p->filled[slot], cs));
         GS_TRY(hipStreamWaitEvent(p->copy_stream, p->filled[slot], 0));
         for (int i = 0; i < m; ++i)
             GS_TRY(hipMemcpyAsync(static_cast<uint8_t *>(host_parity[i]) + off, p->slot_buf(slot, i), len,
                                   hipMemcpyDeviceToHost, p->copy_stream));
+        if (p->timing) GS_TRY(hipEventRecord(p->t_copy_end[c], p->copy_stream));
         GS_TRY(hipEventRecord(p->drained[slot], p->copy_stream));
         p->used[slot] = 1;
     }
+    if (p->timing) p->timed_chunks = nchunks;
     GS_TRY(hipEventRecord(p->done, p->copy_stream));
     p->any = true;
     return GS_OK;
@@ -160,6 +195,11 @@ try {
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);
     std::vector<void *> view(k + m);  // the stripe as the rebuild of one chunk sees it
     const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    p->timed_chunks = 0;
+    if (p->timing) {
+        GS_TRY(grow_timing(p, nchunks));
+        GS_TRY(hipEventRecord(p->t_origin, cs));
+    }
     for (size_t c = 0; c < nchunks; ++c) {
         const int slot = static_cast<int>(c % p->depth);
         const size_t off = c * p->chunk_bytes;
@@ -177,13 +217,17 @@ try {
             }
         }
         for (int x = 0; x < n_erased; ++x) view[erased[x]] = static_cast<uint8_t *>(shards[erased[x]]) + off;
+        if (p->timing) GS_TRY(hipEventRecord(p->t_copy_end[c], p->copy_stream));
         GS_TRY(hipEventRecord(p->filled[slot], p->copy_stream));
         GS_TRY(hipStreamWaitEvent(cs, p->filled[slot], 0));
+        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_begin[c], cs));
         const int rc = gs_reconstruct(p->code, view.data(), erased, n_erased, len, cs);
         if (rc != GS_OK) return rc;
+        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_end[c], cs));
         GS_TRY(hipEventRecord(p->drained[slot], cs));
         p->used[slot] = 1;
     }
+    if (p->timing) p->timed_chunks = nchunks;
     GS_TRY(hipEventRecord(p->done, cs));
     p->any = true;
     return GS_OK;
@@ -197,6 +241,30 @@ int gs_pipe_sync(gs_pipe *p)
     if (p == nullptr) return GS_EINVAL;
     if (!p->any) return GS_OK;
     GS_TRY(hipEventSynchronize(p->done));
+    return GS_OK;
+}
+
+int gs_pipe_set_timing(gs_pipe *p, int enable)
+{
+    if (p == nullptr) return GS_EINVAL;
+    p->timing = enable != 0;
+    if (!p->timing) p->timed_chunks = 0;
+    return GS_OK;
+}
+
+int gs_pipe_chunk_times(gs_pipe *p, int max_chunks, float *kernel_begin_ms, float *kernel_end_ms,
+                        float *copy_end_ms, int *n_chunks_out)
+{
+    if (p == nullptr || n_chunks_out == nullptr || max_chunks < 0) return GS_EINVAL;
+    *n_chunks_out = static_cast<int>(p->timed_chunks);
+    if (p->timed_chunks == 0) return GS_OK;
+    GS_TRY(hipEventSynchronize(p->done));
+    const size_t n = std::min(p->timed_chunks, static_cast<size_t>(max_chunks));
+    for (size_t c = 0; c < n; ++c) {
+        if (kernel_begin_ms) GS_TRY(hipEventElapsedTime(&kernel_begin_ms[c], p->t_origin, p->t_kernel_begin[c]));
+        if (kernel_end_ms) GS_TRY(hipEventElapsedTime(&kernel_end_ms[c], p->t_origin, p->t_kernel_end[c]));
+        if (copy_end_ms) GS_TRY(hipEventElapsedTime(&copy_end_ms[c], p->t_origin, p->t_copy_end[c]));
+    }
     return GS_OK;
 }
 

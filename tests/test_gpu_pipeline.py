@@ -284,3 +284,45 @@ def test_kernels_write_parity_straight_into_pinned_host_memory(gs):
     for i in range(m):
         assert np.array_equal(hp[i].numpy()[:out_bytes], wantp[i])
         assert (hp[i].numpy()[out_bytes:] == 0x5A).all()
+
+
+def test_pipe_timeline_is_ordered_and_results_unchanged(gs):
+    """Per-chunk timing: kernels in stream order, every copy after its kernel (checkpoint) or
+    before it (restore), and the bytes are those of the untimed pipeline."""
+    k, m, S, chunk = 4, 2, (5 << 18) + 4096, 1 << 18
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    data_np = [inputs.uniform_bytes_np(63000 + j, S) for j in range(k)]
+    want = oracle.encode(P, data_np)
+    data = [dev(x) for x in data_np]
+    host = [pinned(S) for _ in range(m)]
+    pipe = gs.gs_pipe_create(code, chunk, 2)
+    assert gs.gs_pipe_chunk_times(pipe) == []
+    gs.gs_pipe_set_timing(pipe, True)
+    gs.gs_checkpoint(pipe, data, S, host)
+    times = gs.gs_pipe_chunk_times(pipe)
+    n = (S + chunk - 1) // chunk
+    assert len(times) == n
+    for c, (kb, ke, ce) in enumerate(times):
+        assert 0 <= kb <= ke <= ce, (c, kb, ke, ce)
+        if c:
+            assert times[c - 1][1] <= kb + 1e-3 and times[c - 1][2] <= ce
+    for i in range(m):
+        assert np.array_equal(host[i].numpy()[:S], want[i])
+    # restore: the H2D of a chunk ends before its reconstruct begins
+    lost = [1, 3]
+    for r in lost:
+        data[r].fill_(0xA5)
+    gs.gs_restore(pipe, data + [None] * m, host, lost, S)
+    times = gs.gs_pipe_chunk_times(pipe)
+    assert len(times) == n
+    for kb, ke, ce in times:
+        assert ce <= kb + 1e-3 <= ke + 1e-3
+    for r in lost:
+        assert np.array_equal(data[r].cpu().numpy(), data_np[r])
+    assert len(gs.gs_pipe_chunk_times(pipe, max_chunks=2)) == 2
+    gs.gs_pipe_set_timing(pipe, False)
+    gs.gs_checkpoint(pipe, data, S, host)
+    gs.gs_pipe_sync(pipe)
+    assert gs.gs_pipe_chunk_times(pipe) == []
+    gs.gs_pipe_destroy(pipe)
