@@ -291,8 +291,16 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
         gs.gs_pipe_sync(pipe)
         lat.append(time.perf_counter() - t0)
     n_par = len(erased)  # every erased data shard pulls one parity shard back
+    gs.gs_pipe_set_timing(pipe, True)
+    gs.gs_restore(pipe, data + [None] * m, host, erased, S)
+    rtl = gs.gs_pipe_chunk_times(pipe)
+    gs.gs_pipe_set_timing(pipe, False)
     res["restore"] = {"latency_ms": round(min(lat) * 1e3, 2), "erased": erased,
-                      "parity_h2d_GBps": round(n_par * S / min(lat) / 1e9, 2)}
+                      "parity_h2d_GBps": round(n_par * S / min(lat) / 1e9, 2),
+                      "timeline_ms": [{"chunk": c, "parity_on_device": round(ce, 2),
+                                       "reconstruct": [round(kb, 2), round(ke, 2)]}
+                                      for c, (kb, ke, ce) in enumerate(rtl)],
+                      "reconstruct_busy_ms": round(sum(ke - kb for kb, ke, _ in rtl), 2)}
     log("[bench] restore %.1f ms" % (min(lat) * 1e3))
     gs.gs_pipe_destroy(pipe)
 
