@@ -40,6 +40,11 @@
  *     at offsets >= shard_bytes are neither read nor written.
  *   - Input and output buffers of one call must not overlap.
  *   - A gs_code is immutable after creation and may be shared between threads.
+ *     gs_pipe and gs_batch objects keep the pointer to the gs_code they
+ *     were made for: free the code only after them.  Destroy an object only
+ *     when the work enqueued through it on the caller's streams has finished
+ *     (the destroy calls themselves wait only for the object's own copy
+ *     stream and descriptor slots).  gs_free_code never touches the device.
  */
 #ifndef GHOSTSERVE_EC_H
 #define GHOSTSERVE_EC_H
