@@ -135,3 +135,29 @@ def test_entry_points_validate_before_touching_the_gpu():
     assert L.gs_set_launch_shape(2, 1, 1, 11) == gs.GS_EINVAL
     assert L.gs_set_launch_shape(0, 0, -1, -1) == gs.GS_OK
     assert L.gs_strerror(gs.GS_ETOOMANY).decode() == "more erasures than parity shards"
+
+
+def test_runtime_failures_surface_as_status_codes_without_a_device():
+    """With no GPU in the process every HIP call fails: object creation must clean up after itself
+    and report GS_EHIP (never crash, never hand back a half-made object), a launch must report the
+    runtime's error, and the host-only entry points must keep working."""
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("needs a process without a GPU")
+    L = gs.lib()
+    code = gs.gs_make_code(4, 2)
+    vp = ctypes.c_void_p
+    out = vp(0xDEAD)
+    assert L.gs_pipe_create(code.handle, 1024, 2, ctypes.byref(out)) == gs.GS_EHIP and not out.value
+    assert L.gs_last_hip_error() != 0
+    out = vp(0xDEAD)
+    assert L.gs_batch_create(code.handle, 4, ctypes.byref(out)) == gs.GS_EHIP and not out.value
+    out = vp(0xDEAD)
+    assert L.gs_pool_create(2, ctypes.byref(out)) == gs.GS_EHIP and not out.value
+    good = (vp * 4)(0x1000, 0x2000, 0x3000, 0x4000)
+    par = (vp * 2)(0x5000, 0x6000)
+    assert L.gs_encode(code.handle, good, par, 64, None) == gs.GS_EHIP
+    assert "HIP" in L.gs_strerror(gs.GS_EHIP).decode()
+    R, surv = gs.gs_decode_matrix(code, [1, 3])
+    assert surv == [0, 2, 4, 5] and R.shape == (2, 4)
+    assert gs.gs_recompute_units(10, 1.0, 0.0, 0.0, 1.0, 0.1)[0] in range(11)
