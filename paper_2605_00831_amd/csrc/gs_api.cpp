@@ -172,6 +172,20 @@ int check_rebuild_args(const gs_code *code, void *const *shards, const std::vect
     return GS_OK;
 }
 
+// the launches of a rebuild whose matrix is already known (not RDP)
+int apply_rebuild(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &survivors,
+                  void *const *shards, const int *erased, int n_erased, size_t shard_bytes, hipStream_t stream)
+{
+    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
+    const int rc = check_rebuild_args(code, shards, survivors, erased, n_erased, shard_bytes);
+    if (rc != GS_OK) return rc;
+    std::vector<const void *> in(code->k);
+    std::vector<void *> out(n_erased);
+    for (int j = 0; j < code->k; ++j) in[j] = shards[survivors[j]];
+    for (int x = 0; x < n_erased; ++x) out[x] = shards[erased[x]];
+    return apply_matrix(n_erased, code->k, R.data(), in.data(), out.data(), shard_bytes, stream);
+}
+
 static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *erased, int n_erased,
                            size_t shard_bytes, hipStream_t stream)
 {
@@ -407,19 +421,7 @@ try {
     std::vector<int> surv;
     const int rc = decode_matrix(code, erased, n_erased, R, surv);
     if (rc != GS_OK) return rc;
-    if (n_erased == 0 || shard_bytes == 0) return GS_OK;
-    std::vector<const void *> in(code->k);
-    std::vector<void *> out(n_erased);
-    for (int j = 0; j < code->k; ++j) {
-        in[j] = shards[surv[j]];
-        if (in[j] == nullptr || !aligned16(in[j])) return GS_EINVAL;
-    }
-    for (int x = 0; x < n_erased; ++x) {
-        out[x] = shards[erased[x]];
-        if (out[x] == nullptr || !aligned16(out[x])) return GS_EINVAL;
-    }
-    return apply_matrix(n_erased, code->k, R.data(), in.data(), out.data(), shard_bytes,
-                        static_cast<hipStream_t>(stream));
+    return apply_rebuild(code, R, surv, shards, erased, n_erased, shard_bytes, static_cast<hipStream_t>(stream));
 }
 catch (...) {
     return caught();

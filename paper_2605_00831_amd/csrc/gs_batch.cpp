@@ -253,7 +253,9 @@ int gs_reconstruct_streams(const gs_code *code, gs_pool *pool, int n_chunks, voi
 try {
     if (code == nullptr || pool == nullptr || n_chunks < 0) return GS_EINVAL;
     std::vector<int> read;
-    const int rc = shards_read(code, erased, n_erased, read);
+    std::vector<uint8_t> R;  // found once for all chunks (not RDP)
+    const int rc = code->is_rdp() ? shards_read(code, erased, n_erased, read)
+                                  : decode_matrix(code, erased, n_erased, R, read);
     if (rc != GS_OK) return rc;
     if (n_chunks == 0 || n_erased == 0) return GS_OK;
     if (shards == nullptr || shard_bytes == nullptr) return GS_EINVAL;
@@ -263,7 +265,9 @@ try {
         if (rcc != GS_OK) return rcc;
     }
     return fan_out(pool, n_chunks, static_cast<hipStream_t>(stream), [&](int c, hipStream_t s) {
-        return gs_reconstruct(code, shards + static_cast<size_t>(c) * n, erased, n_erased, shard_bytes[c], s);
+        void *const *stripe = shards + static_cast<size_t>(c) * n;
+        if (code->is_rdp()) return gs_reconstruct(code, stripe, erased, n_erased, shard_bytes[c], s);
+        return apply_rebuild(code, R, read, stripe, erased, n_erased, shard_bytes[c], s);
     });
 }
 catch (...) {

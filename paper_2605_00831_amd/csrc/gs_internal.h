@@ -34,6 +34,9 @@ int shards_read(const gs_code *code, const int *erased, int n_erased, std::vecto
 int check_encode_args(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes);
 int check_rebuild_args(const gs_code *code, void *const *shards, const std::vector<int> &read, const int *erased,
                        int n_erased, size_t shard_bytes);
+// rebuild with a matrix from decode_matrix (any code but RDP): checks the pointers, then launches
+int apply_rebuild(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &survivors,
+                  void *const *shards, const int *erased, int n_erased, size_t shard_bytes, hipStream_t stream);
 int decode_matrix(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &R,
                   std::vector<int> &survivors);
 

@@ -179,7 +179,9 @@ try {
     if (p == nullptr || shards == nullptr || host_parity == nullptr) return GS_EINVAL;
     const int k = p->code->k, m = p->code->m;
     std::vector<int> read;  // shard ids the rebuild reads
-    const int rc0 = shards_read(p->code, erased, n_erased, read);
+    std::vector<uint8_t> R;  // rebuild matrix, found once for all chunks (not RDP)
+    const int rc0 = p->code->is_rdp() ? shards_read(p->code, erased, n_erased, read)
+                                      : decode_matrix(p->code, erased, n_erased, R, read);
     if (rc0 != GS_OK) return rc0;
     if (n_erased == 0 || shard_bytes == 0) return GS_OK;
     if (p->code->is_rdp() && shard_bytes % (p->code->rdp_cell * (p->code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
@@ -221,7 +223,8 @@ try {
         GS_TRY(hipEventRecord(p->filled[slot], p->copy_stream));
         GS_TRY(hipStreamWaitEvent(cs, p->filled[slot], 0));
         if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_begin[c], cs));
-        const int rc = gs_reconstruct(p->code, view.data(), erased, n_erased, len, cs);
+        const int rc = p->code->is_rdp() ? gs_reconstruct(p->code, view.data(), erased, n_erased, len, cs)
+                                         : apply_rebuild(p->code, R, read, view.data(), erased, n_erased, len, cs);
         if (rc != GS_OK) return rc;
         if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_end[c], cs));
         GS_TRY(hipEventRecord(p->drained[slot], cs));
