@@ -36,6 +36,26 @@ MEASURED_TRAFFIC_BYTES = {   # (workload, code): FETCH_SIZE x 1.99996 + WRITE_SI
 }
 
 
+def native_step_latency(log):
+    """Decode-step checkpoint latency measured from C (paper_2605_00831_amd/csrc/gs_step_latency.c)."""
+    import subprocess
+    from paper_2605_00831_amd import build as hip_build
+    from paper_2605_00831_amd import inputs
+    c = inputs.CONFIGS["decode_paged"]
+    if not os.path.exists(hip_build.STEP_LATENCY):
+        return {"error": "gs_step_latency has not been built"}
+    try:
+        outp = subprocess.run([hip_build.STEP_LATENCY, str(c["steps"]), str(c["layers"])], capture_output=True,
+                              text=True, timeout=240)
+        if outp.returncode != 0:
+            return {"error": "exit %d: %s" % (outp.returncode, outp.stderr.strip()[-200:])}
+        res = json.loads(outp.stdout.strip().splitlines()[-1])
+    except (subprocess.TimeoutExpired, ValueError, IndexError) as e:
+        return {"error": repr(e)[:200]}
+    log("[bench] decode step from C: " + json.dumps(res))
+    return res
+
+
 def pctl(xs, q):
     xs = sorted(xs)
     return xs[min(len(xs) - 1, int(q * len(xs)))]
@@ -61,6 +81,11 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         return 2
 
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+    # The decode-step latency probe is a plain C program: run it as a child process first, before
+    # this process opens the GPU, so that the two never hold the device at the same time.
+    native = None if args.no_extras else native_step_latency(log)
+
     import torch
     from paper_2605_00831_amd import binding as gs
     from paper_2605_00831_amd import inputs
@@ -77,7 +102,6 @@ def main():
     total = inputs.config_total_bytes(args.workload)
     S = total // k
     erased = list(cfg.get("erased", (1, 3) if k >= 4 else (0,)))[:m]
-    log = lambda *a: print(*a, file=sys.stderr, flush=True)
     log("[bench] workload %s: k=%d m=%d S=%.3f GiB total %.1f GiB" % (args.workload, k, m, S / 2**30, total / 2**30))
 
     t0 = time.perf_counter()
@@ -172,13 +196,13 @@ def main():
                     "no kernel GB/s is printed in the paper's text",
     }
     if not args.no_extras:
-        out.update(extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log))
+        out.update(extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log, native))
 
     print(json.dumps(out), flush=True)
     return 0
 
 
-def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log):
+def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log, native=None):
     res = {}
     dev = "cuda:0"
     code = gs.gs_make_code(k, m)
@@ -378,7 +402,7 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     del host_data, want, one
 
     # ---- streaming decode-step checkpoint (paged, k=4, m=1), latency over 1000 steps
-    res["decode_step"] = decode_steps(torch, gs, inputs, log)
+    res["decode_step"] = decode_steps(torch, gs, inputs, log, native)
     # ---- many small chunks: one launch per chunk, a stream per chunk, or one grouped launch
     res["many_chunks"] = many_chunks(torch, gs, log)
     # ---- per-chunk latency breakdown against chunk size (the shape of the paper's kernel microbenchmark)
@@ -471,7 +495,7 @@ def many_chunks(torch, gs, log):
     return out
 
 
-def decode_steps(torch, gs, inputs, log):
+def decode_steps(torch, gs, inputs, log, native=None):
     c = inputs.CONFIGS["decode_paged"]
     k, m, steps = c["k"], c["m"], c["steps"]
     n_planes = c["layers"] * 2
@@ -529,6 +553,8 @@ def decode_steps(torch, gs, inputs, log):
     res["graph_encode_d2h"] = run(lambda: gs.gs_step_graph_launch(g1))
     gs.gs_step_graph_destroy(g0)
     gs.gs_step_graph_destroy(g1)
+    if native is not None:
+        res["native"] = native
     log("[bench] decode step: " + json.dumps(res))
     return res
 
