@@ -19,6 +19,7 @@ static int disk_of_shard(int k, int p, int shard) { return shard < k ? shard : (
 
 bool rdp_plan(int k, const int *missing, int n_missing, RdpPlan &plan)
 {
+    if (k < 1 || k > kRdpMaxPrime - 1 || n_missing < 1 || n_missing > 2) return false;  // RDP rebuilds at most two
     const int p = plan.p = rdp_prime(k), rows = p - 1;
     int lost_disk[2] = {-1, -1};
     for (int x = 0; x < n_missing; ++x) lost_disk[x] = disk_of_shard(k, p, missing[x]);

@@ -6,6 +6,8 @@
 #include <vector>
 
 #include "../paper_2605_00831_amd/csrc/gs_gf.cpp"
+#include "../paper_2605_00831_amd/csrc/gs_plan.cpp"
+#include "../paper_2605_00831_amd/csrc/gs_rdp.cpp"
 
 using namespace gs;
 
@@ -59,6 +61,37 @@ int main()
             const unsigned got = byte(0, x & 7) ^ byte(2, (x >> 3) & 7) ^ byte(4, x >> 6);
             if (got != gf_mul(static_cast<uint8_t>(c), static_cast<uint8_t>(x))) return fail("split tables", c, x);
         }
+    }
+    // RDP planning for every code width and every one- and two-shard loss: masks stay inside the
+    // 2(p-1) syndrome bits, disk ids inside the shard range, and lost shards are never read
+    for (int k = 1; k <= 16; ++k) {
+        const int n = k + 2;
+        for (int a = 0; a < n; ++a)
+            for (int b = a; b < n; ++b) {
+                const int missing[2] = {a, b};
+                const int n_missing = a == b ? 1 : 2;
+                RdpPlan plan;
+                if (!rdp_plan(k, missing, n_missing, plan)) return fail("rdp plan singular", k, a * 100 + b);
+                const int rows = plan.p - 1;
+                if (plan.p != rdp_prime(k) || static_cast<int>(plan.outputs.size()) != n_missing) return fail("rdp plan shape", k, a);
+                if (static_cast<int>(plan.syndrome_mask.size()) != n_missing * rows) return fail("rdp mask count", k, a);
+                for (uint32_t mask : plan.syndrome_mask)
+                    if (rows < 16 && (mask >> (2 * rows)) != 0) return fail("rdp mask range", k, a);
+                for (int j = 0; j <= plan.p; ++j) {
+                    const int sh = plan.shard_of_disk[j];
+                    if (sh < -1 || sh >= n || sh == a || sh == b) return fail("rdp disk", k, j);
+                }
+            }
+        const int three[3] = {0, 1, 2};
+        RdpPlan plan;
+        if (k >= 1 && rdp_plan(k, three, 3, plan)) return fail("rdp accepted three losses", k, 0);
+    }
+    // planner: the answer is inside [0, n] and its makespan is the smaller of the neighbours'
+    for (int n = 0; n <= 40; n += 5) {
+        const gs_recovery_costs costs = {0.01 + 0.001 * n, 0.0005, 0.002, 0.004, 0.001, 0.003};
+        int r = -1;
+        double t = -1.0;
+        if (gs_recompute_units(n, &costs, &r, &t) != GS_OK || r < 0 || r > n || !(t >= 0.0)) return fail("planner", n, r);
     }
     std::printf("OK\n");
     return 0;
