@@ -441,6 +441,39 @@ static int check_allocation_failures()
     return 0;
 }
 
+// the captured per-step checkpoint: one launch and m copies are recorded at creation, the private
+// capture stream is gone afterwards, and a failing capture hands nothing back
+static int check_step_graph()
+{
+    const int k = 4, m = 2, n_planes = 3, pps = 5;
+    const size_t page = 2048, out_bytes = static_cast<size_t>(n_planes) * pps * page;
+    gs_code *code = nullptr;
+    EXPECT(gs_make_code(k, m, GS_CAUCHY, &code) == GS_OK);
+    std::vector<void *> par(m), host(m);
+    for (auto &p : par) p = std::malloc(out_bytes);
+    for (auto &p : host) p = std::malloc(out_bytes);
+    for (auto &p : par) std::memset(p, 0x11, out_bytes);
+    void *planes = reinterpret_cast<void *>(0x100000), *table = reinterpret_cast<void *>(0x200000);
+    reset_record();
+    gs_step_graph *g = nullptr;
+    EXPECT(gs_step_graph_create(code, static_cast<const void *const *>(planes), n_planes, page, 64,
+                                static_cast<const int32_t *>(table), pps, par.data(), host.data(), &g) == GS_OK && g != nullptr);
+    int launches = 0, copies = 0;
+    for (const Op &o : ops) (o.kind == LAUNCH ? launches : copies) += 1;
+    EXPECT(launches == 1 && copies == m);
+    for (int i = 1; i < kMaxStreams; ++i) EXPECT(!stream_live[i]);
+    EXPECT(gs_step_graph_launch(g, nullptr) == GS_OK);
+    gs_step_graph_destroy(g);
+    g = reinterpret_cast<gs_step_graph *>(1);
+    EXPECT(gs_step_graph_create(code, static_cast<const void *const *>(planes), n_planes, 24, 64,
+                                static_cast<const int32_t *>(table), pps, par.data(), host.data(), &g) == GS_EINVAL && g == nullptr);
+    for (int i = 1; i < kMaxStreams; ++i) EXPECT(!stream_live[i]);
+    for (void *p : par) std::free(p);
+    for (void *p : host) std::free(p);
+    gs_free_code(code);
+    return 0;
+}
+
 int main()
 {
     if (check_pipelines(4, 2, GS_CAUCHY, 4096, 2, 10 * 4096 + 100, {1, 3})) return 1;
@@ -451,6 +484,7 @@ int main()
     if (check_pipelines(8, 3, GS_POWER, 4096, 2, 3 * 4096 + 1, {8})) return 1;    // Horner encode, lost parity
     if (check_pool(4, 11) || check_pool(16, 3) || check_pool(1, 5)) return 1;
     if (check_ring()) return 1;
+    if (check_step_graph()) return 1;
     if (check_allocation_failures()) return 1;
     for (int i = 1; i < kMaxStreams; ++i) EXPECT(!stream_live[i]);  // every stream was destroyed
     EXPECT(events.empty());                                          // and every event
