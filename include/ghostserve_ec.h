@@ -347,7 +347,8 @@ int gs_last_hip_error(void);
 int gs_coef_words(int c, uint32_t *words_out);
 /* Launch-shape knobs for benchmarking sweeps; a value <= 0 (< 0 for the last
  * two) restores that knob's default.
- *   unroll            16-byte vectors per lane per shard per tile (1, 2 or 4)
+ *   unroll            16-byte vectors per lane per shard per tile (1, 2 or 4;
+ *                     default: 2 for contiguous shards, 1 for the paged gather)
  *   tiles_per_wg      consecutive tiles one workgroup processes
  *   nontemporal       1 = streaming loads/stores, 0 = default cache policy
  *   interleave_shift  log2 of the modulus with which the contiguous kernel

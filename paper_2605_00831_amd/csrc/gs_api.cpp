@@ -19,7 +19,7 @@ namespace gs {
 thread_local int g_last_hip_error = 0;
 
 // defaults chosen by measurement on MI355X; see gs_set_launch_shape()
-static LaunchShape g_default_shape = {2, 1, 1, 5};
+static LaunchShape g_default_shape = {0, 1, 1, 5};  // unroll 0: chosen per kernel family
 static LaunchShape g_shape = g_default_shape;
 
 LaunchShape current_shape() { return g_shape; }

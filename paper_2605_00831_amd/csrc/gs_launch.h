@@ -11,7 +11,7 @@ constexpr int kLaunchMaxM = 4;   // output rows per launch
 constexpr int kThreads = 256;    // lanes per workgroup (4 wavefronts of 64)
 
 struct LaunchShape {
-    int unroll;        // 16-byte vectors per lane per stream per tile: 1, 2 or 4
+    int unroll;        // 16-byte vectors per lane per stream per tile: 1, 2 or 4; 0 = per kernel family
     int tiles_per_wg;  // consecutive tiles per workgroup
     int nontemporal;   // streaming cache policy on loads and stores
     int interleave_shift;  // log2 of the XCD interleave modulus of the contiguous kernel (0 = off)
