@@ -58,3 +58,80 @@ def test_random_cases_against_the_oracle():
                 assert (got[S:] == 0xC7).all()
     finally:
         gs.gs_set_launch_shape()
+
+
+def test_random_pipeline_and_paged_cases_against_the_oracle():
+    """Seeded random sweep of the chunked checkpoint / restore pipelines (chunk size, depth, shard
+    length, erasure pattern) and of the paged encode / rebuild (planes, pages per shard, page sizes
+    that are and are not powers of two, random tables)."""
+    from paper_2605_00831_amd import binding as gs
+    gs.lib()
+    gs.gs_set_launch_shape()
+    rng = np.random.default_rng(inputs.SEED_BASE + 0x301)
+    for case in range(25):
+        k, m = int(rng.integers(1, 13)), int(rng.integers(1, 5))
+        code = gs.gs_make_code(k, m)
+        P = oracle.generator(k, m)
+        chunk = 16 * int(rng.integers(1, 3000))
+        depth = int(rng.integers(2, 6))
+        S = int(rng.integers(1, 12 * chunk))
+        data_np = [inputs.uniform_bytes_np(70000 + case * 50 + j, S) for j in range(k)]
+        want = oracle.encode(P, data_np, nthreads=8)
+        data = [torch.from_numpy(x).cuda() for x in data_np]
+        host = [torch.full((S + 16,), 0x5A, dtype=torch.uint8).pin_memory() for _ in range(m)]
+        pipe = gs.gs_pipe_create(code, chunk, depth)
+        gs.gs_checkpoint(pipe, data, S, host)
+        gs.gs_pipe_sync(pipe)
+        for i in range(m):
+            assert np.array_equal(host[i].numpy()[:S], want[i]), (case, k, m, S, chunk, depth, i)
+            assert (host[i].numpy()[S:] == 0x5A).all()
+        e = int(rng.integers(1, m + 1))
+        pat = sorted(int(x) for x in rng.choice(k + m, size=e, replace=False))
+        shards = [d if r not in pat else torch.full((S + 16,), 0xA5, dtype=torch.uint8, device="cuda")
+                  for r, d in enumerate(data)]
+        shards += [torch.full((S + 16,), 0xA5, dtype=torch.uint8, device="cuda") if k + i in pat else None for i in range(m)]
+        gs.gs_restore(pipe, shards, host, pat, S)
+        gs.gs_pipe_sync(pipe)
+        full = data_np + want
+        for r in pat:
+            got = shards[r].cpu().numpy()
+            assert np.array_equal(got[:S], full[r]), (case, k, m, S, chunk, depth, pat, r)
+            assert (got[S:] == 0xA5).all()
+        gs.gs_pipe_destroy(pipe)
+
+    for case in range(25):
+        k, m = int(rng.integers(1, 10)), int(rng.integers(1, 4))
+        code = gs.gs_make_code(k, m)
+        P = oracle.generator(k, m)
+        n_planes, pps = int(rng.integers(1, 6)), int(rng.integers(1, 20))
+        page = 16 * int(rng.choice([1, 3, 4, 64, 65, 128, 200, 1024]))
+        n_pages = (k + m) * pps + int(rng.integers(0, 10))
+        planes_np = [inputs.uniform_bytes_np(90000 + case * 20 + p, n_pages * page) for p in range(n_planes)]
+        planes = [torch.from_numpy(x).cuda() for x in planes_np]
+        base = torch.tensor([x.data_ptr() for x in planes], dtype=torch.int64, device="cuda")
+        ids = rng.permutation(n_pages).astype(np.int32)
+        table_np = ids[: k * pps].reshape(k, pps)
+        spare_np = ids[k * pps: (k + m) * pps].reshape(m, pps)       # fresh pages for rebuilt shards
+        table = torch.from_numpy(np.ascontiguousarray(table_np)).cuda()
+        out_bytes = n_planes * pps * page
+        par = [torch.full((out_bytes + 16,), 0xC7, dtype=torch.uint8, device="cuda") for _ in range(m)]
+        gs.gs_encode_paged(code, base, n_planes, page, n_pages, table, pps, par)
+        torch.cuda.synchronize()
+        want = oracle.encode_paged(P, planes_np, page, table_np)
+        for i in range(m):
+            got = par[i].cpu().numpy()
+            assert np.array_equal(got[:out_bytes], want[i]), (case, k, m, n_planes, pps, page, i)
+            assert (got[out_bytes:] == 0xC7).all()
+        # lose one data shard: it is rebuilt into fresh pages named by a new table row
+        lost = int(rng.integers(0, k))
+        new_table_np = table_np.copy()
+        new_table_np[lost] = spare_np[0]
+        new_table = torch.from_numpy(np.ascontiguousarray(new_table_np)).cuda()
+        gs.gs_reconstruct_paged(code, base, n_planes, page, n_pages, new_table, pps, par, [lost])
+        torch.cuda.synchronize()
+        for p in range(n_planes):
+            got = planes[p].cpu().numpy().reshape(n_pages, page)
+            orig = planes_np[p].reshape(n_pages, page)
+            assert np.array_equal(got[new_table_np[lost]], orig[table_np[lost]]), (case, k, m, p, page, lost)
+            untouched = np.setdiff1d(np.arange(n_pages), new_table_np[lost])
+            assert np.array_equal(got[untouched], orig[untouched])
