@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_prefill",
-                    choices=["llama8b_prefill", "llama70b_longctx", "tiny"])
+                    choices=["llama8b_prefill", "llama70b_longctx", "recovery_stress", "tiny"])
     ap.add_argument("--code", default="cauchy", choices=["cauchy", "power", "power-tables"],
                     help="code of the timed step: the canonical Cauchy code (default), the power code "
                          "(Horner encode kernel), or the power code through the general table kernel")
@@ -101,11 +101,19 @@ def main():
     k, m = cfg["k"], cfg["m"]
     total = inputs.config_total_bytes(args.workload)
     S = total // k
-    erased = list(cfg.get("erased", (1, 3) if k >= 4 else (0,)))[:m]
+    # recovery_stress loses a data shard, another data shard and a parity shard (one of its seeded triples)
+    erased = list(cfg.get("erased", (2, 5, 9) if args.workload == "recovery_stress" else (1, 3) if k >= 4 else (0,)))[:m]
     log("[bench] workload %s: k=%d m=%d S=%.3f GiB total %.1f GiB" % (args.workload, k, m, S / 2**30, total / 2**30))
 
     t0 = time.perf_counter()
-    buf = inputs.kv_bytes_device(inputs.config_seed(args.workload), total, cfg["dtype"], cfg["sigma"], dev)
+    if args.workload == "recovery_stress":
+        # first half of the shards uniform random bytes, second half bf16 N(0,1) KV bytes
+        half = (k // 2) * S
+        buf = torch.empty(total, dtype=torch.uint8, device=dev)
+        buf[:half] = inputs.uniform_bytes_device(inputs.config_seed(args.workload), half, dev)
+        buf[half:] = inputs.kv_bytes_device(inputs.config_seed(args.workload) + 1, total - half, "bf16", 1.0, dev)
+    else:
+        buf = inputs.kv_bytes_device(inputs.config_seed(args.workload), total, cfg["dtype"], cfg["sigma"], dev)
     data = [buf[j * S:(j + 1) * S] for j in range(k)]
     parity = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(m)]
     torch.cuda.synchronize()
@@ -166,7 +174,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
-        "config": {"workload": args.workload, "k": k, "m": m, "shard_bytes": S, "kv_dtype": cfg["dtype"],
+        "config": {"workload": args.workload, "k": k, "m": m, "shard_bytes": S, "kv_dtype": cfg.get("dtype", "uniform bytes + bf16"),
                    "erased": erased, "code": args.code,
                    "launch": "gs_encode + gs_reconstruct, default launch shape"},
         "encode_GBps_data": round(k * S / (enc_avg * 1e-3) / 1e9, 1),
@@ -311,12 +319,12 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     for _ in range(2):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        gs.gs_restore(pipe, data + [None] * m, host, erased, S)
+        gs.gs_restore(pipe, data + parity, host, erased, S)
         gs.gs_pipe_sync(pipe)
         lat.append(time.perf_counter() - t0)
     n_par = len(erased)  # every erased data shard pulls one parity shard back
     gs.gs_pipe_set_timing(pipe, True)
-    gs.gs_restore(pipe, data + [None] * m, host, erased, S)
+    gs.gs_restore(pipe, data + parity, host, erased, S)
     rtl = gs.gs_pipe_chunk_times(pipe)
     gs.gs_pipe_set_timing(pipe, False)
     res["restore"] = {"latency_ms": round(min(lat) * 1e3, 2), "erased": erased,
