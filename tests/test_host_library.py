@@ -161,3 +161,42 @@ def test_runtime_failures_surface_as_status_codes_without_a_device():
     R, surv = gs.gs_decode_matrix(code, [1, 3])
     assert surv == [0, 2, 4, 5] and R.shape == (2, 4)
     assert gs.gs_recompute_units(10, 1.0, 0.0, 0.0, 1.0, 0.1)[0] in range(11)
+
+
+def test_product_and_oracle_share_nothing():
+    """The package never imports the oracle (and the oracle never the package); neither shared
+    library carries the other's entry points."""
+    import ast
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imports_of(path):
+        names = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                names.update(a.name.split(".")[0] for a in node.names)
+            elif isinstance(node, ast.ImportFrom) and node.module:
+                names.add(node.module.split(".")[0])
+        return names
+
+    pkg = os.path.join(root, "paper_2605_00831_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            assert "oracle" not in imports_of(os.path.join(pkg, f)), f
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2605_00831_amd" not in imports_of(os.path.join(root, "oracle", f)), f
+    for f in os.listdir(os.path.join(pkg, "csrc")):
+        if not f.endswith((".h", ".c", ".cpp", ".hip")):
+            continue
+        text = open(os.path.join(pkg, "csrc", f)).read()
+        assert "gso_" not in text and "oracle/" not in text, f
+
+    def exported(lib):
+        out = subprocess.run(["nm", "-D", "--defined-only", lib], stdout=subprocess.PIPE, text=True, check=True).stdout
+        return {line.split()[-1] for line in out.splitlines() if line.strip()}
+
+    import oracle
+    product, checker = exported(gs.LIB_PATH), exported(oracle.build())
+    assert not any(s.startswith("gso_") for s in product)
+    assert not any(s.startswith("gs_") for s in checker)
