@@ -30,11 +30,19 @@
  * other, then that block's row to get a block of the first, and so on, two
  * chains, each ending at the unstored diagonal).
  *
- * Pins (tests/test_oracle_rdp.py): row parity == numpy XOR; generator matrix
- * read out by impulses and checked for rank over GF(2) under every pair of
- * lost disks (independent elimination); exhaustive search for the unique
+ * Pins (tests/test_oracle_rdp.py): row parity == numpy XOR; the diagonal
+ * parity against two stripes worked by hand from the definition above (p = 3
+ * and p = 5, expected bytes written out in the test) and, for every k <= 16,
+ * against a definition-direct numpy construction that never calls this file
+ * -- a flipped diagonal direction, a row-parity disk left out of the
+ * diagonals or another unstored diagonal fails them; generator matrix read
+ * out by impulses and checked for rank over GF(2) under every pair of lost
+ * disks (independent elimination); exhaustive search for the unique
  * completion on the smallest stripe; round trips over every pair of disks for
- * every k <= 16.  Nothing here is "parity unpinned".
+ * every k <= 16.  What stays unchecked: that the definition restated above is
+ * the cited publication's (it is not available to this build); by the
+ * authors' own description (row parity plus diagonal parity over the data and
+ * row-parity disks, one diagonal dropped) it is.
  */
 #include <stddef.h>
 #include <stdint.h>

@@ -156,3 +156,98 @@ def test_reconstruct_errors():
     for bad in ([0, 0], [6], [-1]):
         with pytest.raises(ValueError):
             oracle.rdp_reconstruct([x.copy() for x in full], bad)
+
+
+# ---------------------------------------------------------------------------
+# Pins of the diagonal-parity CONVENTION.  The tests above hold for any
+# consistent 2-erasure-MDS array code; the ones below fix which one this is,
+# from the published RDP construction written out cell by cell (Section 2 and
+# Section 4.1 of the paper name RDP; the construction is the cited
+# publication's, which is not available here to read against -- these values
+# follow from its definition as restated in the oracle's header: disks 0..p-2
+# data, disk p-1 row parity, cell (i, j) of those p disks on diagonal
+# (i+j) mod p, diagonal p-1 not stored, Q[d] = XOR of diagonal d).
+# None of the expected values below comes from the oracle.
+
+def test_hand_worked_stripe_p3():
+    """k = 2, p = 3: two rows; disks 0, 1 data, disk 2 row parity R.
+         row 0:  a=01  c=04 | R0 = a^c = 05
+         row 1:  b=02  d=08 | R1 = b^d = 0a
+       diagonal of (i, j) is (i+j) mod 3:
+         diagonal 0 = {(0,0), (1,2)}         -> Q0 = a ^ R1 = 01 ^ 0a = 0b
+         diagonal 1 = {(0,1), (1,0)}         -> Q1 = c ^ b  = 04 ^ 02 = 06
+         diagonal 2 = {(0,2), (1,1)}         not stored
+    """
+    d0 = np.array([0x01, 0x02], np.uint8)
+    d1 = np.array([0x04, 0x08], np.uint8)
+    R, Q = oracle.rdp_encode([d0, d1])
+    assert R.tolist() == [0x05, 0x0A]
+    assert Q.tolist() == [0x0B, 0x06]
+
+
+def test_hand_worked_stripe_p5():
+    """k = 4, p = 5: four rows, cells of two bytes; data cell (row i, disk j)
+    holds the 16-bit word with only bit 4j+i set (little-endian), so every
+    parity word lists the data cells it covers.
+      row parity  R[i] = bits {i, 4+i, 8+i, 12+i} = 0x1111 << i
+      diagonal d  = cells (i, j), i <= 3, j <= 4 (j = 4 is the row-parity disk), i+j = d mod 5:
+        d=0: (0,0) (2,3) (3,2) + R[1]:  0001 ^ 4000 ^ 0800 ^ 2222 = 6a23
+        d=1: (0,1) (1,0) (3,3) + R[2]:  0010 ^ 0002 ^ 8000 ^ 4444 = c456
+        d=2: (0,2) (1,1) (2,0) + R[3]:  0100 ^ 0020 ^ 0004 ^ 8888 = 89ac
+        d=3: (0,3) (1,2) (2,1) (3,0) :  1000 ^ 0200 ^ 0040 ^ 0008 = 1248   (row 4 of disk 4 does not exist)
+        d=4: (0,4) (1,3) (2,2) (3,1)    not stored
+    """
+    data = [np.array([1 << (4 * j + i) for i in range(4)], dtype="<u2").view(np.uint8).copy() for j in range(4)]
+    R, Q = oracle.rdp_encode(data)
+    assert R.view("<u2").tolist() == [0x1111, 0x2222, 0x4444, 0x8888]
+    assert Q.view("<u2").tolist() == [0x6A23, 0xC456, 0x89AC, 0x1248]
+
+
+def rdp_by_definition(data, cell, direction=+1, with_row_parity_disk=True, unstored=None):
+    """Row and diagonal parity written straight from the definition with numpy,
+    stripe by stripe; never calls the oracle.  The keyword arguments exist only
+    to build WRONG variants (flipped diagonal direction, row-parity disk left
+    out of the diagonals, another diagonal left unstored) that the pins must
+    tell apart from the real convention."""
+    k = len(data)
+    p = next(q for q in range(max(3, k + 1), 300) if all(q % f for f in range(2, q)))
+    rows = p - 1
+    unstored = p - 1 if unstored is None else unstored
+    stored = [d for d in range(p) if d != unstored]      # diagonal stored in cell stored.index(d)
+    stripes = data[0].size // (rows * cell)
+    D = np.zeros((stripes, rows, p, cell), np.uint8)     # [stripe][row][disk 0..p-1][byte]
+    for j in range(k):
+        D[:, :, j, :] = data[j].reshape(stripes, rows, cell)
+    D[:, :, p - 1, :] = np.bitwise_xor.reduce(D[:, :, :p - 1, :], axis=2)
+    Q = np.zeros((stripes, rows, cell), np.uint8)
+    for i in range(rows):
+        for j in range(p if with_row_parity_disk else p - 1):
+            d = (i + direction * j) % p
+            if d != unstored:
+                Q[:, stored.index(d), :] ^= D[:, i, j, :]
+    return D[:, :, p - 1, :].reshape(-1).copy(), Q.reshape(-1)
+
+
+@pytest.mark.parametrize("k", list(range(1, 17)))
+def test_diagonal_parity_equals_definition_direct_construction(k):
+    p = oracle.rdp_prime(k)
+    for cell, stripes in ((1, 1), (3, 4), (16, 2)):
+        S = stripes * (p - 1) * cell
+        data = [inputs.uniform_bytes_np(900 + 17 * k + j, S) for j in range(k)]
+        R, Q = oracle.rdp_encode(data, cell)
+        wantR, wantQ = rdp_by_definition(data, cell)
+        assert np.array_equal(R, wantR), (k, cell)
+        assert np.array_equal(Q, wantQ), (k, cell)
+
+
+def test_the_pins_tell_wrong_conventions_apart():
+    """Each plausible wrong convention is still a two-erasure code, so the
+    property tests cannot see it; the hand-worked stripes can: the wrong
+    variants of the definition-direct construction miss the hand-worked Q."""
+    d3 = [np.array([0x01, 0x02], np.uint8), np.array([0x04, 0x08], np.uint8)]
+    d5 = [np.array([1 << (4 * j + i) for i in range(4)], dtype="<u2").view(np.uint8).copy() for j in range(4)]
+    assert rdp_by_definition(d3, 1)[1].tolist() == [0x0B, 0x06]
+    assert rdp_by_definition(d5, 2)[1].view("<u2").tolist() == [0x6A23, 0xC456, 0x89AC, 0x1248]
+    for wrong in (dict(direction=-1), dict(with_row_parity_disk=False), dict(unstored=0), dict(unstored=1)):
+        assert rdp_by_definition(d3, 1, **wrong)[1].tolist() != [0x0B, 0x06], wrong
+        assert rdp_by_definition(d5, 2, **wrong)[1].view("<u2").tolist() != [0x6A23, 0xC456, 0x89AC, 0x1248], wrong
