@@ -10,7 +10,10 @@ survivors (gs_reconstruct).  `value` is the data bytes that pass through those
 two kernels per second of wall time, inputs already in HBM.  The PCIe legs
 (parity D2H pipeline, H2D restore), the paged per-step path and the CPU
 oracle's rate are measured outside the timed steps and reported as extra
-fields of the same JSON line.
+fields of the same JSON line.  The default run then frees the headline
+workload and times the other bulk workloads (70B long context, recovery
+stress) and the bulk paged gather the same way, each with its own roofline
+object, under "configs" and "paged_bulk".
 """
 import argparse
 import json
@@ -27,32 +30,71 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 
 # HBM traffic of one encode launch measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE, scaled by a plain copy kernel of known size; see
-# profiles/encode_contig_llama8b_prefill.md.  Bytes per launch, or None.
-MEASURED_TRAFFIC_BYTES = {   # (workload, code): FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000, KiB -> bytes
-    ("llama8b_prefill", "cauchy"): 51539161269,
-    ("llama8b_prefill", "power"): 51539042211,    # profiles/horner_power_code_llama8b_prefill.md
-    ("llama70b_longctx", "cauchy"): 53686381435,  # profiles/kernels_other_workloads.md
+# WRITE_SIZE, scaled by a plain copy kernel of known size.  Bytes per launch,
+# valid for the kernel template and the default launch shape named beside it;
+# a run with another launch shape reports null.
+MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000 in bytes, kernel, profile)
+    ("llama8b_prefill", "cauchy"): (51539161269, "apply_contig_kernel<2, true, 2, true>",
+                                    "profiles/encode_contig_llama8b_prefill.md"),
+    ("llama8b_prefill", "power"): (51539042211, "horner_contig_kernel<2, 2, true>",
+                                   "profiles/horner_power_code_llama8b_prefill.md"),
+    ("llama70b_longctx", "cauchy"): (53686381435, "apply_contig_kernel<2, true, 2, true>",
+                                     "profiles/kernels_other_workloads.md"),
 }
 
 
-def native_step_latency(log):
-    """Decode-step checkpoint latency measured from C (paper_2605_00831_amd/csrc/gs_step_latency.c)."""
+def traffic_fields(workload, code, default_shape):
+    t = MEASURED_TRAFFIC.get((workload, code))
+    if t is None or not default_shape:
+        return {"traffic": None, "traffic_source": None if t is None else
+                "not reported: the launch shape of this run differs from the profiled one (%s)" % t[2]}
+    return {"traffic": t[0], "traffic_source": "%s: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of %s at the default launch "
+                                               "shape, an earlier run of this command (not re-measured by this run)" % (t[2], t[1])}
+
+
+NATIVE_SRC = os.path.join(ROOT, "bench_native.c")
+NATIVE_EXE = os.path.join(ROOT, "bench_native")
+
+
+def build_native(verbose=True):
+    """Compile bench_native.c (plain C against the library's C ABI and the HIP runtime)."""
     import subprocess
-    from paper_2605_00831_amd import build as hip_build
-    from paper_2605_00831_amd import inputs
-    c = inputs.CONFIGS["decode_paged"]
-    if not os.path.exists(hip_build.STEP_LATENCY):
-        return {"error": "gs_step_latency has not been built"}
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    pkg = os.path.join(ROOT, "paper_2605_00831_amd")
+    cmd = [hipcc, "-O2", "-x", "c", NATIVE_SRC, "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-o", NATIVE_EXE + ".tmp",
+           "-L" + pkg, "-lghostserve_ec", "-Wl,-rpath,$ORIGIN/paper_2605_00831_amd", "-L/opt/rocm/lib", "-lamdhip64"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(NATIVE_EXE + ".tmp", NATIVE_EXE)
+    return NATIVE_EXE
+
+
+def profiler_preloaded():
+    """True when this process runs under a profiler that preloads a tool library (rocprofv3 does).
+    Such a library may have initialised the GPU before the interpreter started, and starting another
+    program from a GPU-initialised process is not allowed on the GPU machines."""
+    for var in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "HSA_TOOLS_LIB", "ROCPROFILER_LIBRARY_CTOR"):
+        if "rocprof" in os.environ.get(var, "").lower() or (var != "LD_PRELOAD" and os.environ.get(var)):
+            return True
+    return False
+
+
+def native_probe(log, *argv):
+    """Run bench_native (plain C, no interpreter in its timed loops) as a child process and return its JSON."""
+    import subprocess
+    if profiler_preloaded():
+        return {"skipped": "a profiler tool library is preloaded; child processes are not started under a profiler"}
+    if not os.path.exists(NATIVE_EXE):
+        return {"error": "bench_native has not been built"}
     try:
-        outp = subprocess.run([hip_build.STEP_LATENCY, str(c["steps"]), str(c["layers"])], capture_output=True,
-                              text=True, timeout=240)
+        outp = subprocess.run([NATIVE_EXE] + [str(a) for a in argv], capture_output=True, text=True, timeout=240)
         if outp.returncode != 0:
             return {"error": "exit %d: %s" % (outp.returncode, outp.stderr.strip()[-200:])}
         res = json.loads(outp.stdout.strip().splitlines()[-1])
     except (subprocess.TimeoutExpired, ValueError, IndexError) as e:
         return {"error": repr(e)[:200]}
-    log("[bench] decode step from C: " + json.dumps(res))
+    log("[bench] native %s: %s" % (argv[0], json.dumps(res)))
     return res
 
 
@@ -75,6 +117,12 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 8 GiB device-to-device copy kernel (counter calibration under rocprofv3 --pmc)")
     ap.add_argument("--cpu-sample-mib", type=int, default=4096, help="bytes per shard for the CPU oracle leg")
+    ap.add_argument("--launch-shape", default=None, metavar="U,T,NT,ILV",
+                    help="gs_set_launch_shape(unroll, tiles_per_wg, nontemporal, interleave_shift) for sweeps; "
+                         "0 / -1 keep a knob's default")
+    ap.add_argument("--only", default=None, choices=["headline", "paged_bulk"],
+                    help="headline: the timed steps of --workload and its extras, not the other bulk workloads; "
+                         "paged_bulk: only the bulk paged-gather leg (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -84,7 +132,9 @@ def main():
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
     # The decode-step latency probe is a plain C program: run it as a child process first, before
     # this process opens the GPU, so that the two never hold the device at the same time.
-    native = None if args.no_extras else native_step_latency(log)
+    native = None
+    if not args.no_extras and args.only != "paged_bulk":
+        native = {"decode": native_probe(log, "decode", inputs_steps(), 32), "many": native_probe(log, "many")}
 
     import torch
     from paper_2605_00831_amd import binding as gs
@@ -96,28 +146,20 @@ def main():
         return 2
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.launch_shape:
+        u, t, nt, ilv = (int(x) for x in args.launch_shape.split(","))
+        gs.gs_set_launch_shape(u, t, nt, ilv)
+    if args.only == "paged_bulk":
+        print(json.dumps({"paged_bulk": paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)}), flush=True)
+        return 0
 
     cfg = inputs.CONFIGS[args.workload]
-    k, m = cfg["k"], cfg["m"]
-    total = inputs.config_total_bytes(args.workload)
-    S = total // k
-    # recovery_stress loses a data shard, another data shard and a parity shard (one of its seeded triples)
-    erased = list(cfg.get("erased", (2, 5, 9) if args.workload == "recovery_stress" else (1, 3) if k >= 4 else (0,)))[:m]
-    log("[bench] workload %s: k=%d m=%d S=%.3f GiB total %.1f GiB" % (args.workload, k, m, S / 2**30, total / 2**30))
-
     t0 = time.perf_counter()
-    if args.workload == "recovery_stress":
-        # first half of the shards uniform random bytes, second half bf16 N(0,1) KV bytes
-        half = (k // 2) * S
-        buf = torch.empty(total, dtype=torch.uint8, device=dev)
-        buf[:half] = inputs.uniform_bytes_device(inputs.config_seed(args.workload), half, dev)
-        buf[half:] = inputs.kv_bytes_device(inputs.config_seed(args.workload) + 1, total - half, "bf16", 1.0, dev)
-    else:
-        buf = inputs.kv_bytes_device(inputs.config_seed(args.workload), total, cfg["dtype"], cfg["sigma"], dev)
-    data = [buf[j * S:(j + 1) * S] for j in range(k)]
-    parity = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(m)]
+    # recovery_stress loses a data shard, another data shard and a parity shard (one of its seeded triples)
+    k, m, S, erased, data, parity = workload_buffers(torch, inputs, args.workload)
     torch.cuda.synchronize()
-    log("[bench] inputs generated in %.1f s" % (time.perf_counter() - t0))
+    log("[bench] workload %s: k=%d m=%d S=%.3f GiB total %.1f GiB, inputs generated in %.1f s"
+        % (args.workload, k, m, S / 2**30, k * S / 2**30, time.perf_counter() - t0))
     shards = data + parity
 
     kind = gs.GS_CAUCHY if args.code == "cauchy" else gs.GS_POWER
@@ -190,9 +232,9 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.code)),
             "algorithmic_bytes_per_launch": enc_alg_bytes,
             "avg_launch_ms": round(enc_avg, 4),
+            **traffic_fields(args.workload, args.code, args.launch_shape is None),
         },
     }
 
@@ -206,8 +248,184 @@ def main():
     if not args.no_extras:
         out.update(extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log, native))
 
+    if args.only is None and args.code == "cauchy":
+        # the other bulk workloads, timed the same way after the headline workload's buffers are gone
+        del data, parity, shards
+        torch.cuda.empty_cache()
+        out["configs"] = [dict(workload=args.workload, kernel=out["roofline"]["kernel"],
+                               algorithmic_bytes_per_launch=enc_alg_bytes, avg_launch_ms=out["roofline"]["avg_launch_ms"],
+                               frac=out["roofline"]["frac"], reconstruct_ms=out["reconstruct_ms"],
+                               reconstruct_frac=out["reconstruct_hbm_frac"], erased=erased,
+                               checkpoint_ms=out.get("checkpoint", {}).get("latency_ms"),
+                               restore_ms=out.get("restore", {}).get("latency_ms"))]
+        for name in ("llama8b_prefill", "llama70b_longctx", "recovery_stress"):
+            if name != args.workload:
+                out["configs"].append(bulk_config(torch, gs, inputs, name, max(args.steps, 20), args.warmup, log,
+                                                  pipelines=not args.no_extras, default_shape=args.launch_shape is None))
+                torch.cuda.empty_cache()
+        out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
+
     print(json.dumps(out), flush=True)
     return 0
+
+
+def inputs_steps():
+    from paper_2605_00831_amd import inputs
+    return inputs.CONFIGS["decode_paged"]["steps"]
+
+
+def workload_buffers(torch, inputs, name, dev="cuda:0"):
+    """(k, m, S, erased, data shards, parity shards) of a bulk workload, generated on the device."""
+    cfg = inputs.CONFIGS[name]
+    k, m = cfg["k"], cfg["m"]
+    total = inputs.config_total_bytes(name)
+    S = total // k
+    erased = list(cfg.get("erased", (2, 5, 9) if name == "recovery_stress" else (1, 3) if k >= 4 else (0,)))[:m]
+    if name == "recovery_stress":
+        half = (k // 2) * S
+        buf = torch.empty(total, dtype=torch.uint8, device=dev)
+        buf[:half] = inputs.uniform_bytes_device(inputs.config_seed(name), half, dev)
+        buf[half:] = inputs.kv_bytes_device(inputs.config_seed(name) + 1, total - half, "bf16", 1.0, dev)
+    else:
+        buf = inputs.kv_bytes_device(inputs.config_seed(name), total, cfg["dtype"], cfg["sigma"], dev)
+    data = [buf[j * S:(j + 1) * S] for j in range(k)]
+    parity = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(m)]
+    return k, m, S, erased, data, parity
+
+
+def bulk_config(torch, gs, inputs, name, launches, warmup, log, pipelines=True, default_shape=True):
+    """One more bulk workload: `launches` encode and reconstruct launches, each between events on the
+    launch stream, then (optionally) the checkpoint and restore pipelines of that workload."""
+    cfg = inputs.CONFIGS[name]
+    k, m, S, erased, data, parity = workload_buffers(torch, inputs, name)
+    shards = data + parity
+    code = gs.gs_make_code(k, m)
+    for _ in range(max(warmup, 1)):
+        gs.gs_encode(code, data, parity, S)
+        gs.gs_reconstruct(code, shards, erased, S)
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(launches)]
+    for ev in evs:
+        ev[0].record()
+        gs.gs_encode(code, data, parity, S)
+        ev[1].record()
+        gs.gs_reconstruct(code, shards, erased, S)
+        ev[2].record()
+    torch.cuda.synchronize()
+    enc = sum(e[0].elapsed_time(e[1]) for e in evs) / launches
+    rec = sum(e[1].elapsed_time(e[2]) for e in evs) / launches
+    enc_bytes, rec_bytes = (k + m) * S, (k + len(erased)) * S
+    res = {"workload": name, "k": k, "m": m, "shard_bytes": S, "erased": erased, "launches": launches,
+           "kernel": "apply_contig_kernel (encode, k=%d m=%d)" % (k, m),
+           "algorithmic_bytes_per_launch": enc_bytes, "avg_launch_ms": round(enc, 4),
+           "achieved": round(enc_bytes / enc / 1e6, 1), "frac": round(enc_bytes / enc / 1e6 / HBM_PEAK_GBPS, 4),
+           "encode_GBps_data": round(k * S / enc / 1e6, 1),
+           "reconstruct_algorithmic_bytes_per_launch": rec_bytes, "reconstruct_ms": round(rec, 4),
+           "reconstruct_frac": round(rec_bytes / rec / 1e6 / HBM_PEAK_GBPS, 4),
+           "reconstruct_GBps_data": round(k * S / rec / 1e6, 1),
+           **traffic_fields(name, "cauchy", default_shape)}
+    if pipelines:
+        chunk_tokens = cfg.get("chunk_tokens")
+        if chunk_tokens:
+            chunk = chunk_tokens * cfg["batch"] * inputs.bytes_per_token(cfg["layers"]) // k
+        else:
+            chunk = max(16, (S // 4 + 15) // 16 * 16)
+        host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+        pipe = gs.gs_pipe_create(code, chunk, 2)
+
+        def best(fn, n=3):
+            ts = []
+            for _ in range(n):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                gs.gs_pipe_sync(pipe)
+                ts.append(time.perf_counter() - t0)
+            return min(ts)
+        ck = best(lambda: gs.gs_checkpoint(pipe, data, S, host))
+        rs = best(lambda: gs.gs_restore(pipe, shards, host, erased, S))
+        n_back = sum(1 for s in gs.gs_decode_matrix(code, erased)[1] if s >= k)
+        res.update({"chunk_bytes_per_shard": chunk, "checkpoint_ms": round(ck * 1e3, 2),
+                    "checkpoint_parity_GBps": round(m * S / ck / 1e9, 2),
+                    "checkpoint_frac_of_pcie_gen5_x16": round(m * S / ck / 1e9 / PCIE_GEN5_X16_GBPS, 3),
+                    "restore_ms": round(rs * 1e3, 2), "restore_parity_shards_from_host": n_back,
+                    "restore_parity_h2d_GBps": round(n_back * S / rs / 1e9, 2)})
+        gs.gs_pipe_destroy(pipe)
+        del host
+    log("[bench] config %s: %s" % (name, json.dumps(res)))
+    return res
+
+
+def paged_bulk(torch, gs, inputs, log, pipelines=True):
+    """Bulk paged gather (the recovery-stress shape on a paged pool): 64 planes of 256 MiB, shards of
+    2 GiB gathered through a block table, 32 KiB pages (16-token blocks) and 2 KiB pages (token slots),
+    behind a seeded random permutation and, as the control, behind the identity table; 4+2 and 8+3.
+    Each case: events around 10 launches on the launch stream.  Then the paged checkpoint / restore
+    pipelines (8+3, 32 KiB pages, shards {2, 5} and parity shard 9 lost)."""
+    dev = "cuda:0"
+    n_planes, plane_bytes, shard_per_plane = 64, 256 << 20, 32 << 20
+    pool = inputs.kv_bytes_device(inputs.config_seed("recovery_stress") + 7, n_planes * plane_bytes, "bf16", 1.0, dev)
+    base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(n_planes)], dtype=torch.int64, device=dev)
+    S = n_planes * shard_per_plane
+    par = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(3)]
+    cases = []
+    tables = {}
+    for page in (32768, 2048):
+        ppp, pps = plane_bytes // page, shard_per_plane // page
+        perm = inputs.block_table_np(inputs.config_seed("recovery_stress"), 8, pps, ppp)
+        ident = np.arange(8 * pps, dtype=np.int32).reshape(8, pps)
+        for tname, tab in (("random permutation", perm), ("identity", ident)):
+            table = torch.from_numpy(np.ascontiguousarray(tab)).to(dev)
+            tables[(page, tname)] = table
+            for k, m in ((4, 2), (8, 3)):
+                code = gs.gs_make_code(k, m)
+                fn = lambda: gs.gs_encode_paged(code, base, n_planes, page, ppp, table, pps, par[:m])
+                for _ in range(3):
+                    fn()
+                torch.cuda.synchronize()
+                n = 10
+                evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+                evs[0].record()
+                for i in range(n):
+                    fn()
+                    evs[i + 1].record()
+                torch.cuda.synchronize()
+                ms = sum(evs[i].elapsed_time(evs[i + 1]) for i in range(n)) / n
+                alg = (k + m) * S
+                cases.append({"k": k, "m": m, "page_bytes": page, "table": tname, "shard_bytes": S, "launches": n,
+                              "roofline": {"kernel": "apply_paged_kernel (encode, k=%d m=%d)" % (k, m), "bound": "hbm",
+                                           "achieved": round(alg / ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                           "frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
+                                           "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(ms, 4)}})
+    res = {"pool": "%d planes x %d MiB, %d MiB of every shard per plane" % (n_planes, plane_bytes >> 20, shard_per_plane >> 20),
+           "cases": cases}
+    if pipelines:
+        k, m, page, erased = 8, 3, 32768, [2, 5, 9]
+        ppp, pps = plane_bytes // page, shard_per_plane // page
+        table = tables[(page, "random permutation")]
+        code = gs.gs_make_code(k, m)
+        host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+        chunk = S // 8
+        pipe = gs.gs_pipe_create(code, chunk, 2)
+
+        def best(fn, n=3):
+            ts = []
+            for _ in range(n):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                fn()
+                gs.gs_pipe_sync(pipe)
+                ts.append(time.perf_counter() - t0)
+            return min(ts)
+        ck = best(lambda: gs.gs_checkpoint_paged(pipe, base, n_planes, page, ppp, table, pps, host))
+        rs = best(lambda: gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, erased, parity_out=par))
+        res["pipelines"] = {"k": k, "m": m, "page_bytes": page, "erased": erased, "chunk_bytes_per_shard": chunk,
+                            "checkpoint_paged_ms": round(ck * 1e3, 2), "checkpoint_parity_GBps": round(m * S / ck / 1e9, 2),
+                            "checkpoint_frac_of_pcie_gen5_x16": round(m * S / ck / 1e9 / PCIE_GEN5_X16_GBPS, 3),
+                            "restore_paged_ms": round(rs * 1e3, 2), "restore_parity_h2d_GBps": round(2 * S / rs / 1e9, 2)}
+        gs.gs_pipe_destroy(pipe)
+    log("[bench] paged bulk: " + json.dumps(res))
+    return res
 
 
 def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, log, native=None):
@@ -383,7 +601,9 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
 
     # ---- CPU oracle on the same bytes (bounded sample), all host cores
     import oracle
-    nthreads = min(os.cpu_count() or 1, 16)
+    # threads the oracle runs on: the CPUs this process may use, at most 16 (the GPU machine's CPU share
+    # for one GPU; its nproc reports the whole machine)
+    nthreads = min(len(os.sched_getaffinity(0)) or 1, 16)
     Ss = min(S, args.cpu_sample_mib << 20)
     host_data = [d[:Ss].cpu().numpy() for d in data]
     P = oracle.generator(k, m)
@@ -394,6 +614,8 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     torch.cuda.synchronize()
     same = all(np.array_equal(parity[i][:Ss].cpu().numpy(), want[i]) for i in range(m))
     res["cpu_baseline"] = {"value": round(k * Ss / cpu_s / 1e9, 3), "unit": "GB/s", "cores": nthreads,
+                           "host_cpus_online": os.cpu_count(),
+                           "host_cpus_this_process_may_use": len(os.sched_getaffinity(0)),
                            "kind": "oracle",
                            "sample": "encode of the first %d MiB of each of the %d shards (%.1f GiB of data), %.1f s"
                                      % (Ss >> 20, k, k * Ss / 2**30, cpu_s),
@@ -410,9 +632,10 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
     del host_data, want, one
 
     # ---- streaming decode-step checkpoint (paged, k=4, m=1), latency over 1000 steps
-    res["decode_step"] = decode_steps(torch, gs, inputs, log, native)
+    res["decode_step"] = decode_steps(torch, gs, inputs, log, native["decode"] if native else None)
     # ---- many small chunks: one launch per chunk, a stream per chunk, or one grouped launch
-    res["many_chunks"] = many_chunks(torch, gs, log)
+    res["many_chunks"] = {"through_python_binding": many_chunks(torch, gs, log),
+                          "from_c": native["many"] if native else None}
     # ---- per-chunk latency breakdown against chunk size (the shape of the paper's kernel microbenchmark)
     res["chunk_sweep"] = chunk_sweep(torch, gs, inputs, log)
     return res

@@ -38,7 +38,12 @@
  *   - Shard base pointers must be 16-byte aligned; shard_bytes may be any
  *     value (the partial last chunk is masked by bounds, Section 4.2).  Bytes
  *     at offsets >= shard_bytes are neither read nor written.
- *   - Input and output buffers of one call must not overlap.
+ *   - An output buffer of a call may overlap neither an input nor another
+ *     output of that call (of the same chunk, for the many-chunk forms):
+ *     contiguous shards are checked and the call returns GS_EINVAL; pages
+ *     named by a block table live in device memory and cannot be checked --
+ *     a table that names one page twice among the rows a call reads and
+ *     writes gives undefined bytes in that page.
  *   - A gs_code is immutable after creation and may be shared between threads.
  *     gs_pipe and gs_batch objects keep the pointer to the gs_code they
  *     were made for: free the code only after them.  Destroy an object only
@@ -183,7 +188,9 @@ void gs_pipe_destroy(gs_pipe *pipe);
  *   data         HOST array of k DEVICE pointers, shard_bytes each
  *   host_parity  HOST array of m PINNED host pointers, shard_bytes each
  * Returns after enqueuing; the parity bytes are valid once gs_pipe_sync()
- * returns (or after the event gs_pipe_done_event() on another stream). */
+ * returns (or after the event gs_pipe_done_event() on another stream).  If a
+ * runtime call fails part of the way (GS_EHIP), gs_pipe_sync() still waits for
+ * everything that had been enqueued, so the buffers can be released safely. */
 int gs_checkpoint(gs_pipe *pipe, const void *const *data, size_t shard_bytes,
                   void *const *host_parity, void *compute_stream);
 
@@ -198,6 +205,32 @@ int gs_checkpoint(gs_pipe *pipe, const void *const *data, size_t shard_bytes,
  *                shards are ignored) */
 int gs_restore(gs_pipe *pipe, void *const *shards, void *const *host_parity,
                const int *erased, int n_erased, size_t shard_bytes, void *compute_stream);
+
+/* The same two pipelines over a paged KV pool (geometry and argument meaning
+ * as in gs_encode_paged / gs_reconstruct_paged): Alg. 1 and Alg. 2 run on the
+ * serving engine's paged cache (Section 5), where a chunk of tokens is a window
+ * of page slots in every plane.  A chunk here is the
+ *     slots_per_chunk = min(pages_per_shard, chunk_bytes / (n_planes*page_bytes))
+ * next slots of every plane (chunk_bytes of the pipe; GS_EINVAL if that is
+ * zero); the last chunk may be shorter.  Parity lives in host memory in the
+ * dense layout gs_encode_paged writes, [plane][pages_per_shard][page_bytes], so
+ * what a paged checkpoint stores equals what one gs_encode_paged call over the
+ * whole table would have produced; each chunk's window of it moves with one
+ * strided copy per parity shard.
+ *   host_parity  HOST array of m PINNED pointers, n_planes*pages_per_shard*page_bytes each
+ *   parity_out   gs_restore_paged only: HOST array of m DEVICE pointers in the
+ *                same dense layout, used only for erased parity shards (may be
+ *                NULL when none is erased)
+ * A lost data shard is rebuilt INTO the pages its table row names.  The block
+ * table and plane pointers are read by the kernels when they run and must stay
+ * unchanged until the pipe has finished. */
+int gs_checkpoint_paged(gs_pipe *pipe, const void *const *plane_base, int n_planes, size_t page_bytes,
+                        int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                        void *const *host_parity, void *compute_stream);
+int gs_restore_paged(gs_pipe *pipe, const void *const *plane_base, int n_planes, size_t page_bytes,
+                     int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                     void *const *host_parity, void *const *parity_out, const int *erased, int n_erased,
+                     void *compute_stream);
 
 /* block the host until everything the pipe enqueued has finished */
 int gs_pipe_sync(gs_pipe *pipe);
@@ -354,9 +387,9 @@ int gs_coef_words(int c, uint32_t *words_out);
  *   interleave_shift  log2 of the modulus with which the contiguous kernel
  *                     deals 1 KiB pieces to workgroups (0 = consecutive
  *                     pieces, default 5; at most 10)
- * Results are identical for every setting.  Process-wide and unsynchronised
- * (as is gs_set_power_horner): set them while no other thread is inside the
- * library. */
+ * Results are identical for every setting.  Process-wide, like
+ * gs_set_power_horner; both are atomic: a call running in another thread uses
+ * either the old or the new setting as a whole. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
 /* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
  * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0

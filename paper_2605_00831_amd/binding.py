@@ -19,7 +19,7 @@ GS_CAUCHY, GS_VANDERMONDE, GS_RDP, GS_POWER = 0, 1, 2, 3
 EXPORTS = [
     "gs_make_code", "gs_free_code", "gs_code_params", "gs_code_matrix", "gs_decode_matrix", "gs_make_rdp_code", "gs_rdp_prime", "gs_rdp_cell_bytes", "gs_rdp_plan",
     "gs_encode", "gs_encode_paged", "gs_reconstruct", "gs_reconstruct_paged",
-    "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_pipe_sync",
+    "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_checkpoint_paged", "gs_restore_paged", "gs_pipe_sync",
     "gs_pipe_done_event", "gs_pipe_set_timing", "gs_pipe_chunk_times",
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
     "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
@@ -86,6 +86,9 @@ def lib():
     L.gs_pipe_destroy.restype = None
     L.gs_checkpoint.argtypes = [_vp, _vpp, ctypes.c_size_t, _vpp, _vp]
     L.gs_restore.argtypes = [_vp, _vpp, _vpp, _intp, ctypes.c_int, ctypes.c_size_t, _vp]
+    L.gs_checkpoint_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp, ctypes.c_int, _vpp, _vp]
+    L.gs_restore_paged.argtypes = [_vp, _vp, ctypes.c_int, ctypes.c_size_t, ctypes.c_int64, _vp, ctypes.c_int, _vpp, _vpp,
+                                   _intp, ctypes.c_int, _vp]
     L.gs_pipe_sync.argtypes = [_vp]
     L.gs_pipe_done_event.argtypes = [_vp]
     L.gs_pipe_done_event.restype = _vp
@@ -292,6 +295,24 @@ def gs_restore(pipe, shards, host_parity, erased, shard_bytes, stream=None):
     er, n = _int_array(erased)
     _check(lib().gs_restore(pipe.handle, _ptr_array(shards), _ptr_array(host_parity), er, n, shard_bytes,
                             _stream(stream)), "gs_restore")
+
+
+def gs_checkpoint_paged(pipe, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                        host_parity, stream=None):
+    if len(host_parity) != pipe.code.m:
+        raise ValueError("need m host parity pointers")
+    _check(lib().gs_checkpoint_paged(pipe.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane, _ptr(table),
+                                     pages_per_shard, _ptr_array(host_parity), _stream(stream)), "gs_checkpoint_paged")
+
+
+def gs_restore_paged(pipe, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
+                     host_parity, erased, parity_out=None, stream=None):
+    if len(host_parity) != pipe.code.m or (parity_out is not None and len(parity_out) != pipe.code.m):
+        raise ValueError("need m host parity pointers (and m device parity pointers, if any)")
+    er, n = _int_array(erased)
+    po = _ptr_array(parity_out) if parity_out is not None else None
+    _check(lib().gs_restore_paged(pipe.handle, _ptr(plane_base), n_planes, page_bytes, pages_per_plane, _ptr(table),
+                                  pages_per_shard, _ptr_array(host_parity), po, er, n, _stream(stream)), "gs_restore_paged")
 
 
 def gs_pipe_sync(pipe):

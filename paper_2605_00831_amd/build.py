@@ -53,44 +53,7 @@ def build(verbose=True):
     return LIB
 
 
-C_CHECK = os.path.join(os.path.dirname(HERE), "tests", "c_abi_roundtrip")
-
-
-def build_c_check(verbose=True):
-    """Plain C program against the C ABI (tests/c_abi_roundtrip.c), linked with the
-    library and with the oracle's C file; tests/test_gpu_c_abi.py runs it."""
-    root = os.path.dirname(HERE)
-    cmd = [HIPCC, "-O2", "-x", "c", os.path.join(root, "tests", "c_abi_roundtrip.c"),
-           os.path.join(root, "oracle", "gs_oracle.c"),
-           "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-o", C_CHECK + ".tmp",
-           "-L" + HERE, "-lghostserve_ec", "-Wl,-rpath,$ORIGIN/../paper_2605_00831_amd",
-           "-L/opt/rocm/lib", "-lamdhip64", "-lpthread"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    os.replace(C_CHECK + ".tmp", C_CHECK)
-    return C_CHECK
-
-
-STEP_LATENCY = os.path.join(HERE, "gs_step_latency")
-
-
-def build_step_latency(verbose=True):
-    """Native latency probe of the decode-step checkpoint (csrc/gs_step_latency.c); bench.py runs it."""
-    cmd = [HIPCC, "-O2", "-x", "c", os.path.join(CSRC, "gs_step_latency.c"),
-           "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-o", STEP_LATENCY + ".tmp",
-           "-L" + HERE, "-lghostserve_ec", "-Wl,-rpath,$ORIGIN",
-           "-L/opt/rocm/lib", "-lamdhip64"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    os.replace(STEP_LATENCY + ".tmp", STEP_LATENCY)
-    return STEP_LATENCY
-
-
 if __name__ == "__main__":
     build()
     print("built", LIB)
-    print("built", build_c_check())
-    print("built", build_step_latency())
     sys.exit(0)

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -18,14 +19,34 @@ namespace gs {
 
 thread_local int g_last_hip_error = 0;
 
-// defaults chosen by measurement on MI355X; see gs_set_launch_shape()
-static LaunchShape g_default_shape = {0, 1, 1, 5};  // unroll 0: chosen per kernel family
-static LaunchShape g_shape = g_default_shape;
+// Launch-shape knobs, defaults chosen by measurement on MI355X; see
+// gs_set_launch_shape().  The four knobs live in one atomic word, so a launch
+// that runs while another thread changes them sees either the old or the new
+// set, never a mixture; every setting gives the same bytes.
+static constexpr LaunchShape kDefaultShape = {0, 1, 1, 5};  // unroll 0: chosen per kernel family
 
-LaunchShape current_shape() { return g_shape; }
+static constexpr uint64_t pack_shape(const LaunchShape &s)
+{
+    return static_cast<uint64_t>(static_cast<uint8_t>(s.unroll)) | (static_cast<uint64_t>(static_cast<uint8_t>(s.nontemporal)) << 8) |
+           (static_cast<uint64_t>(static_cast<uint8_t>(s.interleave_shift)) << 16) |
+           (static_cast<uint64_t>(static_cast<uint32_t>(s.tiles_per_wg)) << 32);
+}
+
+static std::atomic<uint64_t> g_shape{pack_shape(kDefaultShape)};
+
+LaunchShape current_shape()
+{
+    const uint64_t w = g_shape.load(std::memory_order_relaxed);
+    LaunchShape s;
+    s.unroll = static_cast<int>(w & 0xFF);
+    s.nontemporal = static_cast<int>((w >> 8) & 0xFF);
+    s.interleave_shift = static_cast<int>((w >> 16) & 0xFF);
+    s.tiles_per_wg = static_cast<int>(w >> 32);
+    return s;
+}
 
 // power-code encodes go through the Horner kernel unless switched off
-static bool g_power_horner = true;
+static std::atomic<bool> g_power_horner{true};
 
 int hip_status(hipError_t e)
 {
@@ -66,23 +87,69 @@ int apply_matrix(int rows, int cols, const uint8_t *C, const void *const *in, vo
 }
 
 // paged form of apply_matrix: streams are table rows or dense buffers
-static int apply_matrix_paged(int rows, int cols, const uint8_t *C, const void *const *plane_base, int n_planes,
-                              size_t page_bytes, int64_t pages_per_plane, const int32_t *table,
-                              int pages_per_shard, const PagedStream *in, const PagedStream *out,
-                              hipStream_t stream)
+int apply_matrix_paged(int rows, int cols, const uint8_t *C, const PagedView &v, const PagedStream *in,
+                       const PagedStream *out, hipStream_t stream)
 {
     const LaunchShape shape = current_shape();
     for (int r0 = 0; r0 < rows; r0 += kLaunchMaxM) {
         const int nr = std::min(kLaunchMaxM, rows - r0);
         for (int c0 = 0; c0 < cols; c0 += kLaunchMaxK) {
             const int nc = std::min(kLaunchMaxK, cols - c0);
-            const hipError_t e = launch_apply_paged(nr, nc, C + static_cast<size_t>(r0) * cols + c0, cols, plane_base,
-                                                    n_planes, page_bytes, pages_per_plane, table, pages_per_shard,
-                                                    in + c0, out + r0, c0 != 0, shape, stream);
+            const hipError_t e = launch_apply_paged(nr, nc, C + static_cast<size_t>(r0) * cols + c0, cols, v.plane_base,
+                                                    v.n_planes, v.page_bytes, v.pages_per_plane, v.table,
+                                                    v.table_stride, v.n_slots, in + c0, out + r0, c0 != 0, shape, stream);
             if (e != hipSuccess) return hip_status(e);
         }
     }
     return GS_OK;
+}
+
+// Geometry checks shared by the paged entry points.  GS_OK with *empty set
+// means there is nothing to do.
+int check_paged_geometry(const void *const *plane_base, int n_planes, size_t page_bytes, int64_t pages_per_plane,
+                         const int32_t *table, int pages_per_shard, bool *empty)
+{
+    *empty = false;
+    if (plane_base == nullptr || table == nullptr) return GS_EINVAL;
+    if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
+    if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
+    if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
+    if (n_planes == 0 || pages_per_shard == 0) {
+        *empty = true;
+        return GS_OK;
+    }
+    return pages_per_plane == 0 ? GS_EINVAL : GS_OK;
+}
+
+// Rebuild over a paged view with a matrix from decode_matrix: surviving data
+// shards are gathered from their pages, surviving parity comes from
+// parity_in[i] (dense), a lost data shard is scattered into the pages of its
+// table row, a lost parity shard goes to parity_out[i] (dense).
+int rebuild_paged(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &surv, const PagedView &v,
+                  const PagedStream *parity_in, const PagedStream *parity_out, const int *erased, int n_erased,
+                  hipStream_t stream)
+{
+    const int k = code->k;
+    std::vector<PagedStream> in(k), out(n_erased);
+    for (int j = 0; j < k; ++j) {
+        if (surv[j] < k) {
+            in[j] = PagedStream{surv[j], nullptr};
+        } else {
+            in[j] = parity_in[surv[j] - k];
+            if (in[j].dense == nullptr || !aligned16(in[j].dense)) return GS_EINVAL;
+            in[j].table_row = -1;
+        }
+    }
+    for (int x = 0; x < n_erased; ++x) {
+        if (erased[x] < k) {
+            out[x] = PagedStream{erased[x], nullptr};
+        } else {
+            out[x] = parity_out[erased[x] - k];
+            if (out[x].dense == nullptr || !aligned16(out[x].dense)) return GS_EINVAL;
+            out[x].table_row = -1;
+        }
+    }
+    return apply_matrix_paged(n_erased, k, R.data(), v, in.data(), out.data(), stream);
 }
 
 int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost)
@@ -149,6 +216,26 @@ int shards_read(const gs_code *code, const int *erased, int n_erased, std::vecto
     return decode_matrix(code, erased, n_erased, R, read);
 }
 
+// true when the byte ranges [a, a+n) and [b, b+n) share a byte
+static bool ranges_meet(const void *a, const void *b, size_t n)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y ? y - x < n : x - y < n;
+}
+
+// An output buffer of a call may overlap neither an input nor another output:
+// the kernels read and write tile by tile in no fixed order.
+bool outputs_overlap(const void *const *in, int n_in, void *const *out, int n_out, size_t bytes)
+{
+    for (int r = 0; r < n_out; ++r) {
+        for (int j = 0; j < n_in; ++j)
+            if (ranges_meet(out[r], in[j], bytes)) return true;
+        for (int q = 0; q < r; ++q)
+            if (ranges_meet(out[r], out[q], bytes)) return true;
+    }
+    return false;
+}
+
 int check_encode_args(const gs_code *code, const void *const *data, void *const *parity, size_t shard_bytes)
 {
     if (shard_bytes == 0) return GS_OK;
@@ -157,6 +244,7 @@ int check_encode_args(const gs_code *code, const void *const *data, void *const 
     for (int i = 0; i < code->m; ++i)
         if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
     if (code->is_rdp() && shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    if (outputs_overlap(data, code->k, parity, code->m, shard_bytes)) return GS_EINVAL;
     return GS_OK;
 }
 
@@ -169,6 +257,12 @@ int check_rebuild_args(const gs_code *code, void *const *shards, const std::vect
     for (int x = 0; x < n_erased; ++x)
         if (shards[erased[x]] == nullptr || !aligned16(shards[erased[x]])) return GS_EINVAL;
     if (code->is_rdp() && shard_bytes % (code->rdp_cell * (code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    const void *in[256];  // k + m <= 256
+    void *out[256];
+    int n_in = 0;
+    for (int s : read) in[n_in++] = shards[s];
+    for (int x = 0; x < n_erased; ++x) out[x] = shards[erased[x]];
+    if (outputs_overlap(in, n_in, out, n_erased, shard_bytes)) return GS_EINVAL;
     return GS_OK;
 }
 
@@ -200,8 +294,16 @@ static int rdp_reconstruct(const gs_code *code, void *const *shards, const int *
         const int s = plan.shard_of_disk[j];
         if (s >= 0 && (shards[s] == nullptr || !aligned16(shards[s]))) return GS_EINVAL;
     }
-    for (int s : plan.outputs)
+    const void *in[kRdpMaxDisks];
+    void *out[2];
+    int n_in = 0, n_out = 0;
+    for (int j = 0; j <= plan.p; ++j)
+        if (plan.shard_of_disk[j] >= 0) in[n_in++] = shards[plan.shard_of_disk[j]];
+    for (int s : plan.outputs) {
         if (shards[s] == nullptr || !aligned16(shards[s])) return GS_EINVAL;
+        out[n_out++] = shards[s];
+    }
+    if (outputs_overlap(in, n_in, out, n_out, shard_bytes)) return GS_EINVAL;
     return hip_status(launch_rdp(plan, shards, shard_bytes, code->rdp_cell, current_shape(), stream));
 }
 
@@ -337,7 +439,7 @@ try {
         return hip_status(launch_rdp(code->rdp_encode, shards.data(), shard_bytes, code->rdp_cell, current_shape(),
                                          static_cast<hipStream_t>(stream)));
     }
-    if (code->kind == GS_POWER && g_power_horner && code->m >= 2 && code->k <= kLaunchMaxK)
+    if (code->kind == GS_POWER && g_power_horner.load(std::memory_order_relaxed) && code->m >= 2 && code->k <= kLaunchMaxK)
         return hip_status(launch_horner(code->m, code->k, code->P.data(), code->k, data, parity, shard_bytes,
                                         current_shape(), static_cast<hipStream_t>(stream)));
     return apply_matrix(code->m, code->k, code->P.data(), data, parity, shard_bytes,
@@ -351,20 +453,18 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
                     int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
                     void *const *parity, void *stream)
 try {
-    if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
+    if (code == nullptr || parity == nullptr) return GS_EINVAL;
     if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard; it has no paged form
-    if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
-    if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
-    if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
-    if (n_planes == 0 || pages_per_shard == 0) return GS_OK;
-    if (pages_per_plane == 0) return GS_EINVAL;
+    bool empty;
+    const int rc = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
+    if (rc != GS_OK || empty) return rc;
     for (int i = 0; i < code->m; ++i)
         if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
     std::vector<PagedStream> in(code->k), out(code->m);
     for (int j = 0; j < code->k; ++j) in[j] = PagedStream{j, nullptr};
     for (int i = 0; i < code->m; ++i) out[i] = PagedStream{-1, parity[i]};
-    return apply_matrix_paged(code->m, code->k, code->P.data(), plane_base, n_planes, page_bytes, pages_per_plane,
-                              table, pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
+    const PagedView v{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, pages_per_shard};
+    return apply_matrix_paged(code->m, code->k, code->P.data(), v, in.data(), out.data(), static_cast<hipStream_t>(stream));
 }
 catch (...) {
     return caught();
@@ -374,39 +474,20 @@ int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int
                          int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
                          void *const *parity, const int *erased, int n_erased, void *stream)
 try {
-    if (code == nullptr || plane_base == nullptr || table == nullptr || parity == nullptr) return GS_EINVAL;
+    if (code == nullptr || parity == nullptr) return GS_EINVAL;
     if (code->is_rdp()) return GS_EINVAL;
-    if (n_planes < 0 || n_planes > 65535 || pages_per_shard < 0 || pages_per_plane < 0) return GS_EINVAL;
-    if (page_bytes == 0 || page_bytes % 16 != 0) return GS_EINVAL;
-    if ((page_bytes / 16) * static_cast<uint64_t>(pages_per_shard) >= (1ull << 32)) return GS_EINVAL;
+    bool empty;
+    const int rc0 = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
+    if (rc0 != GS_OK) return rc0;
     std::vector<uint8_t> R;
     std::vector<int> surv;
     const int rc = decode_matrix(code, erased, n_erased, R, surv);
     if (rc != GS_OK) return rc;
-    if (n_erased == 0 || n_planes == 0 || pages_per_shard == 0) return GS_OK;
-    if (pages_per_plane == 0) return GS_EINVAL;
-    const int k = code->k;
-    std::vector<PagedStream> in(k), out(n_erased);
-    for (int j = 0; j < k; ++j) {
-        if (surv[j] < k) {
-            in[j] = PagedStream{surv[j], nullptr};
-        } else {
-            const void *p = parity[surv[j] - k];
-            if (p == nullptr || !aligned16(p)) return GS_EINVAL;
-            in[j] = PagedStream{-1, p};
-        }
-    }
-    for (int x = 0; x < n_erased; ++x) {
-        if (erased[x] < k) {
-            out[x] = PagedStream{erased[x], nullptr};
-        } else {
-            void *p = parity[erased[x] - k];
-            if (p == nullptr || !aligned16(p)) return GS_EINVAL;
-            out[x] = PagedStream{-1, p};
-        }
-    }
-    return apply_matrix_paged(n_erased, k, R.data(), plane_base, n_planes, page_bytes, pages_per_plane, table,
-                              pages_per_shard, in.data(), out.data(), static_cast<hipStream_t>(stream));
+    if (n_erased == 0 || empty) return GS_OK;
+    std::vector<PagedStream> dense(code->m);
+    for (int i = 0; i < code->m; ++i) dense[i] = PagedStream{-1, parity[i]};
+    const PagedView v{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, pages_per_shard};
+    return rebuild_paged(code, R, surv, v, dense.data(), dense.data(), erased, n_erased, static_cast<hipStream_t>(stream));
 }
 catch (...) {
     return caught();
@@ -452,24 +533,24 @@ int gs_coef_words(int c, uint32_t *words_out)
 
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift)
 {
-    LaunchShape s = g_default_shape;
+    LaunchShape s = kDefaultShape;
     if (unroll > 0) {
         if (unroll != 1 && unroll != 2 && unroll != 4) return GS_EINVAL;
         s.unroll = unroll;
     }
-    if (tiles_per_wg > 0) s.tiles_per_wg = tiles_per_wg;
+    if (tiles_per_wg > 0) s.tiles_per_wg = tiles_per_wg;  // any positive int fits the packed word
     if (nontemporal >= 0) s.nontemporal = nontemporal ? 1 : 0;
     if (interleave_shift >= 0) {
         if (interleave_shift > 10) return GS_EINVAL;
         s.interleave_shift = interleave_shift;
     }
-    g_shape = s;
+    g_shape.store(pack_shape(s), std::memory_order_relaxed);
     return GS_OK;
 }
 
 int gs_set_power_horner(int enable)
 {
-    g_power_horner = enable != 0;
+    g_power_horner.store(enable != 0, std::memory_order_relaxed);
     return GS_OK;
 }
 

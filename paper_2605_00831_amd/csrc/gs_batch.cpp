@@ -59,8 +59,10 @@ static int run_batch(gs_batch *b, int rows, const uint8_t *C, int n, const void 
     if (b->used[slot]) GS_TRY(hipEventSynchronize(b->done[slot]));
     uint8_t *hslot = b->host + static_cast<size_t>(slot) * b->slot_bytes;
     uint8_t *dslot = b->dev + static_cast<size_t>(slot) * b->slot_bytes;
+    int order[kLaunchMaxM];
+    batch_row_order(rows, k, C, k, order);  // the same matrix for every chunk: planned once
     for (int c = 0; c < n; ++c)
-        write_batch_desc(hslot, c, rows, k, C, k, in + static_cast<size_t>(c) * in_stride,
+        write_batch_desc(hslot, c, rows, k, order, in + static_cast<size_t>(c) * in_stride,
                          out + static_cast<size_t>(c) * out_stride, bytes[c], shape);
     GS_TRY(hipMemcpyAsync(dslot, hslot, static_cast<size_t>(n) * batch_desc_bytes(), hipMemcpyHostToDevice, stream));
     GS_TRY(launch_apply_batch(rows, k, C, k, dslot, n, max_bytes, shape, stream));
@@ -143,6 +145,8 @@ try {
             if (data[c * k + j] == nullptr || !aligned16(data[c * k + j])) return GS_EINVAL;
         for (int i = 0; i < m; ++i)
             if (parity[c * m + i] == nullptr || !aligned16(parity[c * m + i])) return GS_EINVAL;
+        if (outputs_overlap(data + static_cast<size_t>(c) * k, k, parity + static_cast<size_t>(c) * m, m, shard_bytes[c]))
+            return GS_EINVAL;
     }
     return run_batch(b, m, b->code->P.data(), n_chunks, data, k, parity, m, shard_bytes,
                      static_cast<hipStream_t>(stream));
@@ -175,6 +179,9 @@ try {
             if (shard_bytes[c] != 0 && (p == nullptr || !aligned16(p))) return GS_EINVAL;
             out[static_cast<size_t>(c) * n_erased + x] = p;
         }
+        if (shard_bytes[c] != 0 && outputs_overlap(&in[static_cast<size_t>(c) * k], k, &out[static_cast<size_t>(c) * n_erased],
+                                                   n_erased, shard_bytes[c]))
+            return GS_EINVAL;
     }
     return run_batch(b, n_erased, R.data(), n_chunks, in.data(), k, out.data(), n_erased, shard_bytes,
                      static_cast<hipStream_t>(stream));

@@ -68,14 +68,16 @@ struct PagedArgs {
     // parity layout [plane][slot][page] (row < 0, pointer used)
     const uint8_t *in_ptr[kLaunchMaxK];
     int32_t in_row[kLaunchMaxK];
+    uint32_t in_stride[kLaunchMaxK];   // dense streams: 16-byte vectors from one plane to the next
     uint8_t *out[kLaunchMaxM];
     int32_t out_row[kLaunchMaxM];
+    uint32_t out_stride[kLaunchMaxM];
     uint32_t tab[kLaunchMaxM][kLaunchMaxK][8];
-    uint64_t vecs_per_plane;   // pps * vpp, < 2^32
+    uint64_t vecs_per_plane;   // slots * vpp, < 2^32
     uint64_t pages_per_plane;  // valid page ids are [0, pages_per_plane)
     uint32_t vpp;              // 16-byte vectors per page
     int32_t vpp_shift;         // log2(vpp) if a power of two, else -1
-    uint32_t pps;              // pages per shard
+    uint32_t table_stride;     // entries from one table row to the next (>= slots of this launch)
     int32_t k;
     int32_t accumulate;
     uint32_t tiles_per_wg;
@@ -367,7 +369,7 @@ typedef const int32_t __attribute__((address_space(4))) *ConstTable;
 // and every output is dense, which keeps the per-stream kind tests and one
 // dependent scalar load off the latency-bound decode-step path.
 template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE, bool MIXED>
-__device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint64_t out_base,
+__device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint32_t plane,
                                            const uint64_t (&vv)[U])
 {
     bool ok[U];
@@ -393,7 +395,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
         for (int u = 0; u < U; ++u) acc[r][u] = Acc4{{0, 0, 0, 0}};
     // page id of table row `row` at this lane's slot, or -1 if out of range
     auto page_of = [&](int32_t row, int u) -> int64_t {
-        const uint64_t entry = static_cast<uint64_t>(row) * a.pps + slot[u];
+        const uint64_t entry = static_cast<uint64_t>(row) * a.table_stride + slot[u];
         const int64_t page = WAVE_PAGE ? ((ConstTable)a.table)[entry] : a.table[entry];
         return static_cast<uint64_t>(page) < a.pages_per_plane ? page : -1;
     };
@@ -402,7 +404,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     auto gather = [&](int j, int u) -> u32x4 {
         const int32_t row = MIXED ? a.in_row[j] : first_row + j;
         if (MIXED && row < 0) {
-            const u32x4 x = load16<NT>(a.in_ptr[j], out_base + v[u]);
+            const u32x4 x = load16<NT>(a.in_ptr[j], static_cast<uint64_t>(plane) * a.in_stride[j] + v[u]);
             return ok[u] ? x : u32x4{0, 0, 0, 0};
         }
         const int64_t page = page_of(row, u);
@@ -414,7 +416,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     // where output r of vector u lives; nullptr if it must not be touched
     auto out_at = [&](int r, int u) -> u32x4 * {
         const int32_t row = MIXED ? a.out_row[r] : -1;
-        if (row < 0) return reinterpret_cast<u32x4 *>(a.out[r]) + out_base + v[u];
+        if (row < 0) return reinterpret_cast<u32x4 *>(a.out[r]) + static_cast<uint64_t>(plane) * a.out_stride[r] + v[u];
         const int64_t page = page_of(row, u);
         if (page < 0) return nullptr;
         return reinterpret_cast<u32x4 *>(const_cast<uint8_t *>(pbase)) + static_cast<uint64_t>(page) * a.vpp + off[u];
@@ -460,7 +462,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
 }
 
 // Paged gather: blockIdx.y is the plane; blockIdx.x walks the plane's
-// pages_per_shard * vpp vectors in the same interleaved 1 KiB pieces as the
+// slots * vpp vectors in the same interleaved 1 KiB pieces as the
 // contiguous kernel (gridDim.x is a multiple of the interleave modulus, so the
 // piece residue still names the XCD).  Each lane finds its page slot, looks
 // the page id up in every shard's table row, and reads from that page.
@@ -472,7 +474,6 @@ void apply_paged_kernel(const PagedArgs a)
     constexpr uint32_t kPieces = (kThreads / 64) * U;
     const uint32_t plane = blockIdx.y;
     const uint8_t *pbase = a.plane_base[plane];
-    const uint64_t out_base = static_cast<uint64_t>(plane) * a.vecs_per_plane;
     const uint64_t first_tile = static_cast<uint64_t>(blockIdx.x) * a.tiles_per_wg;
     const uint64_t nx_mask = (1ull << a.nx_shift) - 1;
 
@@ -483,7 +484,7 @@ void apply_paged_kernel(const PagedArgs a)
         uint64_t v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
-        paged_tile<M, ROW0_XOR, U, true, WAVE_PAGE, MIXED>(a, pbase, out_base, v);
+        paged_tile<M, ROW0_XOR, U, true, WAVE_PAGE, MIXED>(a, pbase, plane, v);
     }
 }
 
@@ -710,17 +711,29 @@ struct BatchLauncher {
 
 size_t batch_desc_bytes() { return sizeof(BatchDesc); }
 
-void write_batch_desc(void *slot, int idx, int rows, int k, const uint8_t *coef, int coef_stride,
-                      const void *const *in, void *const *out, size_t bytes, const LaunchShape &shape)
+void batch_row_order(int rows, int k, const uint8_t *coef, int coef_stride, int *order)
+{
+    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
+    for (int r = 0; r < kLaunchMaxM; ++r) order[r] = p.order[r];
+}
+
+uint32_t batch_interleave_shift(int rows, size_t bytes, const LaunchShape &shape)
+{
+    uint32_t nx_shift;
+    uint64_t tiles;
+    interleave_for(bytes / 16, sane_unroll(shape.unroll, rows), shape.interleave_shift, nx_shift, tiles);
+    return nx_shift;
+}
+
+void write_batch_desc(void *slot, int idx, int rows, int k, const int *order, const void *const *in,
+                      void *const *out, size_t bytes, const LaunchShape &shape)
 {
     BatchDesc &d = static_cast<BatchDesc *>(slot)[idx];
-    const RowPlan p = plan_rows(rows, k, coef, coef_stride);
     for (int j = 0; j < kLaunchMaxK; ++j) d.in[j] = j < k ? static_cast<const uint8_t *>(in[j]) : nullptr;
-    for (int r = 0; r < kLaunchMaxM; ++r) d.out[r] = r < rows ? static_cast<uint8_t *>(out[p.order[r]]) : nullptr;
+    for (int r = 0; r < kLaunchMaxM; ++r) d.out[r] = r < rows ? static_cast<uint8_t *>(out[order[r]]) : nullptr;
     d.nvec = bytes / 16;
     d.tail = static_cast<uint32_t>(bytes % 16);
-    uint64_t tiles;
-    interleave_for(d.nvec, sane_unroll(shape.unroll, rows), shape.interleave_shift, d.nx_shift, tiles);
+    d.nx_shift = batch_interleave_shift(rows, bytes, shape);
 }
 
 hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_stride, const void *descs_dev,
@@ -748,26 +761,42 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
 hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
                               const void *const *plane_base_dev, int n_planes,
                               size_t page_bytes, int64_t pages_per_plane,
-                              const int32_t *table_dev, int pages_per_shard,
+                              const int32_t *table_dev, int table_stride, int n_slots,
                               const PagedStream *in, const PagedStream *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream)
 {
     if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
     if (n_planes < 1 || n_planes > 65535 || page_bytes == 0 || page_bytes % 16 != 0) return hipErrorInvalidValue;
-    if (pages_per_shard < 1 || pages_per_plane < 1) return hipErrorInvalidValue;
+    if (n_slots < 1 || pages_per_plane < 1 || table_stride < n_slots) return hipErrorInvalidValue;
     const uint64_t vpp = page_bytes / 16;
-    const uint64_t vecs = vpp * static_cast<uint64_t>(pages_per_shard);
+    const uint64_t vecs = vpp * static_cast<uint64_t>(n_slots);
     if (vpp >= (1ull << 32) || vecs >= (1ull << 32)) return hipErrorInvalidValue;
+    // vectors from plane to plane of a dense stream: its own stride, or densely packed
+    auto dense_stride = [&](const PagedStream &s, uint32_t &stride) {
+        if (s.plane_stride_bytes == 0) {
+            stride = static_cast<uint32_t>(vecs);
+            return true;
+        }
+        if (s.plane_stride_bytes % 16 != 0 || s.plane_stride_bytes / 16 < vecs || s.plane_stride_bytes / 16 >= (1ull << 32))
+            return false;
+        stride = static_cast<uint32_t>(s.plane_stride_bytes / 16);
+        return true;
+    };
     PagedArgs a;
     const RowPlan p = plan_rows(rows, k, coef, coef_stride);
     fill_tables(a, p, rows, k, coef, coef_stride);
     for (int j = 0; j < kLaunchMaxK; ++j) {
         a.in_row[j] = j < k ? in[j].table_row : -1;
         a.in_ptr[j] = j < k ? static_cast<const uint8_t *>(in[j].dense) : nullptr;
+        a.in_stride[j] = 0;
+        if (j < k && in[j].table_row < 0 && !dense_stride(in[j], a.in_stride[j])) return hipErrorInvalidValue;
     }
     for (int r = 0; r < kLaunchMaxM; ++r) {
         a.out_row[r] = r < rows ? out[p.order[r]].table_row : -1;
         a.out[r] = r < rows ? static_cast<uint8_t *>(const_cast<void *>(out[p.order[r]].dense)) : nullptr;
+        a.out_stride[r] = 0;
+        if (r < rows && out[p.order[r]].table_row < 0 && !dense_stride(out[p.order[r]], a.out_stride[r]))
+            return hipErrorInvalidValue;
     }
     bool plain = true;  // the paged-encode shape: consecutive table rows in, dense buffers out
     for (int j = 0; j < k; ++j) plain = plain && in[j].table_row >= 0 && in[j].table_row == in[0].table_row + j;
@@ -784,7 +813,7 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
         while ((1ull << sft) < vpp) ++sft;
         a.vpp_shift = sft;
     }
-    a.pps = static_cast<uint32_t>(pages_per_shard);
+    a.table_stride = static_cast<uint32_t>(table_stride);
     a.k = k;
     a.accumulate = accumulate ? 1 : 0;
     const int unroll = sane_unroll(shape.unroll, rows, 1);

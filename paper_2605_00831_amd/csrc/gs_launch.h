@@ -34,13 +34,17 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
 struct PagedStream {
     int table_row;
     const void *dense;
+    size_t plane_stride_bytes = 0;  // dense only: bytes from one plane's part to the next (0 = packed)
 };
 
-// One launch of the paged variant: k input streams, `rows` output streams.
+// One launch of the paged variant: k input streams, `rows` output streams,
+// over n_slots page slots per plane.  table_dev points at the first slot's
+// entry of table row 0; rows are table_stride entries apart (>= n_slots), so
+// a launch can cover a window of the slots of a larger table.
 hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
                               const void *const *plane_base_dev, int n_planes,
                               size_t page_bytes, int64_t pages_per_plane,
-                              const int32_t *table_dev, int pages_per_shard,
+                              const int32_t *table_dev, int table_stride, int n_slots,
                               const PagedStream *in, const PagedStream *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream);
 
@@ -49,8 +53,13 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
 // buffer of n * batch_desc_bytes() bytes, copied to the device by the caller,
 // and passed as descs_dev.  max_bytes is the largest chunk's stream length.
 size_t batch_desc_bytes();
-void write_batch_desc(void *slot, int idx, int rows, int k, const uint8_t *coef, int coef_stride,
-                      const void *const *in, void *const *out, size_t bytes, const LaunchShape &shape);
+// order[kLaunchMaxM]: which matrix row each output position of the launch takes
+// (an all-ones row moves to position 0); the same for every chunk of a call
+void batch_row_order(int rows, int k, const uint8_t *coef, int coef_stride, int *order);
+// log2 of the piece interleave modulus the kernel uses for a stream of `bytes`
+uint32_t batch_interleave_shift(int rows, size_t bytes, const LaunchShape &shape);
+void write_batch_desc(void *slot, int idx, int rows, int k, const int *order, const void *const *in,
+                      void *const *out, size_t bytes, const LaunchShape &shape);
 hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_stride, const void *descs_dev,
                               int n_chunks, size_t max_bytes, const LaunchShape &shape, hipStream_t stream);
 

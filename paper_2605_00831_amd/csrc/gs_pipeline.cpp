@@ -125,49 +125,142 @@ catch (...) {
     return caught();
 }
 
+// Copy `rows` pieces of `width` bytes, `spitch` / `dpitch` bytes apart: one
+// plain copy when the pieces are back to back on both sides, else one strided
+// copy (the parity of a window of page slots inside the dense parity layout).
+static hipError_t copy_rows(void *dst, size_t dpitch, const void *src, size_t spitch, size_t width, size_t rows,
+                            hipMemcpyKind kind, hipStream_t stream)
+{
+    if (rows == 1 || (dpitch == width && spitch == width))
+        return hipMemcpyAsync(dst, src, width * rows, kind, stream);
+    return hipMemcpy2DAsync(dst, dpitch, src, spitch, width, rows, kind, stream);
+}
+
+// What differs between the contiguous and the paged pipelines: how chunk c is
+// encoded into / rebuilt from a staging slot, and how a parity row of chunk c
+// moves between staging and pinned host memory.
+struct ChunkOps {
+    size_t n_chunks;
+    // kernel(s) of chunk c on stream cs, parity rows in / out of staging slot `slot`
+    virtual int compute(size_t c, int slot, hipStream_t cs) = 0;
+    // copy of parity row i of chunk c between the slot and host memory
+    virtual hipError_t copy(size_t c, int slot, int row, hipStream_t copy_stream) = 0;
+    virtual ~ChunkOps() {}
+};
+
+// Checkpoint: per chunk, compute on the compute stream into a staging slot,
+// then copy the slot's m rows to host memory on the copy stream.  Whatever
+// happens, `done` is recorded after the last operation that was enqueued, so
+// gs_pipe_sync() covers it.
+static int run_checkpoint(gs_pipe *p, ChunkOps &ops, hipStream_t cs)
+{
+    const int m = p->code->m;
+    p->timed_chunks = 0;
+    int rc = GS_OK;
+    auto step = [&](hipError_t e) {
+        if (rc == GS_OK && e != hipSuccess) rc = hip_status(e);
+        return rc == GS_OK;
+    };
+    if (p->timing && step(grow_timing(p, ops.n_chunks))) step(hipEventRecord(p->t_origin, cs));
+    size_t c = 0;
+    for (; c < ops.n_chunks && rc == GS_OK; ++c) {
+        const int slot = static_cast<int>(c % p->depth);
+        if (p->used[slot] && !step(hipStreamWaitEvent(cs, p->drained[slot], 0))) break;
+        if (p->timing && !step(hipEventRecord(p->t_kernel_begin[c], cs))) break;
+        rc = ops.compute(c, slot, cs);
+        if (rc != GS_OK) break;
+        if (p->timing && !step(hipEventRecord(p->t_kernel_end[c], cs))) break;
+        if (!step(hipEventRecord(p->filled[slot], cs))) break;
+        if (!step(hipStreamWaitEvent(p->copy_stream, p->filled[slot], 0))) break;
+        for (int i = 0; i < m && rc == GS_OK; ++i) step(ops.copy(c, slot, i, p->copy_stream));
+        if (rc != GS_OK) break;
+        if (p->timing && !step(hipEventRecord(p->t_copy_end[c], p->copy_stream))) break;
+        if (!step(hipEventRecord(p->drained[slot], p->copy_stream))) break;
+        p->used[slot] = 1;
+    }
+    if (rc == GS_OK && p->timing) p->timed_chunks = ops.n_chunks;
+    // after a failure the copy stream may not have been told to wait for the last kernel: order
+    // `done` after both streams
+    if (rc != GS_OK && hipEventRecord(p->done, cs) == hipSuccess) (void)hipStreamWaitEvent(p->copy_stream, p->done, 0);
+    if (hipEventRecord(p->done, p->copy_stream) == hipSuccess) p->any = true;
+    return rc;
+}
+
+// Restore: per chunk, bring the parity rows in `rows_in` from host memory into a
+// staging slot on the copy stream, then compute on the compute stream.
+static int run_restore(gs_pipe *p, ChunkOps &ops, const std::vector<int> &rows_in, hipStream_t cs)
+{
+    p->timed_chunks = 0;
+    int rc = GS_OK;
+    auto step = [&](hipError_t e) {
+        if (rc == GS_OK && e != hipSuccess) rc = hip_status(e);
+        return rc == GS_OK;
+    };
+    if (p->timing && step(grow_timing(p, ops.n_chunks))) step(hipEventRecord(p->t_origin, cs));
+    for (size_t c = 0; c < ops.n_chunks && rc == GS_OK; ++c) {
+        const int slot = static_cast<int>(c % p->depth);
+        if (p->used[slot] && !step(hipStreamWaitEvent(p->copy_stream, p->drained[slot], 0))) break;
+        for (size_t x = 0; x < rows_in.size() && rc == GS_OK; ++x) step(ops.copy(c, slot, rows_in[x], p->copy_stream));
+        if (rc != GS_OK) break;
+        if (p->timing && !step(hipEventRecord(p->t_copy_end[c], p->copy_stream))) break;
+        if (!step(hipEventRecord(p->filled[slot], p->copy_stream))) break;
+        if (!step(hipStreamWaitEvent(cs, p->filled[slot], 0))) break;
+        if (p->timing && !step(hipEventRecord(p->t_kernel_begin[c], cs))) break;
+        rc = ops.compute(c, slot, cs);
+        if (rc != GS_OK) break;
+        if (p->timing && !step(hipEventRecord(p->t_kernel_end[c], cs))) break;
+        if (!step(hipEventRecord(p->drained[slot], cs))) break;
+        p->used[slot] = 1;
+    }
+    if (rc == GS_OK && p->timing) p->timed_chunks = ops.n_chunks;
+    // copies that were enqueued but whose kernel never followed must still be waited for
+    if (rc != GS_OK && hipEventRecord(p->done, p->copy_stream) == hipSuccess) (void)hipStreamWaitEvent(cs, p->done, 0);
+    if (hipEventRecord(p->done, cs) == hipSuccess) p->any = true;
+    return rc;
+}
+
+static bool misaligned(const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15u) != 0; }
+
 int gs_checkpoint(gs_pipe *p, const void *const *data, size_t shard_bytes, void *const *host_parity,
                   void *compute_stream)
 try {
     if (p == nullptr || data == nullptr || host_parity == nullptr) return GS_EINVAL;
     const int k = p->code->k, m = p->code->m;
     for (int j = 0; j < k; ++j)
-        if (data[j] == nullptr || (reinterpret_cast<uintptr_t>(data[j]) & 15u)) return GS_EINVAL;
+        if (data[j] == nullptr || misaligned(data[j])) return GS_EINVAL;
     for (int i = 0; i < m; ++i)
         if (host_parity[i] == nullptr) return GS_EINVAL;
     if (shard_bytes == 0) return GS_OK;
-    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-    std::vector<const void *> in(k);
-    std::vector<void *> out(m);
-    const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
-    p->timed_chunks = 0;
-    if (p->timing) {
-        GS_TRY(grow_timing(p, nchunks));
-        GS_TRY(hipEventRecord(p->t_origin, cs));
-    }
-    for (size_t c = 0; c < nchunks; ++c) {
-        const int slot = static_cast<int>(c % p->depth);
-        const size_t off = c * p->chunk_bytes;
-        const size_t len = std::min(p->chunk_bytes, shard_bytes - off);
-        if (p->used[slot]) GS_TRY(hipStreamWaitEvent(cs, p->drained[slot], 0));
-        for (int j = 0; j < k; ++j) in[j] = static_cast<const uint8_t *>(data[j]) + off;
-        for (int i = 0; i < m; ++i) out[i] = p->slot_buf(slot, i);
-        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_begin[c], cs));
-        const int rc = gs_encode(p->code, in.data(), out.data(), len, cs);
-        if (rc != GS_OK) return rc;
-        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_end[c], cs));
-        GS_TRY(hipEventRecord(p->filled[slot], cs));
-        GS_TRY(hipStreamWaitEvent(p->copy_stream, p->filled[slot], 0));
-        for (int i = 0; i < m; ++i)
-            GS_TRY(hipMemcpyAsync(static_cast<uint8_t *>(host_parity[i]) + off, p->slot_buf(slot, i), len,
-                                  hipMemcpyDeviceToHost, p->copy_stream));
-        if (p->timing) GS_TRY(hipEventRecord(p->t_copy_end[c], p->copy_stream));
-        GS_TRY(hipEventRecord(p->drained[slot], p->copy_stream));
-        p->used[slot] = 1;
-    }
-    if (p->timing) p->timed_chunks = nchunks;
-    GS_TRY(hipEventRecord(p->done, p->copy_stream));
-    p->any = true;
-    return GS_OK;
+    // RDP shards hold whole stripes; refused here, before anything is enqueued
+    if (p->code->is_rdp() && shard_bytes % (p->code->rdp_cell * (p->code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    struct Ops : ChunkOps {
+        gs_pipe *p;
+        const void *const *data;
+        void *const *host;
+        size_t S;
+        std::vector<const void *> in;
+        std::vector<void *> out;
+        size_t len(size_t c) const { return std::min(p->chunk_bytes, S - c * p->chunk_bytes); }
+        int compute(size_t c, int slot, hipStream_t cs) override
+        {
+            for (size_t j = 0; j < in.size(); ++j) in[j] = static_cast<const uint8_t *>(data[j]) + c * p->chunk_bytes;
+            for (size_t i = 0; i < out.size(); ++i) out[i] = p->slot_buf(slot, static_cast<int>(i));
+            return gs_encode(p->code, in.data(), out.data(), len(c), cs);
+        }
+        hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
+        {
+            return hipMemcpyAsync(static_cast<uint8_t *>(host[i]) + c * p->chunk_bytes, p->slot_buf(slot, i), len(c),
+                                  hipMemcpyDeviceToHost, s);
+        }
+    } ops;
+    ops.p = p;
+    ops.data = data;
+    ops.host = host_parity;
+    ops.S = shard_bytes;
+    ops.in.resize(k);
+    ops.out.resize(m);
+    ops.n_chunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    return run_checkpoint(p, ops, static_cast<hipStream_t>(compute_stream));
 }
 catch (...) {
     return caught();
@@ -185,55 +278,215 @@ try {
     if (rc0 != GS_OK) return rc0;
     if (n_erased == 0 || shard_bytes == 0) return GS_OK;
     if (p->code->is_rdp() && shard_bytes % (p->code->rdp_cell * (p->code->rdp_encode.p - 1)) != 0) return GS_EINVAL;
+    std::vector<int> rows_in;
+    std::vector<const void *> in_dev;
+    std::vector<void *> out_dev;
     for (int s : read) {
         if (s < k) {
-            if (shards[s] == nullptr || (reinterpret_cast<uintptr_t>(shards[s]) & 15u)) return GS_EINVAL;
-        } else if (host_parity[s - k] == nullptr) {
-            return GS_EINVAL;
+            if (shards[s] == nullptr || misaligned(shards[s])) return GS_EINVAL;
+            in_dev.push_back(shards[s]);
+        } else {
+            if (host_parity[s - k] == nullptr) return GS_EINVAL;
+            rows_in.push_back(s - k);
         }
     }
-    for (int x = 0; x < n_erased; ++x)
-        if (shards[erased[x]] == nullptr || (reinterpret_cast<uintptr_t>(shards[erased[x]]) & 15u)) return GS_EINVAL;
-    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-    std::vector<void *> view(k + m);  // the stripe as the rebuild of one chunk sees it
-    const size_t nchunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
-    p->timed_chunks = 0;
-    if (p->timing) {
-        GS_TRY(grow_timing(p, nchunks));
-        GS_TRY(hipEventRecord(p->t_origin, cs));
+    for (int x = 0; x < n_erased; ++x) {
+        if (shards[erased[x]] == nullptr || misaligned(shards[erased[x]])) return GS_EINVAL;
+        out_dev.push_back(shards[erased[x]]);
     }
-    for (size_t c = 0; c < nchunks; ++c) {
-        const int slot = static_cast<int>(c % p->depth);
-        const size_t off = c * p->chunk_bytes;
-        const size_t len = std::min(p->chunk_bytes, shard_bytes - off);
-        if (p->used[slot]) GS_TRY(hipStreamWaitEvent(p->copy_stream, p->drained[slot], 0));
-        for (int r = 0; r < k + m; ++r) view[r] = nullptr;
-        for (int s : read) {
-            if (s < k) {
-                view[s] = static_cast<uint8_t *>(shards[s]) + off;
-            } else {
-                uint8_t *stage = p->slot_buf(slot, s - k);
-                GS_TRY(hipMemcpyAsync(stage, static_cast<const uint8_t *>(host_parity[s - k]) + off, len,
-                                      hipMemcpyHostToDevice, p->copy_stream));
-                view[s] = stage;
-            }
+    if (outputs_overlap(in_dev.data(), static_cast<int>(in_dev.size()), out_dev.data(), n_erased, shard_bytes))
+        return GS_EINVAL;
+    struct Ops : ChunkOps {
+        gs_pipe *p;
+        void *const *shards, *const *host;
+        const int *erased;
+        int n_erased;
+        size_t S;
+        const std::vector<int> *read;
+        const std::vector<uint8_t> *R;
+        std::vector<void *> view;  // the stripe as the rebuild of one chunk sees it
+        size_t len(size_t c) const { return std::min(p->chunk_bytes, S - c * p->chunk_bytes); }
+        int compute(size_t c, int slot, hipStream_t cs) override
+        {
+            const int k = p->code->k;
+            const size_t off = c * p->chunk_bytes;
+            std::fill(view.begin(), view.end(), nullptr);
+            for (int s : *read) view[s] = s < k ? static_cast<uint8_t *>(shards[s]) + off : p->slot_buf(slot, s - k);
+            for (int x = 0; x < n_erased; ++x) view[erased[x]] = static_cast<uint8_t *>(shards[erased[x]]) + off;
+            return p->code->is_rdp() ? gs_reconstruct(p->code, view.data(), erased, n_erased, len(c), cs)
+                                     : apply_rebuild(p->code, *R, *read, view.data(), erased, n_erased, len(c), cs);
         }
-        for (int x = 0; x < n_erased; ++x) view[erased[x]] = static_cast<uint8_t *>(shards[erased[x]]) + off;
-        if (p->timing) GS_TRY(hipEventRecord(p->t_copy_end[c], p->copy_stream));
-        GS_TRY(hipEventRecord(p->filled[slot], p->copy_stream));
-        GS_TRY(hipStreamWaitEvent(cs, p->filled[slot], 0));
-        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_begin[c], cs));
-        const int rc = p->code->is_rdp() ? gs_reconstruct(p->code, view.data(), erased, n_erased, len, cs)
-                                         : apply_rebuild(p->code, R, read, view.data(), erased, n_erased, len, cs);
-        if (rc != GS_OK) return rc;
-        if (p->timing) GS_TRY(hipEventRecord(p->t_kernel_end[c], cs));
-        GS_TRY(hipEventRecord(p->drained[slot], cs));
-        p->used[slot] = 1;
+        hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
+        {
+            return hipMemcpyAsync(p->slot_buf(slot, i), static_cast<const uint8_t *>(host[i]) + c * p->chunk_bytes, len(c),
+                                  hipMemcpyHostToDevice, s);
+        }
+    } ops;
+    ops.p = p;
+    ops.shards = shards;
+    ops.host = host_parity;
+    ops.erased = erased;
+    ops.n_erased = n_erased;
+    ops.S = shard_bytes;
+    ops.read = &read;
+    ops.R = &R;
+    ops.view.assign(k + m, nullptr);
+    ops.n_chunks = (shard_bytes + p->chunk_bytes - 1) / p->chunk_bytes;
+    return run_restore(p, ops, rows_in, static_cast<hipStream_t>(compute_stream));
+}
+catch (...) {
+    return caught();
+}
+
+// ---- the same two pipelines over a paged KV pool ------------------------------
+// A chunk is a window of `slots_per_chunk` page slots of every plane; its parity
+// is produced into (or consumed from) a staging slot laid out [plane][slot][page]
+// and lives in host memory inside the dense layout of gs_encode_paged,
+// [plane][pages_per_shard][page], which a strided copy reaches.
+
+struct PagedChunks {
+    const void *const *plane_base;
+    int n_planes;
+    size_t page_bytes;
+    int64_t pages_per_plane;
+    const int32_t *table;
+    int pps;               // pages per shard (table row length)
+    int spc;               // page slots per chunk
+    int slots(size_t c) const { return std::min(spc, pps - static_cast<int>(c) * spc); }
+    gs::PagedView view(size_t c) const
+    {
+        return gs::PagedView{plane_base, n_planes, page_bytes, pages_per_plane, table + c * static_cast<size_t>(spc), pps, slots(c)};
     }
-    if (p->timing) p->timed_chunks = nchunks;
-    GS_TRY(hipEventRecord(p->done, cs));
-    p->any = true;
+};
+
+// chunk geometry of a paged pipeline call; GS_OK with spc == 0 means nothing to do
+static int paged_chunks(const gs_pipe *p, const void *const *plane_base, int n_planes, size_t page_bytes,
+                        int64_t pages_per_plane, const int32_t *table, int pages_per_shard, PagedChunks &g)
+{
+    if (p->code->is_rdp()) return GS_EINVAL;
+    bool empty;
+    const int rc = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
+    g = PagedChunks{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, 0};
+    if (rc != GS_OK || empty) return rc;
+    // a staging buffer holds whole page slots of every plane
+    const size_t slot_row = static_cast<size_t>(n_planes) * page_bytes;
+    if (p->chunk_bytes < slot_row) return GS_EINVAL;
+    g.spc = static_cast<int>(std::min<size_t>(p->chunk_bytes / slot_row, static_cast<size_t>(pages_per_shard)));
     return GS_OK;
+}
+
+int gs_checkpoint_paged(gs_pipe *p, const void *const *plane_base, int n_planes, size_t page_bytes,
+                        int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                        void *const *host_parity, void *compute_stream)
+try {
+    if (p == nullptr || host_parity == nullptr) return GS_EINVAL;
+    PagedChunks g;
+    const int rc = paged_chunks(p, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, g);
+    if (rc != GS_OK) return rc;
+    for (int i = 0; i < p->code->m; ++i)
+        if (host_parity[i] == nullptr) return GS_EINVAL;
+    if (g.spc == 0) return GS_OK;
+    struct Ops : ChunkOps {
+        gs_pipe *p;
+        PagedChunks g;
+        void *const *host;
+        std::vector<gs::PagedStream> in, out;
+        int compute(size_t c, int slot, hipStream_t cs) override
+        {
+            for (size_t i = 0; i < out.size(); ++i) out[i] = gs::PagedStream{-1, p->slot_buf(slot, static_cast<int>(i))};
+            return apply_matrix_paged(p->code->m, p->code->k, p->code->P.data(), g.view(c), in.data(), out.data(), cs);
+        }
+        hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
+        {
+            const size_t width = static_cast<size_t>(g.slots(c)) * g.page_bytes;
+            return copy_rows(static_cast<uint8_t *>(host[i]) + c * static_cast<size_t>(g.spc) * g.page_bytes,
+                             static_cast<size_t>(g.pps) * g.page_bytes, p->slot_buf(slot, i), width, width,
+                             static_cast<size_t>(g.n_planes), hipMemcpyDeviceToHost, s);
+        }
+    } ops;
+    ops.p = p;
+    ops.g = g;
+    ops.host = host_parity;
+    ops.in.resize(p->code->k);
+    ops.out.resize(p->code->m);
+    for (int j = 0; j < p->code->k; ++j) ops.in[j] = gs::PagedStream{j, nullptr};
+    ops.n_chunks = (static_cast<size_t>(pages_per_shard) + g.spc - 1) / g.spc;
+    return run_checkpoint(p, ops, static_cast<hipStream_t>(compute_stream));
+}
+catch (...) {
+    return caught();
+}
+
+int gs_restore_paged(gs_pipe *p, const void *const *plane_base, int n_planes, size_t page_bytes,
+                     int64_t pages_per_plane, const int32_t *table, int pages_per_shard,
+                     void *const *host_parity, void *const *parity_out, const int *erased, int n_erased,
+                     void *compute_stream)
+try {
+    if (p == nullptr || host_parity == nullptr) return GS_EINVAL;
+    PagedChunks g;
+    const int rc = paged_chunks(p, plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, g);
+    if (rc != GS_OK) return rc;
+    const int k = p->code->k, m = p->code->m;
+    std::vector<uint8_t> R;
+    std::vector<int> surv;
+    const int rc1 = decode_matrix(p->code, erased, n_erased, R, surv);
+    if (rc1 != GS_OK) return rc1;
+    if (n_erased == 0 || g.spc == 0) return GS_OK;
+    std::vector<int> rows_in;
+    for (int s : surv)
+        if (s >= k) {
+            if (host_parity[s - k] == nullptr) return GS_EINVAL;
+            rows_in.push_back(s - k);
+        }
+    for (int x = 0; x < n_erased; ++x)
+        if (erased[x] >= k && (parity_out == nullptr || parity_out[erased[x] - k] == nullptr || misaligned(parity_out[erased[x] - k])))
+            return GS_EINVAL;
+    struct Ops : ChunkOps {
+        gs_pipe *p;
+        PagedChunks g;
+        void *const *host, *const *parity_out;
+        const int *erased;
+        int n_erased;
+        const std::vector<uint8_t> *R;
+        const std::vector<int> *surv;
+        std::vector<gs::PagedStream> pin, pout;
+        int compute(size_t c, int slot, hipStream_t cs) override
+        {
+            const int k = p->code->k;
+            // surviving parity comes from the staging slot; a lost parity shard goes straight into the
+            // caller's dense device buffer, at this chunk's slots
+            for (int i = 0; i < p->code->m; ++i) {
+                pin[i] = gs::PagedStream{-1, p->slot_buf(slot, i)};
+                pout[i] = gs::PagedStream{-1, nullptr};
+            }
+            for (int x = 0; x < n_erased; ++x)
+                if (erased[x] >= k)
+                    pout[erased[x] - k] = gs::PagedStream{-1, static_cast<uint8_t *>(parity_out[erased[x] - k]) +
+                                                                  c * static_cast<size_t>(g.spc) * g.page_bytes,
+                                                          static_cast<size_t>(g.pps) * g.page_bytes};
+            return rebuild_paged(p->code, *R, *surv, g.view(c), pin.data(), pout.data(), erased, n_erased, cs);
+        }
+        hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
+        {
+            const size_t width = static_cast<size_t>(g.slots(c)) * g.page_bytes;
+            return copy_rows(p->slot_buf(slot, i), width,
+                             static_cast<const uint8_t *>(host[i]) + c * static_cast<size_t>(g.spc) * g.page_bytes,
+                             static_cast<size_t>(g.pps) * g.page_bytes, width, static_cast<size_t>(g.n_planes),
+                             hipMemcpyHostToDevice, s);
+        }
+    } ops;
+    ops.p = p;
+    ops.g = g;
+    ops.host = host_parity;
+    ops.parity_out = parity_out;
+    ops.erased = erased;
+    ops.n_erased = n_erased;
+    ops.R = &R;
+    ops.surv = &surv;
+    ops.pin.resize(m);
+    ops.pout.resize(m);
+    ops.n_chunks = (static_cast<size_t>(pages_per_shard) + g.spc - 1) / g.spc;
+    return run_restore(p, ops, rows_in, static_cast<hipStream_t>(compute_stream));
 }
 catch (...) {
     return caught();

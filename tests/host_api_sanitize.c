@@ -43,7 +43,8 @@ static int encode_and_rebuild(gs_code *code, int k, int m)
 
 int main(void)
 {
-    for (int i = 0; i < MAXN; i++) fake[i] = (void *)(uintptr_t)(0x100000u + 0x1000u * (unsigned)i);
+    /* far enough apart that no two of them overlap at the largest size tried below */
+    for (int i = 0; i < MAXN; i++) fake[i] = (void *)(uintptr_t)(((uint64_t)1 << 42) + ((uint64_t)(unsigned)i << 41));
 
     /* every code kind over a range of widths, all launch shapes */
     static const int shapes[][4] = {{0, 0, -1, -1}, {1, 1, 1, 5}, {2, 3, 0, 0}, {4, 1, 1, 10}, {1, 7, 1, 3}};
@@ -146,6 +147,44 @@ int main(void)
         int r = -1;
         double t = -1;
         EXPECT(gs_recompute_units(n, &costs, &r, &t) == GS_OK && r >= 0 && r <= n && t >= 0);
+    }
+    /* an output that shares bytes with an input or with another output of the same call is refused
+     * before anything is enqueued; buffers that merely touch end to end are fine */
+    {
+        gs_code *code = NULL;
+        EXPECT(gs_make_code(4, 2, GS_CAUCHY, &code) == GS_OK);
+        void *p[6];
+        const size_t S = 4096;
+        for (int i = 0; i < 6; i++) p[i] = (void *)(uintptr_t)(((uint64_t)1 << 42) + S * (unsigned)i);
+        EXPECT(gs_encode(code, (const void *const *)p, p + 4, S, NULL) == GS_EHIP);         /* adjacent: accepted */
+        EXPECT(gs_encode(code, (const void *const *)p, p + 4, S + 16, NULL) == GS_EINVAL);  /* every buffer runs into the next */
+        void *q[6];
+        memcpy(q, p, sizeof q);
+        q[4] = p[2];                                                                        /* parity 0 on top of data 2 */
+        EXPECT(gs_encode(code, (const void *const *)q, q + 4, S, NULL) == GS_EINVAL);
+        memcpy(q, p, sizeof q);
+        q[5] = (char *)p[4] + S - 16;                                                       /* the two parities overlap */
+        EXPECT(gs_encode(code, (const void *const *)q, q + 4, S, NULL) == GS_EINVAL);
+        const int er[2] = {1, 4};
+        EXPECT(gs_reconstruct(code, p, er, 2, S, NULL) == GS_EHIP);
+        memcpy(q, p, sizeof q);
+        q[1] = p[3];                                                                        /* erased shard 1 = survivor 3 */
+        EXPECT(gs_reconstruct(code, q, er, 2, S, NULL) == GS_EINVAL);
+        memcpy(q, p, sizeof q);
+        q[5] = p[1];                          /* with only shard 1 lost, shard 5 is neither read nor written: it may point anywhere */
+        EXPECT(gs_reconstruct(code, q, er, 1, S, NULL) == GS_EHIP);
+        EXPECT(gs_reconstruct(code, q, er, 2, S, NULL) == GS_EINVAL);   /* with shard 4 lost as well it is read */
+        gs_free_code(code);
+        gs_code *rdp2 = NULL;
+        EXPECT(gs_make_rdp_code(4, 64, &rdp2) == GS_OK);   /* p = 5: stripes of 256 bytes */
+        for (int i = 0; i < 6; i++) p[i] = (void *)(uintptr_t)(((uint64_t)1 << 42) + 1024u * (unsigned)i);
+        EXPECT(gs_encode(rdp2, (const void *const *)p, p + 4, 1024, NULL) == GS_EHIP);
+        EXPECT(gs_encode(rdp2, (const void *const *)p, p + 4, 1280, NULL) == GS_EINVAL);
+        const int er2[2] = {0, 5};
+        memcpy(q, p, sizeof q);
+        q[0] = p[2];
+        EXPECT(gs_reconstruct(rdp2, q, er2, 2, 1024, NULL) == GS_EINVAL);
+        gs_free_code(rdp2);
     }
     EXPECT(gs_last_hip_error() != 0);
     EXPECT(strlen(gs_strerror(GS_EHIP)) > 0 && strlen(gs_strerror(12345)) > 0);

@@ -14,6 +14,10 @@
 //               encode of chunk c + depth     after  copy of chunk c (slot reuse)
 //   restore     reconstruct of chunk c        after  H2D of chunk c's parity
 //               H2D of chunk c + depth        after  reconstruct of chunk c
+//   paged       the same four relations for gs_checkpoint_paged / gs_restore_paged,
+//               whose chunks are windows of page slots moved by strided copies
+//   failure     a refused call enqueues nothing; after a runtime failure part of
+//               the way, gs_pipe_sync still waits for everything that was enqueued
 //   pool        every chunk's launch after what was enqueued on the caller's
 //               stream before the call; what the caller enqueues afterwards
 //               after every chunk
@@ -57,6 +61,7 @@ bool stream_live[kMaxStreams];
 std::vector<Op> ops;
 std::vector<Event *> events;
 int fail_malloc_after = -1;               // >= 0: that many device allocations succeed, then they fail
+int fail_copy_after = -1;                 // >= 0: that many async copies succeed, then they fail
 
 int sid(hipStream_t s) { return static_cast<int>(reinterpret_cast<uintptr_t>(s)); }
 
@@ -156,12 +161,27 @@ hipError_t hipEventElapsedTime(float *ms, hipEvent_t, hipEvent_t) { *ms = 0.0f; 
 
 hipError_t hipMemcpyAsync(void *dst, const void *src, size_t n, hipMemcpyKind kind, hipStream_t s)
 {
+    if (fail_copy_after == 0) return hipErrorUnknown;
+    if (fail_copy_after > 0) --fail_copy_after;
     Op &op = enqueue(COPY, s);
     op.dst = dst;
     op.src = src;
     op.bytes = n;
     op.dir = kind;
     std::memcpy(dst, src, n);
+    return hipSuccess;
+}
+
+hipError_t hipMemcpy2DAsync(void *dst, size_t dpitch, const void *src, size_t spitch, size_t width, size_t height,
+                            hipMemcpyKind kind, hipStream_t s)
+{
+    Op &op = enqueue(COPY, s);
+    op.dst = dst;
+    op.src = src;
+    op.bytes = width * height;
+    op.dir = kind;
+    for (size_t r = 0; r < height; ++r)
+        std::memcpy(static_cast<uint8_t *>(dst) + r * dpitch, static_cast<const uint8_t *>(src) + r * spitch, width);
     return hipSuccess;
 }
 
@@ -327,7 +347,7 @@ static int check_pool(int n_streams, int n_chunks)
     hipStream_t cs;
     EXPECT(hipStreamCreateWithFlags(&cs, 0) == hipSuccess);
     std::vector<void *> ptrs(static_cast<size_t>(n_chunks) * (k + m));
-    for (size_t i = 0; i < ptrs.size(); ++i) ptrs[i] = reinterpret_cast<void *>(0x100000 + 0x1000 * i);
+    for (size_t i = 0; i < ptrs.size(); ++i) ptrs[i] = reinterpret_cast<void *>(0x100000000ull + 0x200000ull * i);
     std::vector<const void *> data;
     std::vector<void *> parity;
     for (int c = 0; c < n_chunks; ++c) {
@@ -377,9 +397,9 @@ static int check_ring()
     for (hipStream_t &s : st) EXPECT(hipStreamCreateWithFlags(&s, 0) == hipSuccess);
     std::vector<const void *> data(static_cast<size_t>(n_chunks) * k);
     std::vector<void *> parity(static_cast<size_t>(n_chunks) * m), shards(static_cast<size_t>(n_chunks) * (k + m));
-    for (size_t i = 0; i < data.size(); ++i) data[i] = reinterpret_cast<void *>(0x100000 + 0x1000 * i);
-    for (size_t i = 0; i < parity.size(); ++i) parity[i] = reinterpret_cast<void *>(0x900000 + 0x1000 * i);
-    for (size_t i = 0; i < shards.size(); ++i) shards[i] = reinterpret_cast<void *>(0x100000 + 0x1000 * i);
+    for (size_t i = 0; i < data.size(); ++i) data[i] = reinterpret_cast<void *>(0x100000000ull + 0x200000ull * i);
+    for (size_t i = 0; i < parity.size(); ++i) parity[i] = reinterpret_cast<void *>(0x900000000ull + 0x200000ull * i);
+    for (size_t i = 0; i < shards.size(); ++i) shards[i] = reinterpret_cast<void *>(0x100000000ull + 0x200000ull * i);
     const std::vector<size_t> bytes = {4096, 0, 100, 1 << 20, 17};
     reset_record();
     const int calls = 11;
@@ -474,6 +494,148 @@ static int check_step_graph()
     return 0;
 }
 
+// Checkpoint / restore over a paged pool: chunks are windows of `spc` page slots of every plane;
+// a chunk's parity moves as one strided copy per parity shard, inside the dense layout
+// [plane][pages_per_shard][page].
+static int check_paged_pipelines(int depth)
+{
+    const int k = 4, m = 2, n_planes = 3, pps = 11, spc = 4;
+    const size_t page = 256, row = static_cast<size_t>(pps) * page, S = n_planes * row;
+    const size_t chunk = static_cast<size_t>(n_planes) * page * spc + 32;  // the 32 extra bytes hold no whole slot
+    const size_t n = (pps + spc - 1) / spc;
+    gs_code *code = nullptr;
+    EXPECT(gs_make_code(k, m, GS_CAUCHY, &code) == GS_OK);
+    gs_pipe *pipe = nullptr;
+    EXPECT(gs_pipe_create(code, chunk, depth, &pipe) == GS_OK);
+    hipStream_t cs;
+    EXPECT(hipStreamCreateWithFlags(&cs, 0) == hipSuccess);
+    std::vector<void *> host(m), dev_par(m);
+    for (auto &p : host) p = std::malloc(S);
+    for (auto &p : dev_par) p = std::malloc(S);
+    for (auto &p : host) std::memset(p, 0x22, S);
+    const void *const *planes = reinterpret_cast<const void *const *>(0x100000);
+    const int32_t *table = reinterpret_cast<const int32_t *>(0x200000);
+
+    for (int rep = 0; rep < 2; ++rep) {
+        reset_record();
+        EXPECT(gs_checkpoint_paged(pipe, planes, n_planes, page, 64, table, pps, host.data(), cs) == GS_OK);
+        const std::vector<const Op *> enc = launches_on(sid(cs));
+        EXPECT(enc.size() == n);
+        std::vector<std::vector<const Op *>> copies(n);
+        for (const Op &o : ops)
+            if (o.kind == COPY) {
+                EXPECT(o.dir == hipMemcpyDeviceToHost);
+                bool found = false;
+                for (int i = 0; i < m && !found; ++i) {
+                    const uint8_t *base = static_cast<const uint8_t *>(host[i]);
+                    const uint8_t *d = static_cast<const uint8_t *>(o.dst);
+                    if (d >= base && d < base + S) {
+                        const size_t c = static_cast<size_t>(d - base) / (spc * page);
+                        const size_t slots = std::min<size_t>(spc, pps - c * spc);
+                        EXPECT(static_cast<size_t>(d - base) == c * spc * page && o.bytes == n_planes * slots * page);
+                        copies[c].push_back(&o);
+                        found = true;
+                    }
+                }
+                EXPECT(found);
+            }
+        for (size_t c = 0; c < n; ++c) {
+            EXPECT(copies[c].size() == static_cast<size_t>(m));
+            for (const Op *cp : copies[c]) {
+                EXPECT(before(*enc[c], *cp));
+                if (c + depth < n) EXPECT(before(*cp, *enc[c + depth]));
+                if (c + 1 < n) EXPECT(!before(*cp, *enc[c + 1]));
+            }
+        }
+        EXPECT(gs_pipe_sync(pipe) == GS_OK);
+    }
+    // data shard 1 and parity shard 0 lost: parity 1 comes back from the host, parity 0 is rebuilt
+    // into the caller's dense device buffer
+    const int erased[2] = {1, 4};
+    for (int rep = 0; rep < 2; ++rep) {
+        reset_record();
+        EXPECT(gs_restore_paged(pipe, planes, n_planes, page, 64, table, pps, host.data(), dev_par.data(), erased, 2, cs) == GS_OK);
+        const std::vector<const Op *> rec = launches_on(sid(cs));
+        EXPECT(rec.size() == n);
+        std::vector<const Op *> h2d;
+        for (const Op &o : ops)
+            if (o.kind == COPY) {
+                EXPECT(o.dir == hipMemcpyHostToDevice);
+                const uint8_t *base = static_cast<const uint8_t *>(host[1]);
+                const uint8_t *sp = static_cast<const uint8_t *>(o.src);
+                EXPECT(sp >= base && sp < base + S && static_cast<size_t>(sp - base) == h2d.size() * spc * page);
+                h2d.push_back(&o);
+            }
+        EXPECT(h2d.size() == n);
+        for (size_t c = 0; c < n; ++c) {
+            EXPECT(before(*h2d[c], *rec[c]));
+            if (c + depth < n) EXPECT(before(*rec[c], *h2d[c + depth]));
+            if (c + 1 < n) EXPECT(!before(*rec[c], *h2d[c + 1]));
+        }
+        EXPECT(gs_pipe_sync(pipe) == GS_OK);
+    }
+    // refusals: nothing is enqueued
+    reset_record();
+    EXPECT(gs_restore_paged(pipe, planes, n_planes, page, 64, table, pps, host.data(), nullptr, erased, 2, cs) == GS_EINVAL);
+    const int three[3] = {0, 1, 2};
+    EXPECT(gs_restore_paged(pipe, planes, n_planes, page, 64, table, pps, host.data(), dev_par.data(), three, 3, cs) == GS_ETOOMANY);
+    EXPECT(gs_checkpoint_paged(pipe, planes, n_planes, 8 * page, 64, table, pps, host.data(), cs) == GS_EINVAL);  // no whole slot fits a chunk
+    EXPECT(gs_checkpoint_paged(pipe, planes, n_planes, page + 8, 64, table, pps, host.data(), cs) == GS_EINVAL);
+    EXPECT(gs_checkpoint_paged(pipe, planes, n_planes, page, 64, table, 0, host.data(), cs) == GS_OK);            // empty
+    EXPECT(ops.empty());
+    gs_pipe_destroy(pipe);
+    for (void *p : host) std::free(p);
+    for (void *p : dev_par) std::free(p);
+    EXPECT(hipStreamDestroy(cs) == hipSuccess);
+    gs_free_code(code);
+    return 0;
+}
+
+// A call that is refused enqueues nothing; a runtime failure part of the way leaves a pipe whose
+// gs_pipe_sync waits for everything that did get enqueued.
+static int check_pipeline_failures()
+{
+    gs_code *rdp = nullptr;
+    EXPECT(gs_make_rdp_code(4, 64, &rdp) == GS_OK);  // p = 5: stripes of 256 bytes
+    gs_pipe *pipe = nullptr;
+    EXPECT(gs_pipe_create(rdp, 1024, 2, &pipe) == GS_OK);
+    hipStream_t cs;
+    EXPECT(hipStreamCreateWithFlags(&cs, 0) == hipSuccess);
+    const size_t S = 5 * 1024;
+    std::vector<void *> dev(6), host(2);
+    for (auto &p : dev) p = std::malloc(S);
+    for (auto &p : host) p = std::malloc(S);
+    reset_record();
+    // three whole chunks and a last one that is not a whole number of stripes: refused up front
+    EXPECT(gs_checkpoint(pipe, dev.data(), 3 * 1024 + 128, host.data(), cs) == GS_EINVAL);
+    EXPECT(ops.empty());
+    EXPECT(gs_pipe_done_event(pipe) == nullptr && gs_pipe_sync(pipe) == GS_OK);
+    const int erased[2] = {0, 5};
+    EXPECT(gs_restore(pipe, dev.data(), host.data(), erased, 2, 3 * 1024 + 128, cs) == GS_EINVAL);
+    EXPECT(ops.empty());
+
+    // the fourth copy fails: two chunks are complete, the third has its kernel and one copy
+    for (int which = 0; which < 2; ++which) {
+        reset_record();
+        std::memset(host_vc, 0, sizeof host_vc);
+        fail_copy_after = which == 0 ? 5 : 2;
+        const int rc = which == 0 ? gs_checkpoint(pipe, dev.data(), S, host.data(), cs)
+                                  : gs_restore(pipe, dev.data(), host.data(), erased, 2, S, cs);
+        fail_copy_after = -1;
+        EXPECT(rc == GS_EHIP);
+        EXPECT(!ops.empty());
+        EXPECT(gs_pipe_done_event(pipe) != nullptr);
+        EXPECT(gs_pipe_sync(pipe) == GS_OK);
+        for (const Op &o : ops) EXPECT(host_vc[o.stream] >= o.seq);  // the host has waited for every one of them
+    }
+    gs_pipe_destroy(pipe);
+    for (void *p : dev) std::free(p);
+    for (void *p : host) std::free(p);
+    EXPECT(hipStreamDestroy(cs) == hipSuccess);
+    gs_free_code(rdp);
+    return 0;
+}
+
 int main()
 {
     if (check_pipelines(4, 2, GS_CAUCHY, 4096, 2, 10 * 4096 + 100, {1, 3})) return 1;
@@ -482,6 +644,8 @@ int main()
     if (check_pipelines(40, 6, GS_VANDERMONDE, 512, 2, 5 * 512 + 16, {39, 41})) return 1;  // several launches per chunk
     if (check_pipelines(4, 2, GS_RDP, 1024, 2, 7 * 1024, {0, 5})) return 1;       // p = 5: stripes of 256 bytes
     if (check_pipelines(8, 3, GS_POWER, 4096, 2, 3 * 4096 + 1, {8})) return 1;    // Horner encode, lost parity
+    if (check_paged_pipelines(2) || check_paged_pipelines(3)) return 1;
+    if (check_pipeline_failures()) return 1;
     if (check_pool(4, 11) || check_pool(16, 3) || check_pool(1, 5)) return 1;
     if (check_ring()) return 1;
     if (check_step_graph()) return 1;

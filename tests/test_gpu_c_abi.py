@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 def test_c_program_round_trip():
     exe = os.path.join(HERE, "c_abi_roundtrip")
     if not os.path.exists(exe):
-        pytest.skip("tests/c_abi_roundtrip has not been built (python -m paper_2605_00831_amd.build)")
+        pytest.skip("tests/c_abi_roundtrip has not been built (python -m tests.build_c_check)")
     out = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
     assert out.returncode == 0, out.stdout
     assert "C ABI round trip OK" in out.stdout

@@ -207,3 +207,65 @@ def test_recovery_stress_full_size_20_seeded_patterns(gs):
     for r in pat:
         assert torch.equal(work[r], full[r])
     gs.gs_pipe_destroy(pipe)
+
+
+def test_recovery_stress_full_size_through_the_paged_pipelines(gs):
+    """The recovery-stress stripe (k=8, m=3, shards of 512 MiB) living in a paged pool of 64 planes
+    with 32 KiB pages (16-token blocks): shards 0-3 are uniform random bytes in consecutive pages,
+    shards 4-7 bf16 N(0,1) KV pages behind a seeded permutation.  gs_checkpoint_paged ships the
+    parity to pinned host memory; for 20 seeded erasure triples the lost shards' pages are flushed
+    and gs_restore_paged rebuilds them in place with parity coming back from the host."""
+    c = inputs.CONFIGS["recovery_stress"]
+    k, m, S = c["k"], c["m"], c["shard_bytes"]
+    seed = inputs.config_seed("recovery_stress")
+    n_planes, page = 64, 32768
+    pps = S // (n_planes * page)                    # 256 slots per shard and plane
+    ppp = k * pps                                   # 2048 pages = 64 MiB per plane
+    half = 4 * pps * page                           # bytes per plane that belong to shards 0-3
+    pool = torch.empty(n_planes, ppp * page, dtype=torch.uint8, device="cuda")
+    pool[:, :half] = inputs.uniform_bytes_device(seed, n_planes * half, "cuda").view(n_planes, half)
+    pool[:, half:] = inputs.kv_bytes_device(seed + 7, n_planes * half, "bf16", 1.0, "cuda").view(n_planes, half)
+    table_np = np.concatenate([np.arange(4 * pps, dtype=np.int32).reshape(4, pps),
+                               4 * pps + inputs.block_table_np(seed, 4, pps, 4 * pps)])
+    table = torch.from_numpy(np.ascontiguousarray(table_np)).cuda()
+    base = torch.tensor([pool.data_ptr() + p * ppp * page for p in range(n_planes)], dtype=torch.int64, device="cuda")
+    pages = pool.view(n_planes, ppp, page)
+
+    def gathered(j):   # shard j's logical byte stream, [plane][slot][page]
+        return pages[:, table[j].long()].reshape(-1).contiguous()
+
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    pipe = gs.gs_pipe_create(code, 64 << 20, 2)     # 32 slots of every plane per chunk, 8 chunks
+    gs.gs_checkpoint_paged(pipe, base, n_planes, page, ppp, table, pps, host)
+    gs.gs_pipe_sync(pipe)
+    data = [gathered(j) for j in range(k)]
+    parity = [h.cuda() for h in host]
+    check_windows(P, data, parity, S, seed + 3)
+    check_folds(P, data, parity)
+    # one gs_encode_paged call over the whole table gives the same parity
+    whole = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    gs.gs_encode_paged(code, base, n_planes, page, ppp, table, pps, whole)
+    torch.cuda.synchronize()
+    for i in range(m):
+        assert torch.equal(whole[i], parity[i])
+    del whole, data
+    original = pool.clone()
+    pats = inputs.random_erasure_patterns(seed, k + m, 3, c["patterns_full"])
+    assert len(pats) == 20
+    out = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    for pat in pats:
+        for r in pat:
+            if r < k:
+                pages[:, table[r].long()] = 0xA5    # the failed worker's buffers are flushed
+            else:
+                out[r - k].fill_(0xA5)
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, list(pat), parity_out=out)
+        gs.gs_pipe_sync(pipe)
+        torch.cuda.synchronize()
+        assert torch.equal(pool, original), pat
+        for r in pat:
+            if r >= k:
+                assert torch.equal(out[r - k], parity[r - k]), (pat, r)
+    gs.gs_pipe_destroy(pipe)

@@ -326,3 +326,131 @@ def test_pipe_timeline_is_ordered_and_results_unchanged(gs):
     gs.gs_pipe_sync(pipe)
     assert gs.gs_pipe_chunk_times(pipe) == []
     gs.gs_pipe_destroy(pipe)
+
+
+# ---- the same pipelines over a paged pool (Alg. 1 / Alg. 2 on the engine's paged KV cache) ----
+
+def paged_pool(seed, k, n_planes, page, pps, spare=5):
+    """planes of k*pps + spare pages each, and a table of distinct page ids from a seeded permutation"""
+    ppp = k * pps + spare
+    planes_np = [inputs.kv_bytes_np(seed + p, ppp * page, "bf16", 1.0) for p in range(n_planes)]
+    table_np = inputs.block_table_np(seed, k, pps, ppp)
+    return ppp, planes_np, table_np
+
+
+def upload_pool(planes_np, table_np):
+    pool = torch.from_numpy(np.concatenate(planes_np)).cuda()
+    plane_bytes = planes_np[0].size
+    base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(len(planes_np))], dtype=torch.int64, device="cuda")
+    return pool, base, torch.from_numpy(table_np).cuda()
+
+
+@pytest.mark.parametrize("k,m,n_planes,page,pps,slots_per_chunk,depth", [
+    (4, 2, 3, 2048, 11, 4, 2),      # three chunks, the last one of three slots
+    (8, 3, 5, 32768, 9, 2, 3),      # 32 KiB pages (16-token blocks), five chunks
+    (4, 1, 64, 2048, 16, 16, 2),    # the decode-step shape: one chunk
+    (4, 2, 2, 48, 37, 5, 2),        # pages that are not a multiple of 1 KiB
+    (8, 2, 4, 1024, 7, 100, 2),     # a chunk larger than the shard
+])
+def test_checkpoint_paged_equals_oracle_encode_paged(gs, k, m, n_planes, page, pps, slots_per_chunk, depth):
+    ppp, planes_np, table_np = paged_pool(300 + k + pps, k, n_planes, page, pps)
+    want = oracle.encode_paged(oracle.generator(k, m), planes_np, page, table_np)
+    pool, base, table = upload_pool(planes_np, table_np)
+    S = n_planes * pps * page
+    code = gs.gs_make_code(k, m)
+    pipe = gs.gs_pipe_create(code, n_planes * page * slots_per_chunk, depth)
+    host = [pinned(S) for _ in range(m)]
+    for rep in range(2):
+        for h in host:
+            h.fill_(0x5A)
+        gs.gs_checkpoint_paged(pipe, base, n_planes, page, ppp, table, pps, host)
+        gs.gs_pipe_sync(pipe)
+        for i in range(m):
+            got = host[i].numpy()
+            assert np.array_equal(got[:S], want[i]), (rep, i)
+            assert (got[S:] == 0x5A).all()
+    # the pool itself is only read
+    assert np.array_equal(pool.cpu().numpy(), np.concatenate(planes_np))
+    gs.gs_pipe_destroy(pipe)
+
+
+@pytest.mark.parametrize("k,m,n_planes,page,pps,slots_per_chunk,pat", [
+    (4, 2, 3, 2048, 11, 4, (1, 3)),        # two data shards: both parities come back from the host
+    (4, 2, 3, 2048, 11, 4, (0,)),
+    (8, 3, 5, 32768, 9, 2, (2, 5, 9)),     # data shards and a parity shard
+    (8, 3, 2, 4096, 6, 4, (8, 9, 10)),     # only parity lost: re-encoded into the device buffers, no H2D
+    (4, 2, 2, 48, 37, 5, (3, 5)),
+    (4, 2, 4, 1024, 7, 100, (0, 4)),
+])
+def test_restore_paged_rebuilds_pages_from_host_parity(gs, k, m, n_planes, page, pps, slots_per_chunk, pat):
+    ppp, planes_np, table_np = paged_pool(400 + k + pps, k, n_planes, page, pps)
+    par_np = oracle.encode_paged(oracle.generator(k, m), planes_np, page, table_np)
+    S = n_planes * pps * page
+    # the failure: the pages of the lost data shards are flushed (Section 6.1); lost parity is gone too
+    broken = [pl.copy() for pl in planes_np]
+    for r in pat:
+        if r < k:
+            for pl in broken:
+                pl.reshape(ppp, page)[table_np[r]] = 0xA5
+    pool, base, table = upload_pool(broken, table_np)
+    host = []
+    for i in range(m):
+        h = pinned(S)
+        if k + i in pat:
+            h.fill_(0xA5)          # must not be read
+        else:
+            h[:S] = torch.from_numpy(par_np[i])
+        host.append(h)
+    out = [torch.full((S + 64,), 0xC3, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    pipe = gs.gs_pipe_create(code, n_planes * page * slots_per_chunk, 2)
+    for rep in range(2):
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, list(pat), parity_out=out)
+        gs.gs_pipe_sync(pipe)
+        torch.cuda.synchronize()
+        # every page of the pool is back (lost shards rebuilt, survivors and spare pages untouched)
+        assert np.array_equal(pool.cpu().numpy(), np.concatenate(planes_np)), rep
+        for i in range(m):
+            got = out[i].cpu().numpy()
+            if k + i in pat:
+                assert np.array_equal(got[:S], par_np[i]), (rep, i)
+            else:
+                assert (got[:S] == 0xC3).all()
+            assert (got[S:] == 0xC3).all()
+    if all(r < k for r in pat):
+        # no parity shard is lost: the device parity array may be omitted
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, list(pat))
+        gs.gs_pipe_sync(pipe)
+        assert np.array_equal(pool.cpu().numpy(), np.concatenate(planes_np))
+    gs.gs_pipe_destroy(pipe)
+
+
+def test_paged_pipelines_refuse_bad_arguments(gs):
+    k, m, n_planes, page, pps = 4, 2, 2, 2048, 4
+    ppp, planes_np, table_np = paged_pool(77, k, n_planes, page, pps)
+    pool, base, table = upload_pool(planes_np, table_np)
+    code = gs.gs_make_code(k, m)
+    host = [pinned(n_planes * pps * page) for _ in range(m)]
+    small = gs.gs_pipe_create(code, page, 2)          # one page: less than one slot of both planes
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_checkpoint_paged(small, base, n_planes, page, ppp, table, pps, host)
+    assert e.value.status == gs.GS_EINVAL
+    pipe = gs.gs_pipe_create(code, n_planes * page * 2, 2)
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, [0, 1, 2])
+    assert e.value.status == gs.GS_ETOOMANY
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, [0, 5])   # lost parity needs parity_out
+    assert e.value.status == gs.GS_EINVAL
+    rdp = gs.gs_make_code(4, 2, gs.GS_RDP)
+    rp = gs.gs_pipe_create(rdp, 4 * 32768 * 4, 2)
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_checkpoint_paged(rp, base, n_planes, page, ppp, table, pps, host)
+    assert e.value.status == gs.GS_EINVAL
+    with pytest.raises(gs.GsError) as e:   # RDP shards hold whole stripes: refused before anything is enqueued
+        gs.gs_checkpoint(rp, [pool[j * 8192:] for j in range(4)], 4 * 32768 * 4 + 16, host)
+    assert e.value.status == gs.GS_EINVAL
+    gs.gs_pipe_sync(rp)
+    assert np.array_equal(pool.cpu().numpy(), np.concatenate(planes_np))
+    for p in (small, pipe, rp):
+        gs.gs_pipe_destroy(p)

@@ -179,10 +179,31 @@ def test_product_and_oracle_share_nothing():
                 names.add(node.module.split(".")[0])
         return names
 
+    def names_in_code(path, word):
+        tree = ast.parse(open(path).read())
+        docstrings = set()
+        for node in ast.walk(tree):
+            if isinstance(node, (ast.Module, ast.FunctionDef, ast.ClassDef)) and node.body and \
+                    isinstance(node.body[0], ast.Expr) and isinstance(node.body[0].value, ast.Constant):
+                docstrings.add(id(node.body[0].value))
+        hits = []
+        for node in ast.walk(tree):
+            if isinstance(node, ast.Constant) and isinstance(node.value, str) and id(node) not in docstrings \
+                    and word in node.value.lower():
+                hits.append(node.value)
+            elif isinstance(node, ast.Name) and word in node.id.lower():
+                hits.append(node.id)
+            elif isinstance(node, ast.Attribute) and word in node.attr.lower():
+                hits.append(node.attr)
+        return hits
+
     pkg = os.path.join(root, "paper_2605_00831_amd")
     for f in os.listdir(pkg):
         if f.endswith(".py"):
             assert "oracle" not in imports_of(os.path.join(pkg, f)), f
+            # nor names it in code (a path to its sources, a dlopen, a subprocess): no string
+            # literal other than a docstring, and no identifier, contains the word
+            assert not names_in_code(os.path.join(pkg, f), "oracle"), f
     for f in os.listdir(os.path.join(root, "oracle")):
         if f.endswith(".py"):
             assert "paper_2605_00831_amd" not in imports_of(os.path.join(root, "oracle", f)), f
