@@ -73,7 +73,8 @@ enum gs_status {
     GS_ENOMEM = -2,    /* host or device allocation failed                       */
     GS_ETOOMANY = -3,  /* more erasures than parity shards                       */
     GS_ESINGULAR = -4, /* survivor matrix not invertible (cannot happen for a code made here) */
-    GS_EHIP = -5       /* a HIP runtime call failed; see gs_last_hip_error()      */
+    GS_EHIP = -5,      /* a HIP runtime call failed; see gs_last_hip_error()      */
+    GS_ELIMIT = -6     /* beyond the fixed capacity of an entry point that allocates nothing */
 };
 
 enum gs_kind {
@@ -331,6 +332,25 @@ int gs_encode_batch(gs_batch *batch, int n_chunks, const void *const *data, void
                     const size_t *shard_bytes, void *stream);
 int gs_reconstruct_batch(gs_batch *batch, int n_chunks, void *const *shards, const int *erased,
                          int n_erased, const size_t *shard_bytes, void *stream);
+
+/* Grouped encode that allocates nothing.  For callers that cannot call
+ * hipMalloc: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments and results as gs_encode_batch without
+ * the gs_batch object: the chunk descriptors live in a fixed array inside the
+ * library's device image (GS_STATIC_MAX_CHUNKS descriptors, 176 KiB, held on
+ * every device the library runs on until the process ends) and are written by
+ * a small kernel that receives them as launch arguments, so the call enqueues
+ * kernel launches only -- no allocation, no copy, no host wait -- and may be
+ * captured into a graph.
+ *   n_chunks > GS_STATIC_MAX_CHUNKS, or a chunk of 64 GiB or more: GS_ELIMIT,
+ *   nothing enqueued.  Codes with k <= 16 and m <= 4 only (else GS_EINVAL).
+ * All calls on one device share that device's array, and a call overwrites
+ * what the previous one left there: calls on the same stream are ordered by
+ * the stream; calls that may run at the same time on different streams of one
+ * device race on the array and must be ordered by the caller (an event). */
+#define GS_STATIC_MAX_CHUNKS 1024
+int gs_encode_batch_static(const gs_code *code, int n_chunks, const void *const *data, void *const *parity,
+                           const size_t *shard_bytes, void *stream);
 
 /* Stream pool (gs_pool): the paper's form.  Chunk c is enqueued on pool
  * stream c mod n_streams (default priority); the pool streams start after the

@@ -13,7 +13,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libghostserve_ec.so")
 
-GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP = 0, -1, -2, -3, -4, -5
+GS_OK, GS_EINVAL, GS_ENOMEM, GS_ETOOMANY, GS_ESINGULAR, GS_EHIP, GS_ELIMIT = 0, -1, -2, -3, -4, -5, -6
+GS_STATIC_MAX_CHUNKS = 1024
 GS_CAUCHY, GS_VANDERMONDE, GS_RDP, GS_POWER = 0, 1, 2, 3
 
 EXPORTS = [
@@ -22,7 +23,7 @@ EXPORTS = [
     "gs_pipe_create", "gs_pipe_destroy", "gs_checkpoint", "gs_restore", "gs_checkpoint_paged", "gs_restore_paged", "gs_pipe_sync",
     "gs_pipe_done_event", "gs_pipe_set_timing", "gs_pipe_chunk_times",
     "gs_step_graph_create", "gs_step_graph_launch", "gs_step_graph_destroy",
-    "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch",
+    "gs_batch_create", "gs_batch_destroy", "gs_encode_batch", "gs_reconstruct_batch", "gs_encode_batch_static",
     "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
     "gs_recompute_units",
     "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape", "gs_set_power_horner",
@@ -106,6 +107,7 @@ def lib():
     L.gs_batch_destroy.restype = None
     L.gs_encode_batch.argtypes = [_vp, ctypes.c_int, _vpp, _vpp, _szp, _vp]
     L.gs_reconstruct_batch.argtypes = [_vp, ctypes.c_int, _vpp, _intp, ctypes.c_int, _szp, _vp]
+    L.gs_encode_batch_static.argtypes = [_vp, ctypes.c_int, _vpp, _vpp, _szp, _vp]
     L.gs_pool_create.argtypes = [ctypes.c_int, ctypes.POINTER(_vp)]
     L.gs_pool_destroy.argtypes = [_vp]
     L.gs_pool_destroy.restype = None
@@ -415,6 +417,13 @@ def gs_encode_batch(batch, data, parity, shard_bytes, stream=None):
     n = len(data)
     _check(lib().gs_encode_batch(batch.handle, n, _flat_ptrs(data, batch.code.k), _flat_ptrs(parity, batch.code.m),
                                  _size_array(shard_bytes), _stream(stream)), "gs_encode_batch")
+
+
+def gs_encode_batch_static(code, data, parity, shard_bytes, stream=None):
+    """gs_encode_batch without a gs_batch object and without any allocation (at most GS_STATIC_MAX_CHUNKS chunks)."""
+    n = len(data)
+    _check(lib().gs_encode_batch_static(code.handle, n, _flat_ptrs(data, code.k), _flat_ptrs(parity, code.m),
+                                        _size_array(shard_bytes), _stream(stream)), "gs_encode_batch_static")
 
 
 def gs_reconstruct_batch(batch, shards, erased, shard_bytes, stream=None):

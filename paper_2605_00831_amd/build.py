@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libghostserve_ec.so")
-SOURCES = ["gs_gf.cpp", "gs_api.cpp", "gs_pipeline.cpp", "gs_batch.cpp", "gs_plan.cpp", "gs_rdp.cpp", "gs_rdp_kernels.hip", "gs_kernels.hip"]
+SOURCES = ["gs_gf.cpp", "gs_api.cpp", "gs_pipeline.cpp", "gs_batch.cpp", "gs_plan.cpp", "gs_rdp.cpp", "gs_rdp_kernels.hip", "gs_kernels.hip", "gs_static.hip"]
 HEADERS = ["gs_gf.h", "gs_internal.h", "gs_launch.h", "gs_rdp.h", os.path.join("..", "..", "include", "ghostserve_ec.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

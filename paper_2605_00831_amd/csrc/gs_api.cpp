@@ -517,6 +517,7 @@ const char *gs_strerror(int status)
         case GS_ETOOMANY: return "more erasures than parity shards";
         case GS_ESINGULAR: return "survivor matrix is singular";
         case GS_EHIP: return "HIP runtime error";
+        case GS_ELIMIT: return "beyond the fixed capacity of an entry point that allocates nothing";
         default: return "unknown status";
     }
 }

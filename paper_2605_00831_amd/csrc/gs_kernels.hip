@@ -46,14 +46,7 @@ struct ApplyArgs {
     uint32_t nx_shift;    // log2 of the interleave modulus (0 = plain consecutive tiles)
 };
 
-// one chunk of a batched launch (device memory)
-struct BatchDesc {
-    const uint8_t *in[kLaunchMaxK];
-    uint8_t *out[kLaunchMaxM];
-    uint64_t nvec;
-    uint32_t tail;
-    uint32_t nx_shift;
-};
+static_assert(sizeof(BatchDesc) == kBatchDescBytes, "descriptor size is part of the internal interface");
 
 struct BatchArgs {
     const BatchDesc *descs;  // device array, one per blockIdx.y

@@ -48,6 +48,16 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
                               const PagedStream *in, const PagedStream *out, bool accumulate,
                               const LaunchShape &shape, hipStream_t stream);
 
+// one chunk of a batched launch, as the kernel reads it from device memory
+struct BatchDesc {
+    const uint8_t *in[kLaunchMaxK];
+    uint8_t *out[kLaunchMaxM];   // in the launch's row order (batch_row_order)
+    uint64_t nvec;               // whole 16-byte vectors per stream
+    uint32_t tail;               // trailing bytes after the last whole vector (0..15)
+    uint32_t nx_shift;           // log2 of this chunk's piece interleave modulus
+};
+constexpr size_t kBatchDescBytes = 8 * (kLaunchMaxK + kLaunchMaxM) + 16;
+
 // Batched form: n_chunks independent stream sets in one launch (blockIdx.y =
 // chunk).  Descriptors are written on the host with write_batch_desc() into a
 // buffer of n * batch_desc_bytes() bytes, copied to the device by the caller,

@@ -186,6 +186,34 @@ int main(void)
         EXPECT(gs_reconstruct(rdp2, q, er2, 2, 1024, NULL) == GS_EINVAL);
         gs_free_code(rdp2);
     }
+    /* the grouped encode that allocates nothing: refusals, and the host side up to the first launch */
+    {
+        gs_code *code = NULL;
+        EXPECT(gs_make_code(8, 2, GS_CAUCHY, &code) == GS_OK);
+        static const void *data[8 * 40];
+        static void *par[2 * 40];
+        static size_t sizes[GS_STATIC_MAX_CHUNKS + 1];
+        for (int c = 0; c < 40; c++) {
+            for (int j = 0; j < 8; j++) data[c * 8 + j] = fake[(c * 10 + j) % MAXN];
+            for (int i = 0; i < 2; i++) par[c * 2 + i] = fake[(c * 10 + 8 + i) % MAXN];
+            sizes[c] = 4096 + 7 * (size_t)c;
+        }
+        EXPECT(gs_encode_batch_static(code, GS_STATIC_MAX_CHUNKS + 1, data, par, sizes, NULL) == GS_ELIMIT);
+        EXPECT(gs_encode_batch_static(code, 0, data, par, sizes, NULL) == GS_OK);
+        EXPECT(gs_encode_batch_static(code, -1, data, par, sizes, NULL) == GS_EINVAL);
+        EXPECT(gs_encode_batch_static(code, 25, data, par, sizes, NULL) == GS_EHIP);   /* no device: the first runtime call fails */
+        sizes[3] = (size_t)1 << 36;
+        EXPECT(gs_encode_batch_static(code, 25, data, par, sizes, NULL) == GS_ELIMIT);
+        sizes[3] = 64;
+        par[2 * 3] = (void *)data[8 * 3 + 1];
+        EXPECT(gs_encode_batch_static(code, 25, data, par, sizes, NULL) == GS_EINVAL);  /* output on top of an input */
+        gs_free_code(code);
+        gs_code *wide = NULL;
+        EXPECT(gs_make_code(17, 2, GS_CAUCHY, &wide) == GS_OK);
+        EXPECT(gs_encode_batch_static(wide, 1, data, par, sizes, NULL) == GS_EINVAL);
+        gs_free_code(wide);
+        EXPECT(strlen(gs_strerror(GS_ELIMIT)) > 0);
+    }
     EXPECT(gs_last_hip_error() != 0);
     EXPECT(strlen(gs_strerror(GS_EHIP)) > 0 && strlen(gs_strerror(12345)) > 0);
     gs_pipe_destroy(NULL);
