@@ -98,6 +98,48 @@ def native_probe(log, *argv):
     return res
 
 
+_PINNED = None
+
+
+def pinned_arena(torch, nbytes=0):
+    """One pinned host allocation made when the run starts and shared, one after the other, by every
+    leg that ships parity over PCIe.  Pinned memory lands on the NUMA node of the thread that asks for
+    it; buffers pinned later in the run, after the multi-threaded CPU legs have moved this thread
+    around, gave transfers anywhere between 31 and 56 GB/s from one run to the next, so everything is
+    pinned up front by the same thread."""
+    global _PINNED
+    if _PINNED is None or _PINNED.numel() < nbytes:
+        _PINNED = None
+        _PINNED = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, pin_memory=True)
+    return _PINNED
+
+
+_DEVICE = None
+
+
+def device_arena(torch, nbytes):
+    """One device allocation that the bulk workloads take their shards from, one after the other.
+    Giving tens of GiB back to the driver in the middle of a run (hipFree) is not free on this
+    machine: for a few seconds afterwards the driver is busy with the released memory, parity D2H
+    through the copy engines ran at 31 GB/s instead of 56 and the HBM-bound kernels lost 3 points.
+    So nothing large is freed between the legs."""
+    global _DEVICE
+    if _DEVICE is None or _DEVICE.numel() < nbytes:
+        _DEVICE = None
+        _DEVICE = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    return _DEVICE
+
+
+def pinned_slices(torch, sizes):
+    """len(sizes) disjoint pinned host buffers out of the arena (each start 4 KiB aligned)"""
+    offs, at = [], 0
+    for n in sizes:
+        offs.append(at)
+        at += (n + 4095) // 4096 * 4096
+    arena = pinned_arena(torch, at)
+    return [arena[o:o + n] for o, n in zip(offs, sizes)]
+
+
 def pctl(xs, q):
     xs = sorted(xs)
     return xs[min(len(xs) - 1, int(q * len(xs)))]
@@ -149,8 +191,15 @@ def main():
     if args.launch_shape:
         u, t, nt, ilv = (int(x) for x in args.launch_shape.split(","))
         gs.gs_set_launch_shape(u, t, nt, ilv)
+    if args.only is None:
+        device_arena(torch, 50 << 30)   # the 70B workload with its parity: the largest of the bulk workloads
+    if not args.no_extras:
+        t0 = time.perf_counter()
+        pinned_arena(torch, (16 << 30) + (1 << 20))   # the 8B workload's parity; every other leg needs less
+        log("[bench] pinned %.1f GiB of host memory in %.1f s" % (_PINNED.numel() / 2**30, time.perf_counter() - t0))
     if args.only == "paged_bulk":
-        print(json.dumps({"paged_bulk": paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)}), flush=True)
+        print(json.dumps({"paged_bulk": paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras,
+                                                   calibrate=args.calibrate_copy)}), flush=True)
         return 0
 
     cfg = inputs.CONFIGS[args.workload]
@@ -251,7 +300,6 @@ def main():
     if args.only is None and args.code == "cauchy":
         # the other bulk workloads, timed the same way after the headline workload's buffers are gone
         del data, parity, shards
-        torch.cuda.empty_cache()
         out["configs"] = [dict(workload=args.workload, kernel=out["roofline"]["kernel"],
                                algorithmic_bytes_per_launch=enc_alg_bytes, avg_launch_ms=out["roofline"]["avg_launch_ms"],
                                frac=out["roofline"]["frac"], reconstruct_ms=out["reconstruct_ms"],
@@ -262,7 +310,6 @@ def main():
             if name != args.workload:
                 out["configs"].append(bulk_config(torch, gs, inputs, name, max(args.steps, 20), args.warmup, log,
                                                   pipelines=not args.no_extras, default_shape=args.launch_shape is None))
-                torch.cuda.empty_cache()
         out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
 
     print(json.dumps(out), flush=True)
@@ -275,21 +322,23 @@ def inputs_steps():
 
 
 def workload_buffers(torch, inputs, name, dev="cuda:0"):
-    """(k, m, S, erased, data shards, parity shards) of a bulk workload, generated on the device."""
+    """(k, m, S, erased, data shards, parity shards) of a bulk workload, generated on the device
+    inside the device arena."""
     cfg = inputs.CONFIGS[name]
     k, m = cfg["k"], cfg["m"]
     total = inputs.config_total_bytes(name)
     S = total // k
     erased = list(cfg.get("erased", (2, 5, 9) if name == "recovery_stress" else (1, 3) if k >= 4 else (0,)))[:m]
+    arena = device_arena(torch, (k + m) * S)
+    buf = arena[:total]
     if name == "recovery_stress":
         half = (k // 2) * S
-        buf = torch.empty(total, dtype=torch.uint8, device=dev)
-        buf[:half] = inputs.uniform_bytes_device(inputs.config_seed(name), half, dev)
-        buf[half:] = inputs.kv_bytes_device(inputs.config_seed(name) + 1, total - half, "bf16", 1.0, dev)
+        inputs.uniform_bytes_device(inputs.config_seed(name), half, dev, out=buf[:half])
+        inputs.kv_bytes_device(inputs.config_seed(name) + 1, total - half, "bf16", 1.0, dev, out=buf[half:])
     else:
-        buf = inputs.kv_bytes_device(inputs.config_seed(name), total, cfg["dtype"], cfg["sigma"], dev)
+        inputs.kv_bytes_device(inputs.config_seed(name), total, cfg["dtype"], cfg["sigma"], dev, out=buf)
     data = [buf[j * S:(j + 1) * S] for j in range(k)]
-    parity = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(m)]
+    parity = [arena[(k + i) * S:(k + i + 1) * S] for i in range(m)]
     return k, m, S, erased, data, parity
 
 
@@ -330,10 +379,10 @@ def bulk_config(torch, gs, inputs, name, launches, warmup, log, pipelines=True, 
             chunk = chunk_tokens * cfg["batch"] * inputs.bytes_per_token(cfg["layers"]) // k
         else:
             chunk = max(16, (S // 4 + 15) // 16 * 16)
-        host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+        host = pinned_slices(torch, [S] * m)
         pipe = gs.gs_pipe_create(code, chunk, 2)
 
-        def best(fn, n=3):
+        def best(fn, n=5):
             ts = []
             for _ in range(n):
                 torch.cuda.synchronize()
@@ -356,26 +405,40 @@ def bulk_config(torch, gs, inputs, name, launches, warmup, log, pipelines=True, 
     return res
 
 
-def paged_bulk(torch, gs, inputs, log, pipelines=True):
-    """Bulk paged gather (the recovery-stress shape on a paged pool): 64 planes of 256 MiB, shards of
+def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
+    """Bulk paged gather (the recovery-stress shape on a paged pool): 64 planes of 272 MiB, shards of
     2 GiB gathered through a block table, 32 KiB pages (16-token blocks) and 2 KiB pages (token slots),
-    behind a seeded random permutation and, as the control, behind the identity table; 4+2 and 8+3.
+    behind a seeded random permutation and, as controls, behind identity tables; 4+2 and 8+3.
     Each case: events around 10 launches on the launch stream.  Then the paged checkpoint / restore
     pipelines (8+3, 32 KiB pages, shards {2, 5} and parity shard 9 lost)."""
     dev = "cuda:0"
-    n_planes, plane_bytes, shard_per_plane = 64, 256 << 20, 32 << 20
-    pool = inputs.kv_bytes_device(inputs.config_seed("recovery_stress") + 7, n_planes * plane_bytes, "bf16", 1.0, dev)
-    base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(n_planes)], dtype=torch.int64, device=dev)
+    n_planes, shard_per_plane = 64, 32 << 20
+    # room for 8 shards per plane plus a margin, so that one identity control can keep its shards off
+    # power-of-two distances from each other (equal offsets of streams exactly 32 MiB apart fall on the
+    # same DRAM banks, which costs the contiguous kernels the same 5 points)
+    plane_bytes = 8 * (shard_per_plane + (2 << 20))
     S = n_planes * shard_per_plane
-    par = [torch.empty(S, dtype=torch.uint8, device=dev) for _ in range(3)]
+    arena = device_arena(torch, n_planes * plane_bytes + 3 * S)
+    pool = inputs.kv_bytes_device(inputs.config_seed("recovery_stress") + 7, n_planes * plane_bytes, "bf16", 1.0, dev,
+                                  out=arena[:n_planes * plane_bytes])
+    base = torch.tensor([pool.data_ptr() + p * plane_bytes for p in range(n_planes)], dtype=torch.int64, device=dev)
+    par = [arena[n_planes * plane_bytes + i * S: n_planes * plane_bytes + (i + 1) * S] for i in range(3)]
+    if calibrate:
+        # a plain elementwise copy of known size (counter calibration under rocprofv3 --pmc)
+        par[0].copy_(par[1])
+        torch.cuda.synchronize()
+        log("[bench] calibration copy: %d bytes read, %d bytes written" % (S, S))
     cases = []
     tables = {}
     for page in (32768, 2048):
         ppp, pps = plane_bytes // page, shard_per_plane // page
         perm = inputs.block_table_np(inputs.config_seed("recovery_stress"), 8, pps, ppp)
-        ident = np.arange(8 * pps, dtype=np.int32).reshape(8, pps)
-        for tname, tab in (("random permutation", perm), ("identity", ident)):
-            table = torch.from_numpy(np.ascontiguousarray(tab)).to(dev)
+        skew = (2 << 20) // page   # identity control: shard j starts at j * (32 MiB + 2 MiB) of its plane
+        ident = (np.arange(8, dtype=np.int32)[:, None] * (pps + skew) + np.arange(pps, dtype=np.int32)[None, :])
+        dense = np.arange(8 * pps, dtype=np.int32).reshape(8, pps)
+        for tname, tab in (("random permutation", perm), ("identity, shards 34 MiB apart", ident),
+                           ("identity, shards 32 MiB apart", dense)):
+            table = torch.from_numpy(np.ascontiguousarray(tab.astype(np.int32))).to(dev)
             tables[(page, tname)] = table
             for k, m in ((4, 2), (8, 3)):
                 code = gs.gs_make_code(k, m)
@@ -404,11 +467,11 @@ def paged_bulk(torch, gs, inputs, log, pipelines=True):
         ppp, pps = plane_bytes // page, shard_per_plane // page
         table = tables[(page, "random permutation")]
         code = gs.gs_make_code(k, m)
-        host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+        host = pinned_slices(torch, [S] * m)
         chunk = S // 8
         pipe = gs.gs_pipe_create(code, chunk, 2)
 
-        def best(fn, n=3):
+        def best(fn, n=5):
             ts = []
             for _ in range(n):
                 torch.cuda.synchronize()
@@ -440,9 +503,7 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
         chunk = chunk_tokens * cfg["batch"] * per_tok // k
     else:
         chunk = max(16, (S // 4 + 15) // 16 * 16)
-    t0 = time.perf_counter()
-    host = [torch.empty(S, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
-    log("[bench] pinned %.1f GiB of host memory in %.1f s" % (m * S / 2**30, time.perf_counter() - t0))
+    host = pinned_slices(torch, [S] * m)
     # plain pinned D2H / H2D rate of one parity shard, same run
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -652,7 +713,7 @@ def chunk_sweep(torch, gs, inputs, log):
     max_S = 4096 * batch * per_tok // k
     buf = torch.empty((k + m) * max_S, dtype=torch.uint8, device="cuda")
     buf.random_(0, 256)
-    host = torch.empty(m * max_S, dtype=torch.uint8, pin_memory=True)
+    host = pinned_slices(torch, [m * max_S])[0]
 
     def med(fn):
         ts = []
@@ -749,7 +810,7 @@ def decode_steps(torch, gs, inputs, log, native=None):
     table = tables[0].clone()
     out_bytes = n_planes * seqs_per_shard * slot_bytes
     par = [torch.empty(out_bytes, dtype=torch.uint8, device=dev) for _ in range(m)]
-    host = [torch.empty(out_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(m)]
+    host = pinned_slices(torch, [out_bytes] * m)
     code = gs.gs_make_code(k, m)
     torch.cuda.synchronize()
 

@@ -327,6 +327,20 @@ static int run_decode(int steps, int layers)
                 printf(", \"stream_encode_only\": {\"sustained_us_per_step\": %.2f, \"host_enqueue_us_per_step\": %.2f}",
                        (t2 - t0) / steps, (t1 - t0) / steps);
         }
+        /* graph replays back to back, no host wait: the one-step graph and the graph of GRAPH_STEPS steps */
+        for (int v = 0; v < 2; v++) {
+            hipGraphExec_t exec = v == 0 ? c.own : c.multi;
+            const int per = v == 0 ? 1 : GRAPH_STEPS, n = steps / per;
+            for (int r = 0; r < 10; r++) CHECK_HIP(hipGraphLaunch(exec, c.stream));
+            CHECK_HIP(hipStreamSynchronize(c.stream));
+            const double t0 = now_us();
+            for (int r = 0; r < n; r++) CHECK_HIP(hipGraphLaunch(exec, c.stream));
+            const double t1 = now_us();
+            CHECK_HIP(hipStreamSynchronize(c.stream));
+            const double t2 = now_us();
+            printf(", \"stream_graph_of_%d\": {\"sustained_us_per_step\": %.2f, \"host_enqueue_us_per_step\": %.2f}",
+                   per, (t2 - t0) / (n * per), (t1 - t0) / (n * per));
+        }
         for (int s = 0; s < steps; s++) {
             (void)hipEventDestroy(t_begin[s]);
             (void)hipEventDestroy(t_end[s]);

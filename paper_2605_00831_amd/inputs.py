@@ -135,12 +135,15 @@ def random_erasure_patterns(seed, n_shards, e, count):
 
 # ---------------------------------------------------------------- torch side
 
-def kv_bytes_device(seed, nbytes, dtype="bf16", sigma=1.0, device="cuda", piece=GiB):
+def kv_bytes_device(seed, nbytes, dtype="bf16", sigma=1.0, device="cuda", piece=GiB, out=None):
     """Same distribution generated on the device, in pieces of at most `piece`
-    bytes so the float32 staging stays small.  Returns a uint8 tensor."""
+    bytes so the float32 staging stays small.  Returns a uint8 tensor (`out`,
+    a uint8 device tensor of nbytes, if one is given)."""
     import torch
     tdt = {"bf16": torch.bfloat16, "fp16": torch.float16}[dtype]
-    out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    assert out.numel() == nbytes
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     done = 0
@@ -156,9 +159,11 @@ def kv_bytes_device(seed, nbytes, dtype="bf16", sigma=1.0, device="cuda", piece=
     return out
 
 
-def uniform_bytes_device(seed, nbytes, device="cuda", piece=GiB):
+def uniform_bytes_device(seed, nbytes, device="cuda", piece=GiB, out=None):
     import torch
-    out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    assert out.numel() == nbytes
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     done = 0
