@@ -33,13 +33,15 @@ PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 # WRITE_SIZE, scaled by a plain copy kernel of known size.  Bytes per launch,
 # valid for the kernel template and the default launch shape named beside it;
 # a run with another launch shape reports null.
-MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE x 1.99996 + WRITE_SIZE x 1.00000 in bytes, kernel, profile)
+MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE and WRITE_SIZE scaled to bytes, kernel, profile)
     ("llama8b_prefill", "cauchy"): (51539161269, "apply_contig_kernel<2, true, 2, true>",
                                     "profiles/encode_contig_llama8b_prefill.md"),
     ("llama8b_prefill", "power"): (51539042211, "horner_contig_kernel<2, 2, true>",
                                    "profiles/horner_power_code_llama8b_prefill.md"),
-    ("llama70b_longctx", "cauchy"): (53686381435, "apply_contig_kernel<2, true, 2, true>",
-                                     "profiles/kernels_other_workloads.md"),
+    ("llama70b_longctx", "cauchy"): (53685737460, "apply_contig_kernel<2, true, 2, true>",
+                                     "profiles/encode_contig_llama70b_longctx.md"),
+    ("recovery_stress", "cauchy"): (5905626583, "apply_contig_kernel<3, true, 2, true>",
+                                    "profiles/encode_contig_recovery_stress.md"),
 }
 
 
@@ -408,7 +410,8 @@ def bulk_config(torch, gs, inputs, name, launches, warmup, log, pipelines=True, 
 def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
     """Bulk paged gather (the recovery-stress shape on a paged pool): 64 planes of 272 MiB, shards of
     2 GiB gathered through a block table, 32 KiB pages (16-token blocks) and 2 KiB pages (token slots),
-    behind a seeded random permutation and, as controls, behind identity tables; 4+2 and 8+3.
+    behind a seeded random permutation and, as controls, behind identity tables and behind permutations
+    of runs of consecutive pages; 4+2 and 8+3.
     Each case: events around 10 launches on the launch stream.  Then the paged checkpoint / restore
     pipelines (8+3, 32 KiB pages, shards {2, 5} and parity shard 9 lost)."""
     dev = "cuda:0"
@@ -436,8 +439,16 @@ def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
         skew = (2 << 20) // page   # identity control: shard j starts at j * (32 MiB + 2 MiB) of its plane
         ident = (np.arange(8, dtype=np.int32)[:, None] * (pps + skew) + np.arange(pps, dtype=np.int32)[None, :])
         dense = np.arange(8 * pps, dtype=np.int32).reshape(8, pps)
-        for tname, tab in (("random permutation", perm), ("identity, shards 34 MiB apart", ident),
-                           ("identity, shards 32 MiB apart", dense)):
+        variants = [("random permutation", perm), ("identity, shards 34 MiB apart", ident),
+                    ("identity, shards 32 MiB apart", dense)]
+        if page == 32768:
+            # an allocator that hands out pages in runs: the pool permuted in units of 2, 8 and 128 pages
+            rng = np.random.default_rng(inputs.config_seed("recovery_stress") + inputs.TABLE_SEED_OFFSET + 1)
+            for run in (2, 8, 128):
+                starts = rng.permutation(ppp // run)[: 8 * pps // run]
+                runs = (starts[:, None] * run + np.arange(run)[None, :]).reshape(8, pps)
+                variants.append(("random permutation of runs of %d pages (%d KiB)" % (run, run * page >> 10), runs))
+        for tname, tab in variants:
             table = torch.from_numpy(np.ascontiguousarray(tab.astype(np.int32))).to(dev)
             tables[(page, tname)] = table
             for k, m in ((4, 2), (8, 3)):
@@ -460,8 +471,32 @@ def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
                                            "achieved": round(alg / ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                            "frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
                                            "algorithmic_bytes_per_launch": alg, "avg_launch_ms": round(ms, 4)}})
+    # controls: the contiguous kernel on shards of the same length laid out back to back, and the paged
+    # kernel over exactly those addresses (one plane, identity table)
+    controls = []
+    page = 32768
+    one_plane = torch.tensor([arena.data_ptr()], dtype=torch.int64, device=dev)
+    for k, m in ((4, 2), (8, 3)):
+        code = gs.gs_make_code(k, m)
+        shards = [arena[j * S:(j + 1) * S] for j in range(k + m)]
+        ident = torch.arange(k * (S // page), dtype=torch.int32, device=dev).reshape(k, S // page).contiguous()
+        for name, fn in (("gs_encode, contiguous shards", lambda: gs.gs_encode(code, shards[:k], shards[k:], S)),
+                         ("gs_encode_paged, one plane, identity table, the same addresses",
+                          lambda: gs.gs_encode_paged(code, one_plane, 1, page, (k + m) * (S // page), ident, S // page, shards[k:]))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / 10
+            controls.append({"k": k, "m": m, "what": name, "shard_bytes": S, "avg_launch_ms": round(ms, 4),
+                             "frac": round((k + m) * S / ms / 1e6 / HBM_PEAK_GBPS, 4)})
     res = {"pool": "%d planes x %d MiB, %d MiB of every shard per plane" % (n_planes, plane_bytes >> 20, shard_per_plane >> 20),
-           "cases": cases}
+           "cases": cases, "controls": controls}
     if pipelines:
         k, m, page, erased = 8, 3, 32768, [2, 5, 9]
         ppp, pps = plane_bytes // page, shard_per_plane // page

@@ -313,6 +313,23 @@ static int run_decode(int steps, int layers)
                        "\"host_enqueue_us_per_step\": %.2f, \"parity_GBps\": %.2f}",
                        RING, (t2 - t0) / steps, (t1 - t0) / steps, M * c.out_bytes / ((t2 - t0) / steps) / 1e3);
         }
+        /* encode and D2H copy on ONE stream, no events: nothing overlaps, but the host makes two calls per step */
+        for (int pass = 0; pass < 2; pass++) {
+            const int n = pass == 0 ? warm : steps, first = pass == 0 ? 0 : warm;
+            CHECK_HIP(hipStreamSynchronize(c.stream));
+            const double t0 = now_us();
+            for (int s = 0; s < n; s++) {
+                CHECK_GS(encode_into(&c, tables_all_dev + (size_t)(first + s) * SEQS, &ring_dev[s % RING], c.stream));
+                CHECK_HIP(hipMemcpyAsync(ring_host[s % RING], ring_dev[s % RING], c.out_bytes, hipMemcpyDeviceToHost, c.stream));
+            }
+            const double t1 = now_us();
+            CHECK_HIP(hipStreamSynchronize(c.stream));
+            const double t2 = now_us();
+            if (pass)
+                printf(", \"stream_one_stream_encode_then_copy\": {\"sustained_us_per_step\": %.2f, "
+                       "\"host_enqueue_us_per_step\": %.2f, \"parity_GBps\": %.2f}",
+                       (t2 - t0) / steps, (t1 - t0) / steps, M * c.out_bytes / ((t2 - t0) / steps) / 1e3);
+        }
         /* and encode only, back to back, into the device ring: what the GPU side of a step costs */
         for (int pass = 0; pass < 2; pass++) {
             const int n = pass == 0 ? warm : steps, first = pass == 0 ? 0 : warm;
