@@ -105,10 +105,8 @@ _PINNED = None
 
 def pinned_arena(torch, nbytes=0):
     """One pinned host allocation made when the run starts and shared, one after the other, by every
-    leg that ships parity over PCIe.  Pinned memory lands on the NUMA node of the thread that asks for
-    it; buffers pinned later in the run, after the multi-threaded CPU legs have moved this thread
-    around, gave transfers anywhere between 31 and 56 GB/s from one run to the next, so everything is
-    pinned up front by the same thread."""
+    leg that ships parity over PCIe: pinning tens of GiB takes seconds of host time, and nothing is
+    unpinned or re-pinned in the middle of the run."""
     global _PINNED
     if _PINNED is None or _PINNED.numel() < nbytes:
         _PINNED = None
@@ -313,6 +311,7 @@ def main():
                 out["configs"].append(bulk_config(torch, gs, inputs, name, max(args.steps, 20), args.warmup, log,
                                                   pipelines=not args.no_extras, default_shape=args.launch_shape is None))
         out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
+        out["code_shapes"] = code_shapes(torch, gs, log)
 
     print(json.dumps(out), flush=True)
     return 0
@@ -405,6 +404,33 @@ def bulk_config(torch, gs, inputs, name, launches, warmup, log, pipelines=True, 
         del host
     log("[bench] config %s: %s" % (name, json.dumps(res)))
     return res
+
+
+def code_shapes(torch, gs, log):
+    """gs_encode over 40 GiB in total (data + parity) for a range of code shapes, default launch shape:
+    how the number of streams and of parity rows moves the HBM fraction.  Events around 7 launches."""
+    total = 40 << 30
+    arena = device_arena(torch, total)
+    rows = []
+    for k, m in ((1, 1), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1), (8, 2), (8, 3), (8, 4), (16, 1), (16, 2), (16, 4), (1, 4)):
+        S = total // (k + m) // 4096 * 4096
+        shards = [arena[j * S:(j + 1) * S] for j in range(k + m)]
+        code = gs.gs_make_code(k, m)
+        for _ in range(2):
+            gs.gs_encode(code, shards[:k], shards[k:], S)
+        torch.cuda.synchronize()
+        n = 7
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        evs[0].record()
+        for i in range(n):
+            gs.gs_encode(code, shards[:k], shards[k:], S)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        ms = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n))[n // 2]
+        rows.append({"k": k, "m": m, "shard_bytes": S, "encode_ms": round(ms, 4),
+                     "frac": round((k + m) * S / ms / 1e6 / HBM_PEAK_GBPS, 4)})
+    log("[bench] code shapes: " + json.dumps(rows))
+    return rows
 
 
 def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
