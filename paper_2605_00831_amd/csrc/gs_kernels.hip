@@ -82,6 +82,7 @@ template <bool NT>
 __device__ __forceinline__ u32x4 load16(const uint8_t *base, uint64_t vec)
 {
     const u32x4 *p = reinterpret_cast<const u32x4 *>(base) + vec;
+
     if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
@@ -92,6 +93,27 @@ __device__ __forceinline__ void store16(uint8_t *base, uint64_t vec, u32x4 v)
     u32x4 *p = reinterpret_cast<u32x4 *>(base) + vec;
     if (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
+}
+
+// The same two accesses for a 1 KiB piece: `piece` (first vector of the piece)
+// is the same for every lane of the wavefront, so base + piece is scalar
+// arithmetic and the only per-lane part of the address is the 32-bit lane
+// offset -- the scalar-base + vector-offset form of the memory instructions,
+// which needs no 64-bit address arithmetic and no address registers per stream.
+template <bool NT>
+__device__ __forceinline__ u32x4 load_piece(const uint8_t *base, uint64_t piece, uint32_t lane)
+{
+    const u32x4 *p = reinterpret_cast<const u32x4 *>(base) + piece;
+    if (NT) return __builtin_nontemporal_load(p + lane);
+    return p[lane];
+}
+
+template <bool NT>
+__device__ __forceinline__ void store_piece(uint8_t *base, uint64_t piece, uint32_t lane, u32x4 v)
+{
+    u32x4 *p = reinterpret_cast<u32x4 *>(base) + piece;
+    if (NT) __builtin_nontemporal_store(v, p + lane);
+    else p[lane] = v;
 }
 
 // c (x) each of the four bytes of d, given the five table words of c.
@@ -194,11 +216,12 @@ constexpr int kBatch = 4;  // streams whose loads are issued together
 // the streams in descending order instead of through the tables.
 template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, bool HORNER, class S>
 __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
-                                            int k, int accumulate, const uint64_t (&v)[U])
+                                            int k, int accumulate, const uint64_t (&piece)[U], uint32_t lane)
 {
+    // piece[u]: first vector of this wavefront's u-th piece (wavefront-uniform)
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = FULL || v[u] < s.nvec;
+    for (int u = 0; u < U; ++u) ok[u] = FULL || piece[u] + lane < s.nvec;
 
     Acc4 acc[M][U];
 #pragma unroll
@@ -210,7 +233,7 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
         for (int r = 0; r < M; ++r)
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) acc[r][u] = from_vec(load16<NT>(s.out[r], v[u]));
+                if (ok[u]) acc[r][u] = from_vec(load_piece<NT>(s.out[r], piece[u], lane));
     }
 
     int j = 0;
@@ -224,7 +247,7 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 x[b][u] = u32x4{0, 0, 0, 0};
-                if (ok[u]) x[b][u] = load16<NT>(src[b], v[u]);
+                if (ok[u]) x[b][u] = load_piece<NT>(src[b], piece[u], lane);
             }
 #pragma unroll
         for (int b = 0; b < kBatch; ++b) {
@@ -238,7 +261,7 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u] = u32x4{0, 0, 0, 0};
-            if (ok[u]) x[u] = load16<NT>(src, v[u]);
+            if (ok[u]) x[u] = load_piece<NT>(src, piece[u], lane);
         }
         if constexpr (HORNER) horner_step<M, U>(acc, x);
         else mac<M, ROW0_XOR, U>(acc, x, tab, j);
@@ -248,16 +271,22 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
     for (int r = 0; r < M; ++r)
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (ok[u]) store16<NT>(s.out[r], v[u], to_vec(acc[r][u]));
+            if (ok[u]) store_piece<NT>(s.out[r], piece[u], lane, to_vec(acc[r][u]));
 }
 
 // Occupancy the register allocator is asked to reach (wavefronts per SIMD).
 // The path is bandwidth-bound: many resident wavefronts with a few loads each
-// beat few wavefronts with long dependency-free instruction runs.
-template <int M, bool ROW0_XOR, int U>
+// beat few wavefronts with long dependency-free instruction runs.  The
+// allocator fills whatever budget it is given to hoist loads, and runs over
+// it into scratch memory for the widest variants, so those get a larger budget
+// (BATCH: pointers and lengths come from a descriptor in memory, which costs
+// a few registers more).
+template <int M, bool ROW0_XOR, int U, bool BATCH = false>
 constexpr int kWavesPerEu()
 {
-    return U == 1 ? 8 : 4;  // 64 resp. 128 VGPRs; every variant fits without spilling
+    if (U == 1) return (BATCH && M >= 2) ? 5 : 8;             // 102 resp. 64 VGPRs
+    if (!ROW0_XOR && (M >= 3 || (BATCH && M >= 2))) return 3;  // 170 VGPRs
+    return 4;                                                  // 128 VGPRs
 }
 
 // Work distribution.  A shard is cut into 1 KiB pieces (one 16-byte vector per
@@ -275,7 +304,9 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
                                                int k, int accumulate, uint32_t tiles_per_wg, bool last_wg)
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t wave = tid >> 6, lane = tid & 63u;
+    // the wavefront's index is the same in all of its lanes: say so, which keeps everything derived
+    // from it in scalar registers
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63u;
     constexpr uint32_t kPieces = (kThreads / 64) * U;  // pieces per tile
     const uint32_t nx_shift = s.nx_shift;
     const uint64_t nvec = s.nvec;
@@ -288,12 +319,12 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
         // first vector of the super-tile; nothing to do once it is past the end
         const uint64_t super_first = ((g * kPieces) << nx_shift) * 64;
         if (super_first >= nvec) break;
-        uint64_t v[U];
+        uint64_t piece[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << nx_shift) + r) << 6) + lane;
+        for (int u = 0; u < U; ++u) piece[u] = (((g * kPieces + wave * U + u) << nx_shift) + r) << 6;
         const uint64_t super_end = (((g + 1) * kPieces) << nx_shift) * 64;
-        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER>(s, tab, k, accumulate, v);
-        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER>(s, tab, k, accumulate, v);
+        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER>(s, tab, k, accumulate, piece, lane);
+        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER>(s, tab, k, accumulate, piece, lane);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
@@ -338,7 +369,7 @@ void horner_contig_kernel(const ApplyArgs a)
 typedef const BatchDesc __attribute__((address_space(4))) *ConstDesc;
 
 template <int M, bool ROW0_XOR, int U, bool NT>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U, true>(), 8)))
 void apply_batch_kernel(const BatchArgs a)
 {
     ConstDesc d = (ConstDesc)a.descs + blockIdx.y;

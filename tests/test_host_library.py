@@ -221,3 +221,29 @@ def test_product_and_oracle_share_nothing():
     product, checker = exported(gs.LIB_PATH), exported(oracle.build())
     assert not any(s.startswith("gso_") for s in product)
     assert not any(s.startswith("gs_") for s in checker)
+
+
+def test_no_kernel_spills_registers_to_scratch_memory(tmp_path):
+    """Every kernel of the library fits its register budget: the device assembly of each .hip file
+    reports private_segment_fixed_size 0 for every kernel (a spill would add scratch traffic and a
+    scratch allocation per wavefront to HBM-bound kernels)."""
+    import re
+    import subprocess
+    from paper_2605_00831_amd import build as hip_build
+    hips = [f for f in hip_build.SOURCES if f.endswith(".hip")]
+    procs = []
+    for f in hips:
+        out = str(tmp_path / (f + ".s"))
+        cmd = [hip_build.HIPCC] + [x for x in hip_build.FLAGS if x != "-fPIC"] + \
+              ["--offload-device-only", "-S", "-o", out, os.path.join(hip_build.CSRC, f)]
+        procs.append((f, out, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    kernels = 0
+    for f, out, p in procs:
+        log, _ = p.communicate()
+        assert p.returncode == 0, log
+        meta = re.findall(r"\.name:\s+(\S+)\n\s+\.private_segment_fixed_size:\s+(\d+)", open(out).read())
+        assert meta, f
+        kernels += len(meta)
+        spilled = [(n, int(b)) for n, b in meta if int(b) != 0]
+        assert not spilled, spilled
+    assert kernels > 100
