@@ -283,8 +283,15 @@ void gs_step_graph_destroy(gs_step_graph *g);
  * diagonal parity) and gs_reconstruct, with the same argument conventions,
  * except that shard_bytes must be a whole number of stripes (else GS_EINVAL).
  * The checkpoint / restore pipelines accept it when chunk_bytes is a whole
- * number of stripes.  It has no paged or grouped form: those entry points,
- * gs_code_matrix and gs_decode_matrix return GS_EINVAL for it.  A single lost shard other than the diagonal
+ * number of stripes.  The paged entry points (gs_encode_paged,
+ * gs_reconstruct_paged, gs_checkpoint_paged, gs_restore_paged) accept it when a
+ * cell is a page: page_bytes == cell_bytes (make the code with
+ * gs_make_rdp_code(k, page_bytes)), page_bytes >= 1024, and pages_per_shard a
+ * multiple of p-1 -- a stripe is then p-1 consecutive page slots of a plane,
+ * which is the contiguous definition applied to the shard's gathered byte
+ * stream; anything else gives GS_EINVAL.  It has no grouped form, and
+ * gs_code_matrix / gs_decode_matrix return GS_EINVAL for it.  A single lost
+ * shard other than the diagonal
  * parity is rebuilt from the row equations alone (the diagonal parity shard
  * is then not read and may be NULL). */
 #define GS_RDP_DEFAULT_CELL 32768

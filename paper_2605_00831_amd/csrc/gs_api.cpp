@@ -152,6 +152,67 @@ int rebuild_paged(const gs_code *code, const std::vector<uint8_t> &R, const std:
     return apply_matrix_paged(n_erased, k, R.data(), v, in.data(), out.data(), stream);
 }
 
+// RDP over a paged pool: a cell is a page, a stripe p-1 consecutive slots of a plane
+int check_rdp_paged(const gs_code *code, size_t page_bytes, int n_slots)
+{
+    if (page_bytes != code->rdp_cell || page_bytes < 1024) return GS_EINVAL;
+    if (n_slots % (code->rdp_encode.p - 1) != 0) return GS_EINVAL;
+    return GS_OK;
+}
+
+static int rdp_paged(const gs_code *code, const RdpPlan &plan, const PagedView &v, const PagedStream *parity_in,
+                     const PagedStream *parity_out, hipStream_t stream)
+{
+    const int k = code->k;
+    PagedStream shards[kRdpMaxDisks];
+    for (int j = 0; j < k; ++j) shards[j] = PagedStream{j, nullptr};
+    for (int i = 0; i < 2; ++i) {
+        bool produced = false;
+        for (int s : plan.outputs) produced = produced || s == k + i;
+        shards[k + i] = produced ? parity_out[i] : parity_in[i];
+        shards[k + i].table_row = -1;
+    }
+    // every dense buffer the plan touches must be there
+    for (int j = 0; j <= plan.p; ++j) {
+        const int s = plan.shard_of_disk[j];
+        if (s >= k && (shards[s].dense == nullptr || !aligned16(shards[s].dense))) return GS_EINVAL;
+    }
+    for (int s : plan.outputs)
+        if (s >= k && (shards[s].dense == nullptr || !aligned16(shards[s].dense))) return GS_EINVAL;
+    return hip_status(launch_rdp_paged(plan, v.plane_base, v.n_planes, v.page_bytes, v.pages_per_plane, v.table,
+                                       v.table_stride, v.n_slots, shards, current_shape(), stream));
+}
+
+// Encode over a paged view, any code kind: data shards are table rows 0..k-1,
+// parity goes to the dense streams parity_out[0..m).
+int encode_paged_view(const gs_code *code, const PagedView &v, const PagedStream *parity_out, hipStream_t stream)
+{
+    for (int i = 0; i < code->m; ++i)
+        if (parity_out[i].dense == nullptr || !aligned16(parity_out[i].dense)) return GS_EINVAL;
+    if (code->is_rdp()) {
+        const int rc = check_rdp_paged(code, v.page_bytes, v.n_slots);
+        if (rc != GS_OK) return rc;
+        return rdp_paged(code, code->rdp_encode, v, parity_out, parity_out, stream);
+    }
+    std::vector<PagedStream> in(code->k);
+    for (int j = 0; j < code->k; ++j) in[j] = PagedStream{j, nullptr};
+    return apply_matrix_paged(code->m, code->k, code->P.data(), v, in.data(), parity_out, stream);
+}
+
+// Rebuild over a paged view, any code kind.  R and surv come from decode_matrix
+// (unused for RDP, whose plan is made here).
+int rebuild_paged_view(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &surv, const PagedView &v,
+                       const PagedStream *parity_in, const PagedStream *parity_out, const int *erased, int n_erased,
+                       hipStream_t stream)
+{
+    if (!code->is_rdp()) return rebuild_paged(code, R, surv, v, parity_in, parity_out, erased, n_erased, stream);
+    const int rc = check_rdp_paged(code, v.page_bytes, v.n_slots);
+    if (rc != GS_OK) return rc;
+    RdpPlan plan;
+    if (!rdp_plan(code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+    return rdp_paged(code, plan, v, parity_in, parity_out, stream);
+}
+
 int check_erasures(const gs_code *code, const int *erased, int n_erased, std::vector<uint8_t> &lost)
 {
     const int n = code->k + code->m;
@@ -454,17 +515,13 @@ int gs_encode_paged(const gs_code *code, const void *const *plane_base, int n_pl
                     void *const *parity, void *stream)
 try {
     if (code == nullptr || parity == nullptr) return GS_EINVAL;
-    if (code->is_rdp()) return GS_EINVAL;  // RDP rows span the whole shard; it has no paged form
     bool empty;
     const int rc = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
     if (rc != GS_OK || empty) return rc;
-    for (int i = 0; i < code->m; ++i)
-        if (parity[i] == nullptr || !aligned16(parity[i])) return GS_EINVAL;
-    std::vector<PagedStream> in(code->k), out(code->m);
-    for (int j = 0; j < code->k; ++j) in[j] = PagedStream{j, nullptr};
+    std::vector<PagedStream> out(code->m);
     for (int i = 0; i < code->m; ++i) out[i] = PagedStream{-1, parity[i]};
     const PagedView v{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, pages_per_shard};
-    return apply_matrix_paged(code->m, code->k, code->P.data(), v, in.data(), out.data(), static_cast<hipStream_t>(stream));
+    return encode_paged_view(code, v, out.data(), static_cast<hipStream_t>(stream));
 }
 catch (...) {
     return caught();
@@ -475,19 +532,18 @@ int gs_reconstruct_paged(const gs_code *code, const void *const *plane_base, int
                          void *const *parity, const int *erased, int n_erased, void *stream)
 try {
     if (code == nullptr || parity == nullptr) return GS_EINVAL;
-    if (code->is_rdp()) return GS_EINVAL;
     bool empty;
     const int rc0 = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
     if (rc0 != GS_OK) return rc0;
     std::vector<uint8_t> R;
     std::vector<int> surv;
-    const int rc = decode_matrix(code, erased, n_erased, R, surv);
+    const int rc = code->is_rdp() ? shards_read(code, erased, n_erased, surv) : decode_matrix(code, erased, n_erased, R, surv);
     if (rc != GS_OK) return rc;
     if (n_erased == 0 || empty) return GS_OK;
     std::vector<PagedStream> dense(code->m);
     for (int i = 0; i < code->m; ++i) dense[i] = PagedStream{-1, parity[i]};
     const PagedView v{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, pages_per_shard};
-    return rebuild_paged(code, R, surv, v, dense.data(), dense.data(), erased, n_erased, static_cast<hipStream_t>(stream));
+    return rebuild_paged_view(code, R, surv, v, dense.data(), dense.data(), erased, n_erased, static_cast<hipStream_t>(stream));
 }
 catch (...) {
     return caught();

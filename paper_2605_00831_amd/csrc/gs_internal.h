@@ -57,6 +57,12 @@ int check_paged_geometry(const void *const *plane_base, int n_planes, size_t pag
                          const int32_t *table, int pages_per_shard, bool *empty);
 int apply_matrix_paged(int rows, int cols, const uint8_t *C, const PagedView &v, const PagedStream *in,
                        const PagedStream *out, hipStream_t stream);
+// the same two operations for any code kind (RDP included: a cell is a page)
+int check_rdp_paged(const gs_code *code, size_t page_bytes, int n_slots);
+int encode_paged_view(const gs_code *code, const PagedView &v, const PagedStream *parity_out, hipStream_t stream);
+int rebuild_paged_view(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &surv, const PagedView &v,
+                       const PagedStream *parity_in, const PagedStream *parity_out, const int *erased, int n_erased,
+                       hipStream_t stream);
 int rebuild_paged(const gs_code *code, const std::vector<uint8_t> &R, const std::vector<int> &surv, const PagedView &v,
                   const PagedStream *parity_in, const PagedStream *parity_out, const int *erased, int n_erased,
                   hipStream_t stream);

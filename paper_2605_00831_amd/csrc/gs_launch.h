@@ -81,4 +81,12 @@ struct RdpPlan;
 hipError_t launch_rdp(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
                       size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
 
+// RDP over a paged pool: a cell is one page (a power of two >= 1 KiB), a stripe
+// p-1 consecutive page slots of a plane (n_slots a multiple of p-1).  shards[]
+// is indexed by shard id like the contiguous form; each is a table row or a
+// dense buffer laid out [plane][slot][page].
+hipError_t launch_rdp_paged(const RdpPlan &plan, const void *const *plane_base_dev, int n_planes, size_t page_bytes,
+                            int64_t pages_per_plane, const int32_t *table_dev, int table_stride, int n_slots,
+                            const PagedStream *shards, const LaunchShape &shape, hipStream_t stream);
+
 }  // namespace gs

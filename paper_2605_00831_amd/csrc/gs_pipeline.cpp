@@ -363,15 +363,21 @@ struct PagedChunks {
 static int paged_chunks(const gs_pipe *p, const void *const *plane_base, int n_planes, size_t page_bytes,
                         int64_t pages_per_plane, const int32_t *table, int pages_per_shard, PagedChunks &g)
 {
-    if (p->code->is_rdp()) return GS_EINVAL;
     bool empty;
     const int rc = check_paged_geometry(plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, &empty);
     g = PagedChunks{plane_base, n_planes, page_bytes, pages_per_plane, table, pages_per_shard, 0};
     if (rc != GS_OK || empty) return rc;
-    // a staging buffer holds whole page slots of every plane
+    // a staging buffer holds whole page slots of every plane -- whole stripes of them for RDP
     const size_t slot_row = static_cast<size_t>(n_planes) * page_bytes;
-    if (p->chunk_bytes < slot_row) return GS_EINVAL;
-    g.spc = static_cast<int>(std::min<size_t>(p->chunk_bytes / slot_row, static_cast<size_t>(pages_per_shard)));
+    size_t spc = std::min<size_t>(p->chunk_bytes / slot_row, static_cast<size_t>(pages_per_shard));
+    if (p->code->is_rdp()) {
+        const int rc2 = check_rdp_paged(p->code, page_bytes, pages_per_shard);
+        if (rc2 != GS_OK) return rc2;
+        const size_t rows = static_cast<size_t>(p->code->rdp_encode.p - 1);
+        spc = spc / rows * rows;
+    }
+    if (spc == 0) return GS_EINVAL;
+    g.spc = static_cast<int>(spc);
     return GS_OK;
 }
 
@@ -390,11 +396,11 @@ try {
         gs_pipe *p;
         PagedChunks g;
         void *const *host;
-        std::vector<gs::PagedStream> in, out;
+        std::vector<gs::PagedStream> out;
         int compute(size_t c, int slot, hipStream_t cs) override
         {
             for (size_t i = 0; i < out.size(); ++i) out[i] = gs::PagedStream{-1, p->slot_buf(slot, static_cast<int>(i))};
-            return apply_matrix_paged(p->code->m, p->code->k, p->code->P.data(), g.view(c), in.data(), out.data(), cs);
+            return encode_paged_view(p->code, g.view(c), out.data(), cs);
         }
         hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
         {
@@ -407,9 +413,7 @@ try {
     ops.p = p;
     ops.g = g;
     ops.host = host_parity;
-    ops.in.resize(p->code->k);
     ops.out.resize(p->code->m);
-    for (int j = 0; j < p->code->k; ++j) ops.in[j] = gs::PagedStream{j, nullptr};
     ops.n_chunks = (static_cast<size_t>(pages_per_shard) + g.spc - 1) / g.spc;
     return run_checkpoint(p, ops, static_cast<hipStream_t>(compute_stream));
 }
@@ -428,8 +432,9 @@ try {
     if (rc != GS_OK) return rc;
     const int k = p->code->k, m = p->code->m;
     std::vector<uint8_t> R;
-    std::vector<int> surv;
-    const int rc1 = decode_matrix(p->code, erased, n_erased, R, surv);
+    std::vector<int> surv;  // the shards the rebuild reads
+    const int rc1 = p->code->is_rdp() ? shards_read(p->code, erased, n_erased, surv)
+                                      : decode_matrix(p->code, erased, n_erased, R, surv);
     if (rc1 != GS_OK) return rc1;
     if (n_erased == 0 || g.spc == 0) return GS_OK;
     std::vector<int> rows_in;
@@ -464,7 +469,7 @@ try {
                     pout[erased[x] - k] = gs::PagedStream{-1, static_cast<uint8_t *>(parity_out[erased[x] - k]) +
                                                                   c * static_cast<size_t>(g.spc) * g.page_bytes,
                                                           static_cast<size_t>(g.pps) * g.page_bytes};
-            return rebuild_paged(p->code, *R, *surv, g.view(c), pin.data(), pout.data(), erased, n_erased, cs);
+            return rebuild_paged_view(p->code, *R, *surv, g.view(c), pin.data(), pout.data(), erased, n_erased, cs);
         }
         hipError_t copy(size_t c, int slot, int i, hipStream_t s) override
         {

@@ -116,6 +116,211 @@ __global__ __launch_bounds__(kThreads) void rdp_kernel(const RdpArgs a)
     else rdp_tile<P, E, W, false>(a, v);
 }
 
+// ---- the same two steps over a paged pool ---------------------------------------
+// A cell is one page, a stripe p-1 consecutive page slots of a plane; data
+// disks are rows of the block table, parity disks dense buffers laid out
+// [plane][slot][page] (on either side: a lost data shard is rebuilt into the
+// pages of its table row).  Pages are at least 1 KiB, so the 64 lanes of a
+// piece share one cell: stripe, slot and page id are wavefront-uniform and the
+// table entries come through scalar loads.  A page id outside the plane reads
+// as zeros and is not written.
+struct RdpPagedArgs {
+    const uint8_t *const *plane_base;   // device array [n_planes]
+    const int32_t *table;               // device; row stride table_stride, first slot of the window
+    const uint8_t *dense[kRdpMaxDisks]; // stripe disks 0..p that are dense buffers (else nullptr)
+    int32_t row[kRdpMaxDisks];          // table row of a paged disk, -1 otherwise
+    uint32_t stride[kRdpMaxDisks];      // dense: vectors from plane to plane
+    uint8_t *out_dense[2];
+    int32_t out_row[2];
+    uint32_t out_stride[2];
+    uint32_t syndrome_mask[2 * kRdpMaxRows];
+    uint64_t pages_per_plane;
+    uint64_t nvb;            // vectors per row summed over the stripes of one plane (multiple of 64)
+    uint32_t table_stride;
+    uint32_t nx_shift;
+    uint32_t cell_shift;     // log2 of the vectors per cell (= per page)
+    uint32_t needs_diagonals;
+};
+
+typedef const int32_t __attribute__((address_space(4))) *ConstTableRdp;
+
+template <int P, int E, int W>
+__global__ __launch_bounds__(kThreads) void rdp_paged_kernel(const RdpPagedArgs a)
+{
+    typedef typename VecOf<W>::type vec;
+    constexpr int kRows = P - 1;
+    constexpr uint32_t kPieces = kThreads / 64;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63u;
+    const uint32_t plane = blockIdx.y;
+    const uint64_t t = blockIdx.x;
+    const uint64_t g = t >> a.nx_shift, r = t & ((1ull << a.nx_shift) - 1);
+    const uint64_t piece = (((g * kPieces + wave) << a.nx_shift) + r) << 6;  // first vector of this wavefront's piece
+    if (piece >= a.nvb) return;  // nvb is a multiple of 64: a piece is inside the plane or outside as a whole
+    const uint64_t vpc = 1ull << a.cell_shift;
+    const uint64_t stripe = piece >> a.cell_shift;
+    const uint64_t off = (piece & (vpc - 1)) + lane;  // this lane's vector inside its cell
+    const uint8_t *pbase = a.plane_base[plane];
+    const bool diagonals = a.needs_diagonals != 0;
+
+    // page of table row `trow` at `slot`, or -1
+    auto page_of = [&](int32_t trow, uint64_t slot) -> int64_t {
+        const int64_t page = ((ConstTableRdp)a.table)[static_cast<uint64_t>(trow) * a.table_stride + slot];
+        return static_cast<uint64_t>(page) < a.pages_per_plane ? page : -1;
+    };
+
+    vec sr[kRows], sd[kRows];
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        sr[i] = vec(0);
+        sd[i] = vec(0);
+    }
+#pragma unroll
+    for (int j = 0; j <= P; ++j) {
+        const int32_t trow = a.row[j];
+        const uint8_t *dense = a.dense[j];
+        if (trow < 0 && dense == nullptr) continue;   // disk absent (imaginary, missing, or not needed)
+        if (j == P && !diagonals) continue;
+        vec x[kRows];
+#pragma unroll
+        for (int row = 0; row < kRows; ++row) {
+            const uint64_t slot = stripe * kRows + row;
+            if (trow >= 0) {
+                const int64_t page = page_of(trow, slot);
+                const vec *src = reinterpret_cast<const vec *>(pbase) + (page < 0 ? 0 : static_cast<uint64_t>(page)) * vpc + off;
+                const vec val = __builtin_nontemporal_load(src);
+                x[row] = page < 0 ? vec(0) : val;
+            } else {
+                const vec *src = reinterpret_cast<const vec *>(dense) + static_cast<uint64_t>(plane) * a.stride[j] + slot * vpc + off;
+                x[row] = __builtin_nontemporal_load(src);
+            }
+        }
+        if (j < P) {
+#pragma unroll
+            for (int row = 0; row < kRows; ++row) sr[row] ^= x[row];
+            if (diagonals) {
+#pragma unroll
+                for (int row = 0; row < kRows; ++row) {
+                    constexpr int kNone = P - 1;
+                    const int d = (row + j) % P;
+                    if (d != kNone) sd[d] ^= x[row];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < kRows; ++d) sd[d] ^= x[d];
+        }
+    }
+
+#pragma unroll
+    for (int o = 0; o < E * kRows; ++o) {
+        const uint32_t m = a.syndrome_mask[o];
+        vec acc = vec(0);
+#pragma unroll
+        for (int i = 0; i < kRows; ++i)
+            if (m >> i & 1u) acc ^= sr[i];
+        if (diagonals) {
+#pragma unroll
+            for (int d = 0; d < kRows; ++d)
+                if (m >> (kRows + d) & 1u) acc ^= sd[d];
+        }
+        const int x = o / kRows;
+        const uint64_t slot = stripe * kRows + (o % kRows);
+        const int32_t trow = a.out_row[x];
+        if (trow >= 0) {
+            const int64_t page = page_of(trow, slot);
+            if (page < 0) continue;
+            vec *dst = reinterpret_cast<vec *>(const_cast<uint8_t *>(pbase)) + static_cast<uint64_t>(page) * vpc + off;
+            __builtin_nontemporal_store(acc, dst);
+        } else {
+            vec *dst = reinterpret_cast<vec *>(a.out_dense[x]) + static_cast<uint64_t>(plane) * a.out_stride[x] + slot * vpc + off;
+            __builtin_nontemporal_store(acc, dst);
+        }
+    }
+}
+
+template <int P, int W>
+static hipError_t launch_paged_p(const RdpPagedArgs &a, int n_out, dim3 grid, hipStream_t stream)
+{
+    if (n_out == 1) hipLaunchKernelGGL((rdp_paged_kernel<P, 1, W>), grid, dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL((rdp_paged_kernel<P, 2, W>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rdp_paged(const RdpPlan &plan, const void *const *plane_base_dev, int n_planes, size_t page_bytes,
+                            int64_t pages_per_plane, const int32_t *table_dev, int table_stride, int n_slots,
+                            const PagedStream *shards, const LaunchShape &shape, hipStream_t stream)
+{
+    const int rows = plan.p - 1;
+    const int n_out = static_cast<int>(plan.outputs.size());
+    if (n_out < 1 || n_out > 2 || plan.p > kRdpMaxPrime) return hipErrorInvalidValue;
+    if (page_bytes < 1024 || (page_bytes & (page_bytes - 1)) != 0) return hipErrorInvalidValue;
+    if (n_planes < 1 || n_planes > 65535 || n_slots < 1 || n_slots % rows != 0 || table_stride < n_slots ||
+        pages_per_plane < 1)
+        return hipErrorInvalidValue;
+    (void)shape;
+    constexpr int w = 2;  // 8-byte vectors, as in the contiguous kernel
+    const uint64_t vec_bytes = 4u * w;
+    RdpPagedArgs a;
+    const uint64_t packed = static_cast<uint64_t>(n_slots) * page_bytes / vec_bytes;  // dense: vectors per plane
+    auto stride_of = [&](const PagedStream &s, uint32_t &out) {
+        const uint64_t v = s.plane_stride_bytes == 0 ? packed : s.plane_stride_bytes / vec_bytes;
+        if ((s.plane_stride_bytes % vec_bytes) != 0 || v < packed || v >= (1ull << 32)) return false;
+        out = static_cast<uint32_t>(v);
+        return true;
+    };
+    for (int j = 0; j < kRdpMaxDisks; ++j) {
+        a.dense[j] = nullptr;
+        a.row[j] = -1;
+        a.stride[j] = 0;
+        if (j > plan.p || plan.shard_of_disk[j] < 0) continue;
+        const PagedStream &s = shards[plan.shard_of_disk[j]];
+        if (s.table_row >= 0) {
+            a.row[j] = s.table_row;
+        } else {
+            if (s.dense == nullptr || !stride_of(s, a.stride[j])) return hipErrorInvalidValue;
+            a.dense[j] = static_cast<const uint8_t *>(s.dense);
+        }
+    }
+    for (int x = 0; x < 2; ++x) {
+        a.out_dense[x] = nullptr;
+        a.out_row[x] = -1;
+        a.out_stride[x] = 0;
+        if (x >= n_out) continue;
+        const PagedStream &s = shards[plan.outputs[x]];
+        if (s.table_row >= 0) {
+            a.out_row[x] = s.table_row;
+        } else {
+            if (s.dense == nullptr || !stride_of(s, a.out_stride[x])) return hipErrorInvalidValue;
+            a.out_dense[x] = static_cast<uint8_t *>(const_cast<void *>(s.dense));
+        }
+    }
+    for (int i = 0; i < 2 * kRdpMaxRows; ++i)
+        a.syndrome_mask[i] = i < static_cast<int>(plan.syndrome_mask.size()) ? plan.syndrome_mask[i] : 0u;
+    a.needs_diagonals = plan.needs_diagonals ? 1u : 0u;
+    a.plane_base = reinterpret_cast<const uint8_t *const *>(plane_base_dev);
+    a.table = table_dev;
+    a.table_stride = static_cast<uint32_t>(table_stride);
+    a.pages_per_plane = static_cast<uint64_t>(pages_per_plane < (1ll << 31) ? pages_per_plane : (1ll << 31));
+    a.cell_shift = 0;
+    while ((vec_bytes << a.cell_shift) < page_bytes) ++a.cell_shift;
+    a.nvb = static_cast<uint64_t>(n_slots / rows) << a.cell_shift;
+    uint32_t nx_shift = 5u;
+    const uint64_t tile = kThreads;
+    while (nx_shift > 0 && (tile << nx_shift) > a.nvb) --nx_shift;
+    const uint64_t super = tile << nx_shift;
+    const uint64_t tiles = ((a.nvb + super - 1) / super) << nx_shift;
+    if (tiles >= (1ull << 23)) return hipErrorInvalidValue;
+    a.nx_shift = nx_shift;
+    const dim3 grid(static_cast<uint32_t>(tiles ? tiles : 1), static_cast<uint32_t>(n_planes));
+#define GS_RDP_PAGED_CASE(P_) case P_: return launch_paged_p<P_, w>(a, n_out, grid, stream);
+    switch (plan.p) {
+        GS_RDP_PAGED_CASE(3) GS_RDP_PAGED_CASE(5) GS_RDP_PAGED_CASE(7) GS_RDP_PAGED_CASE(11) GS_RDP_PAGED_CASE(13)
+        GS_RDP_PAGED_CASE(17)
+        default: return hipErrorInvalidValue;
+    }
+#undef GS_RDP_PAGED_CASE
+}
+
 template <int P, int W>
 static hipError_t launch_p(const RdpArgs &a, int n_out, dim3 grid, hipStream_t stream)
 {

@@ -110,6 +110,15 @@ int main(void)
                     EXPECT(gs_reconstruct(code, fake, miss, 2, stripe + 16, NULL) == GS_EINVAL);
                     uint8_t dummy[4];
                     EXPECT(gs_code_matrix(code, dummy) == GS_EINVAL);
+                    /* paged RDP: a cell must be a page and the shard whole stripes of slots */
+                    EXPECT(gs_encode_paged(code, (const void *const *)fake[0], 3, cell, 1 << 20, (const int32_t *)fake[1], 4 * (p - 1),
+                                           fake + k, NULL) == GS_EHIP);
+                    EXPECT(gs_encode_paged(code, (const void *const *)fake[0], 3, cell, 1 << 20, (const int32_t *)fake[1], 4 * (p - 1) + 1,
+                                           fake + k, NULL) == GS_EINVAL);
+                    EXPECT(gs_encode_paged(code, (const void *const *)fake[0], 3, 2048, 1 << 20, (const int32_t *)fake[1], 4 * (p - 1),
+                                           fake + k, NULL) == GS_EINVAL);
+                    EXPECT(gs_reconstruct_paged(code, (const void *const *)fake[0], 3, cell, 1 << 20, (const int32_t *)fake[1],
+                                                4 * (p - 1), fake + k, miss, 2, NULL) == GS_EHIP);
                 }
                 /* objects that need device memory cannot be made here, and must not leak or crash */
                 gs_pipe *pipe = (gs_pipe *)fake[0];

@@ -170,3 +170,108 @@ def test_rdp_checkpoint_and_restore_pipelines(gs):
     with pytest.raises(gs.GsError):
         gs.gs_pipe_create(code, stripe + 16, 2)        # chunks must hold whole stripes
     gs.gs_pipe_destroy(pipe)
+
+
+# ---- RDP over a paged pool: a cell is a page, a stripe p-1 consecutive page slots of a plane ----
+
+def rdp_paged_case(k, n_planes, page, stripes, seed, spare=3):
+    p = oracle.rdp_prime(k)
+    pps = stripes * (p - 1)
+    ppp = k * pps + spare
+    planes_np = [inputs.kv_bytes_np(seed + pl, ppp * page, "bf16", 1.0) for pl in range(n_planes)]
+    table_np = inputs.block_table_np(seed, k, pps, ppp)
+    # shard j's byte stream: for each plane, its pages in table order
+    gathered = [np.concatenate([pl.reshape(ppp, page)[table_np[j]].reshape(-1) for pl in planes_np]) for j in range(k)]
+    want = oracle.rdp_encode(gathered, page)      # the contiguous definition on the gathered streams
+    return p, pps, ppp, planes_np, table_np, want
+
+
+@pytest.mark.parametrize("k,n_planes,page,stripes", [
+    (4, 3, 2048, 5),       # p = 5: token slots of 2 KiB
+    (8, 2, 1024, 7),       # p = 11
+    (2, 1, 4096, 1),       # p = 3, a single stripe
+    (16, 2, 1024, 3),      # p = 17
+    (3, 2, 32768, 2),      # p = 5 with an imaginary disk, 16-token blocks
+])
+def test_rdp_paged_encode_and_every_erasure_pattern(gs, k, n_planes, page, stripes):
+    p, pps, ppp, planes_np, table_np, want = rdp_paged_case(k, n_planes, page, stripes, 700 + k)
+    S = n_planes * pps * page
+    code = gs.gs_make_rdp_code(k, page)
+    pool = dev(np.concatenate(planes_np))
+    base = torch.tensor([pool.data_ptr() + pl * ppp * page for pl in range(n_planes)], dtype=torch.int64, device="cuda")
+    table = torch.from_numpy(table_np).cuda()
+    par = [out_buf(S), out_buf(S)]
+    gs.gs_encode_paged(code, base, n_planes, page, ppp, table, pps, par)
+    torch.cuda.synchronize()
+    check(par[0], want[0])
+    check(par[1], want[1])
+    assert np.array_equal(pool.cpu().numpy(), np.concatenate(planes_np))
+    original = np.concatenate(planes_np)
+    pats = list(itertools.combinations(range(k + 2), 1)) + list(itertools.combinations(range(k + 2), 2))
+    if len(pats) > 40:
+        rng = np.random.default_rng(k)
+        pats = [pats[i] for i in rng.choice(len(pats), 40, replace=False)]
+    for pat in pats:
+        broken = [pl.copy() for pl in planes_np]
+        for r in pat:
+            if r < k:
+                for pl in broken:
+                    pl.reshape(ppp, page)[table_np[r]] = 0xA5
+        pool.copy_(torch.from_numpy(np.concatenate(broken)))
+        work = []
+        for i in range(2):
+            b = out_buf(S)
+            if k + i not in pat:
+                b[:S] = torch.from_numpy(want[i])
+            work.append(b)
+        # a single lost shard other than the diagonal parity does not read the diagonal parity
+        if len(pat) == 1 and pat[0] != k + 1:
+            work[1][:S] = 0x33
+        gs.gs_reconstruct_paged(code, base, n_planes, page, ppp, table, pps, work, list(pat))
+        torch.cuda.synchronize()
+        assert np.array_equal(pool.cpu().numpy(), original), pat
+        for i in range(2):
+            if k + i in pat:
+                check(work[i], want[i])
+
+
+def test_rdp_paged_refusals_and_pipelines(gs):
+    k, n_planes, page, stripes = 4, 3, 2048, 6
+    p, pps, ppp, planes_np, table_np, want = rdp_paged_case(k, n_planes, page, stripes, 811)
+    S = n_planes * pps * page
+    pool = dev(np.concatenate(planes_np))
+    base = torch.tensor([pool.data_ptr() + pl * ppp * page for pl in range(n_planes)], dtype=torch.int64, device="cuda")
+    table = torch.from_numpy(table_np).cuda()
+    par = [out_buf(S), out_buf(S)]
+    code = gs.gs_make_rdp_code(k, page)
+    other = gs.gs_make_rdp_code(k, 4096)
+    for bad in (lambda: gs.gs_encode_paged(other, base, n_planes, page, ppp, table, pps, par),         # cell != page
+                lambda: gs.gs_encode_paged(code, base, n_planes, page, ppp, table, pps - 1, par)):    # not whole stripes
+        with pytest.raises(gs.GsError) as e:
+            bad()
+        assert e.value.status == gs.GS_EINVAL
+    # the paged pipelines: chunks of two stripes of every plane (the last chunk shorter)
+    pipe = gs.gs_pipe_create(code, (p - 1) * page * n_planes * 2, 2)
+    host = [torch.full((S + 64,), 0x5A, dtype=torch.uint8).pin_memory() for _ in range(2)]
+    gs.gs_checkpoint_paged(pipe, base, n_planes, page, ppp, table, pps, host)
+    gs.gs_pipe_sync(pipe)
+    for i in range(2):
+        got = host[i].numpy()
+        assert np.array_equal(got[:S], want[i]) and (got[S:] == 0x5A).all()
+    original = np.concatenate(planes_np)
+    for pat in ((1, 3), (0, 5), (4,), (2,)):
+        broken = [pl.copy() for pl in planes_np]
+        for r in pat:
+            if r < k:
+                for pl in broken:
+                    pl.reshape(ppp, page)[table_np[r]] = 0xA5
+        pool.copy_(torch.from_numpy(np.concatenate(broken)))
+        out = [out_buf(S), out_buf(S)]
+        gs.gs_restore_paged(pipe, base, n_planes, page, ppp, table, pps, host, list(pat), parity_out=out)
+        gs.gs_pipe_sync(pipe)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool.cpu().numpy(), original), pat
+        for i in range(2):
+            if k + i in pat:
+                check(out[i], want[i])
+    gs.gs_pipe_destroy(pipe)
