@@ -717,6 +717,29 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
                           "encode_ms": round(enc, 4), "encode_hbm_frac": round((k + 2) * Sr / enc / 1e6 / HBM_PEAK_GBPS, 4),
                           "reconstruct_ms": round(rec, 4),
                           "reconstruct_hbm_frac": round((k + len(erased[:2])) * Sr / rec / 1e6 / HBM_PEAK_GBPS, 4)}
+            # the same encode through the paged entry point (one plane over the arena, identity table,
+            # a page = a cell) and as one grouped launch over 16 chunks of whole stripes
+            cell = gs.gs_rdp_cell_bytes(rdp)
+            lo = min(d.data_ptr() for d in data)
+            if all((d.data_ptr() - lo) % cell == 0 for d in data):
+                pps = Sr // cell
+                tab = torch.stack([torch.arange(pps, dtype=torch.int32, device=dev) + (d.data_ptr() - lo) // cell
+                                   for d in data]).contiguous()
+                span = max(d.data_ptr() for d in data) + Sr - lo
+                one_plane = torch.tensor([lo], dtype=torch.int64, device=dev)
+                pg = ev_ms(lambda: gs.gs_encode_paged(rdp, one_plane, 1, cell, span // cell, tab, pps, parity[:2]))
+                res["rdp"]["encode_paged_identity_ms"] = round(pg, 4)
+                res["rdp"]["encode_paged_identity_hbm_frac"] = round((k + 2) * Sr / pg / 1e6 / HBM_PEAK_GBPS, 4)
+            n_g = 16
+            per = Sr // stripe // n_g * stripe
+            if per:
+                batch = gs.gs_batch_create(rdp, n_g)
+                gd = [[d[c * per:(c + 1) * per] for d in data] for c in range(n_g)]
+                gp = [[q[c * per:(c + 1) * per] for q in parity[:2]] for c in range(n_g)]
+                gr = ev_ms(lambda: gs.gs_encode_batch(batch, gd, gp, [per] * n_g))
+                res["rdp"]["encode_grouped_16_chunks_ms"] = round(gr, 4)
+                res["rdp"]["encode_grouped_16_chunks_hbm_frac"] = round((k + 2) * per * n_g / gr / 1e6 / HBM_PEAK_GBPS, 4)
+                gs.gs_batch_destroy(batch)
             log("[bench] rdp: " + json.dumps(res["rdp"]))
             gs.gs_encode(code, data, parity, S)   # put the Reed-Solomon parity back
             torch.cuda.synchronize()

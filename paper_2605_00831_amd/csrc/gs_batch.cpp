@@ -72,6 +72,55 @@ static int run_batch(gs_batch *b, int rows, const uint8_t *C, int n, const void 
     return GS_OK;
 }
 
+// The RDP form of run_batch: one plan for all chunks; shards is chunk-major with k+2 entries per chunk
+// (data, row parity, diagonal parity), every chunk whole stripes.
+static int run_rdp_batch(gs_batch *b, const RdpPlan &plan, int n, const void *const *shards, const size_t *bytes,
+                         hipStream_t stream)
+{
+    const gs_code *code = b->code;
+    const int width = code->k + 2;
+    const size_t stripe = code->rdp_cell * static_cast<size_t>(plan.p - 1);
+    const LaunchShape shape = current_shape();
+    size_t max_bytes = 0;
+    for (int c = 0; c < n; ++c) {
+        if (bytes[c] % stripe != 0 || bytes[c] >= (1ull << 36)) return GS_EINVAL;
+        max_bytes = std::max(max_bytes, bytes[c]);
+    }
+    if (max_bytes == 0) return GS_OK;
+    // pointers of every chunk that has bytes: the shards the plan reads and the ones it writes
+    for (int c = 0; c < n; ++c) {
+        if (bytes[c] == 0) continue;
+        const void *const *row = shards + static_cast<size_t>(c) * width;
+        const void *in[kRdpMaxDisks];
+        void *out[2];
+        int n_in = 0, n_out = 0;
+        for (int j = 0; j <= plan.p; ++j) {
+            const int sh = plan.shard_of_disk[j];
+            if (sh < 0) continue;
+            if (row[sh] == nullptr || !aligned16(row[sh])) return GS_EINVAL;
+            in[n_in++] = row[sh];
+        }
+        for (int sh : plan.outputs) {
+            if (row[sh] == nullptr || !aligned16(row[sh])) return GS_EINVAL;
+            out[n_out++] = const_cast<void *>(row[sh]);
+        }
+        if (outputs_overlap(in, n_in, out, n_out, bytes[c])) return GS_EINVAL;
+    }
+    const unsigned slot = b->next % kRing;
+    if (b->used[slot]) GS_TRY(hipEventSynchronize(b->done[slot]));
+    uint8_t *hslot = b->host + static_cast<size_t>(slot) * b->slot_bytes;
+    uint8_t *dslot = b->dev + static_cast<size_t>(slot) * b->slot_bytes;
+    for (int c = 0; c < n; ++c)
+        if (!write_rdp_batch_desc(hslot, c, plan, shards + static_cast<size_t>(c) * width, bytes[c], code->rdp_cell, shape))
+            return GS_EINVAL;
+    GS_TRY(hipMemcpyAsync(dslot, hslot, static_cast<size_t>(n) * batch_desc_bytes(), hipMemcpyHostToDevice, stream));
+    GS_TRY(launch_rdp_batch(plan, dslot, n, max_bytes, code->rdp_cell, shape, stream));
+    GS_TRY(hipEventRecord(b->done[slot], stream));
+    b->used[slot] = true;
+    ++b->next;
+    return GS_OK;
+}
+
 // chunk c runs on pool stream c mod n; the pool streams start after everything
 // already enqueued on `stream`, and `stream` continues after all of them
 template <typename PerChunk>
@@ -110,7 +159,7 @@ try {
     if (out == nullptr) return GS_EINVAL;
     *out = nullptr;
     if (code == nullptr || max_chunks < 1 || max_chunks > 65535) return GS_EINVAL;
-    if (code->is_rdp() || code->k > kLaunchMaxK || code->m > kLaunchMaxM) return GS_EINVAL;
+    if (code->k > kLaunchMaxK || code->m > kLaunchMaxM) return GS_EINVAL;
     gs_batch *b = new (std::nothrow) gs_batch;
     if (b == nullptr) return GS_ENOMEM;
     b->code = code;
@@ -139,6 +188,15 @@ try {
     if (n_chunks == 0) return GS_OK;
     if (data == nullptr || parity == nullptr || shard_bytes == nullptr) return GS_EINVAL;
     const int k = b->code->k, m = b->code->m;
+    if (b->code->is_rdp()) {
+        // one stripe view per chunk: k data shards, then the two parity shards
+        std::vector<const void *> shards(static_cast<size_t>(n_chunks) * (k + 2));
+        for (int c = 0; c < n_chunks; ++c) {
+            for (int j = 0; j < k; ++j) shards[static_cast<size_t>(c) * (k + 2) + j] = data[c * k + j];
+            for (int i = 0; i < 2; ++i) shards[static_cast<size_t>(c) * (k + 2) + k + i] = parity[c * 2 + i];
+        }
+        return run_rdp_batch(b, b->code->rdp_encode, n_chunks, shards.data(), shard_bytes, static_cast<hipStream_t>(stream));
+    }
     for (int c = 0; c < n_chunks; ++c) {
         if (shard_bytes[c] == 0) continue;
         for (int j = 0; j < k; ++j)
@@ -159,6 +217,16 @@ int gs_reconstruct_batch(gs_batch *b, int n_chunks, void *const *shards, const i
                          const size_t *shard_bytes, void *stream)
 try {
     if (b == nullptr || n_chunks < 0 || n_chunks > b->max_chunks) return GS_EINVAL;
+    if (b->code->is_rdp()) {
+        std::vector<uint8_t> lost;
+        const int rcr = check_erasures(b->code, erased, n_erased, lost);
+        if (rcr != GS_OK) return rcr;
+        if (n_chunks == 0 || n_erased == 0) return GS_OK;
+        if (shards == nullptr || shard_bytes == nullptr) return GS_EINVAL;
+        RdpPlan plan;
+        if (!rdp_plan(b->code->k, erased, n_erased, plan)) return GS_ESINGULAR;
+        return run_rdp_batch(b, plan, n_chunks, shards, shard_bytes, static_cast<hipStream_t>(stream));
+    }
     std::vector<uint8_t> R;
     std::vector<int> surv;
     const int rc = decode_matrix(b->code, erased, n_erased, R, surv);

@@ -81,6 +81,22 @@ struct RdpPlan;
 hipError_t launch_rdp(const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
                       size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
 
+// RDP, many chunks in one launch: descriptors of kBatchDescBytes each, written
+// with write_rdp_batch_desc() (false if a chunk is not whole stripes) and copied
+// to the device by the caller; one plan for all chunks.
+struct RdpBatchDesc {
+    const uint8_t *disk[18];  // stripe disks 0..p, nullptr = not read
+    uint8_t *out[2];
+    uint64_t nvb;             // 8-byte vectors per row summed over the chunk's stripes
+    uint32_t nx_shift;
+    uint32_t pad;
+};
+static_assert(sizeof(RdpBatchDesc) == kBatchDescBytes, "both descriptor kinds share the batch object's slots");
+bool write_rdp_batch_desc(void *slot, int idx, const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
+                          size_t cell_bytes, const LaunchShape &shape);
+hipError_t launch_rdp_batch(const RdpPlan &plan, const void *descs_dev, int n_chunks, size_t max_bytes,
+                            size_t cell_bytes, const LaunchShape &shape, hipStream_t stream);
+
 // RDP over a paged pool: a cell is one page (a power of two >= 1 KiB), a stripe
 // p-1 consecutive page slots of a plane (n_slots a multiple of p-1).  shards[]
 // is indexed by shard id like the contiguous form; each is a table row or a

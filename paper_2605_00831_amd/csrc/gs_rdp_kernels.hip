@@ -116,6 +116,109 @@ __global__ __launch_bounds__(kThreads) void rdp_kernel(const RdpArgs a)
     else rdp_tile<P, E, W, false>(a, v);
 }
 
+// ---- many chunks in one launch --------------------------------------------------
+// blockIdx.y is the chunk; its shard pointers and length come from a descriptor
+// in device memory (scalar loads), the plan is the same for every chunk.
+struct RdpBatchArgs {
+    const RdpBatchDesc *descs;
+    uint32_t syndrome_mask[2 * kRdpMaxRows];
+    uint32_t cell_shift;
+    uint32_t needs_diagonals;
+};
+
+typedef const RdpBatchDesc __attribute__((address_space(4))) *ConstRdpDesc;
+
+template <int P, int E, int W>
+__global__ __launch_bounds__(kThreads) void rdp_batch_kernel(const RdpBatchArgs b)
+{
+    ConstRdpDesc d = (ConstRdpDesc)b.descs + blockIdx.y;
+    RdpArgs a;
+#pragma unroll
+    for (int j = 0; j < kRdpMaxDisks; ++j) a.disk[j] = j <= P ? d->disk[j] : nullptr;
+    a.out[0] = d->out[0];
+    a.out[1] = d->out[1];
+#pragma unroll
+    for (int i = 0; i < 2 * kRdpMaxRows; ++i) a.syndrome_mask[i] = b.syndrome_mask[i];
+    a.nvb = d->nvb;
+    a.nx_shift = d->nx_shift;
+    a.cell_shift = b.cell_shift;
+    a.needs_diagonals = b.needs_diagonals;
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    constexpr uint32_t kPieces = kThreads / 64;
+    const uint64_t t = blockIdx.x;
+    const uint64_t g = t >> a.nx_shift, r = t & ((1ull << a.nx_shift) - 1);
+    if (((g * kPieces) << a.nx_shift) * 64 >= a.nvb) return;
+    const uint64_t v = ((((g * kPieces + wave) << a.nx_shift) + r) << 6) + lane;
+    if ((((g + 1) * kPieces) << a.nx_shift) * 64 <= a.nvb) rdp_tile<P, E, W, true>(a, v);
+    else rdp_tile<P, E, W, false>(a, v);
+}
+
+static uint32_t rdp_interleave_shift(uint64_t nvb, const LaunchShape &shape, uint64_t *tiles)
+{
+    uint32_t nx_shift = shape.interleave_shift >= 0 && shape.interleave_shift <= 10
+                            ? static_cast<uint32_t>(shape.interleave_shift) : 5u;
+    const uint64_t tile = kThreads;  // vectors per workgroup
+    while (nx_shift > 0 && (tile << nx_shift) > nvb) --nx_shift;
+    const uint64_t super = tile << nx_shift;
+    if (tiles) *tiles = ((nvb + super - 1) / super) << nx_shift;
+    return nx_shift;
+}
+
+constexpr int kRdpBatchW = 2;  // 8-byte vectors
+
+bool write_rdp_batch_desc(void *slot, int idx, const RdpPlan &plan, const void *const *shards, size_t shard_bytes,
+                          size_t cell_bytes, const LaunchShape &shape)
+{
+    const int rows = plan.p - 1;
+    if (shard_bytes % (cell_bytes * rows) != 0) return false;
+    RdpBatchDesc &d = static_cast<RdpBatchDesc *>(slot)[idx];
+    for (int j = 0; j < kRdpMaxDisks; ++j)
+        d.disk[j] = (j <= plan.p && plan.shard_of_disk[j] >= 0 && shard_bytes != 0)
+                        ? static_cast<const uint8_t *>(shards[plan.shard_of_disk[j]]) : nullptr;
+    for (int x = 0; x < 2; ++x)
+        d.out[x] = x < static_cast<int>(plan.outputs.size()) ? static_cast<uint8_t *>(const_cast<void *>(shards[plan.outputs[x]])) : nullptr;
+    d.nvb = shard_bytes / rows / (4u * kRdpBatchW);
+    d.nx_shift = rdp_interleave_shift(d.nvb ? d.nvb : 1, shape, nullptr);
+    d.pad = 0;
+    return true;
+}
+
+template <int P>
+static hipError_t launch_batch_p(const RdpBatchArgs &a, int n_out, dim3 grid, hipStream_t stream)
+{
+    if (n_out == 1) hipLaunchKernelGGL((rdp_batch_kernel<P, 1, kRdpBatchW>), grid, dim3(kThreads), 0, stream, a);
+    else hipLaunchKernelGGL((rdp_batch_kernel<P, 2, kRdpBatchW>), grid, dim3(kThreads), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_rdp_batch(const RdpPlan &plan, const void *descs_dev, int n_chunks, size_t max_bytes,
+                            size_t cell_bytes, const LaunchShape &shape, hipStream_t stream)
+{
+    const int rows = plan.p - 1;
+    const int n_out = static_cast<int>(plan.outputs.size());
+    if (n_out < 1 || n_out > 2 || plan.p > kRdpMaxPrime || n_chunks < 1 || n_chunks > 65535) return hipErrorInvalidValue;
+    if (cell_bytes < 16 || (cell_bytes & (cell_bytes - 1)) != 0) return hipErrorInvalidValue;
+    if (max_bytes == 0) return hipSuccess;
+    RdpBatchArgs a;
+    a.descs = static_cast<const RdpBatchDesc *>(descs_dev);
+    for (int i = 0; i < 2 * kRdpMaxRows; ++i)
+        a.syndrome_mask[i] = i < static_cast<int>(plan.syndrome_mask.size()) ? plan.syndrome_mask[i] : 0u;
+    a.needs_diagonals = plan.needs_diagonals ? 1u : 0u;
+    a.cell_shift = 0;
+    while ((static_cast<size_t>(4u * kRdpBatchW) << a.cell_shift) < cell_bytes) ++a.cell_shift;
+    uint64_t tiles = 0;
+    rdp_interleave_shift(max_bytes / rows / (4u * kRdpBatchW), shape, &tiles);
+    if (tiles >= (1ull << 23)) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<uint32_t>(tiles ? tiles : 1), static_cast<uint32_t>(n_chunks));
+#define GS_RDP_BATCH_CASE(P_) case P_: return launch_batch_p<P_>(a, n_out, grid, stream);
+    switch (plan.p) {
+        GS_RDP_BATCH_CASE(3) GS_RDP_BATCH_CASE(5) GS_RDP_BATCH_CASE(7) GS_RDP_BATCH_CASE(11) GS_RDP_BATCH_CASE(13)
+        GS_RDP_BATCH_CASE(17)
+        default: return hipErrorInvalidValue;
+    }
+#undef GS_RDP_BATCH_CASE
+}
+
 // ---- the same two steps over a paged pool ---------------------------------------
 // A cell is one page, a stripe p-1 consecutive page slots of a plane; data
 // disks are rows of the block table, parity disks dense buffers laid out

@@ -434,6 +434,54 @@ static int check_ring()
     return 0;
 }
 
+// The grouped launch with an RDP code: the same ring discipline, and every chunk
+// is checked (whole stripes, no output on an input) before anything is enqueued.
+static int check_rdp_ring()
+{
+    const int k = 4, n_chunks = 3;
+    gs_code *code = nullptr;
+    EXPECT(gs_make_rdp_code(k, 64, &code) == GS_OK);  // p = 5: stripes of 256 bytes
+    gs_batch *batch = nullptr;
+    EXPECT(gs_batch_create(code, n_chunks, &batch) == GS_OK);
+    hipStream_t s = nullptr;
+    EXPECT(hipStreamCreateWithFlags(&s, 0) == hipSuccess);
+    std::vector<const void *> data(static_cast<size_t>(n_chunks) * k);
+    std::vector<void *> parity(static_cast<size_t>(n_chunks) * 2), shards(static_cast<size_t>(n_chunks) * (k + 2));
+    for (size_t i = 0; i < data.size(); ++i) data[i] = reinterpret_cast<void *>(0x100000000ull + 0x200000ull * i);
+    for (size_t i = 0; i < parity.size(); ++i) parity[i] = reinterpret_cast<void *>(0x900000000ull + 0x200000ull * i);
+    for (size_t i = 0; i < shards.size(); ++i) shards[i] = reinterpret_cast<void *>(0x100000000ull + 0x200000ull * i);
+    std::vector<size_t> bytes = {256 * 40, 0, 256};
+    reset_record();
+    for (int c = 0; c < 6; ++c) {
+        if (c & 1) {
+            const int erased[2] = {1, 4};
+            EXPECT(gs_reconstruct_batch(batch, n_chunks, shards.data(), erased, 2, bytes.data(), s) == GS_OK);
+        } else {
+            EXPECT(gs_encode_batch(batch, n_chunks, data.data(), parity.data(), bytes.data(), s) == GS_OK);
+        }
+    }
+    size_t uploads = 0, launches = 0;
+    for (const Op &o : ops) (o.kind == COPY ? uploads : launches) += 1;
+    EXPECT(uploads == 6 && launches == 6);
+    reset_record();
+    bytes[2] = 256 + 64;  // a cell too many
+    EXPECT(gs_encode_batch(batch, n_chunks, data.data(), parity.data(), bytes.data(), s) == GS_EINVAL);
+    bytes[2] = 256;
+    void *keep = parity[0];
+    parity[0] = const_cast<void *>(data[1]);  // chunk 0 writes its row parity over its own data
+    EXPECT(gs_encode_batch(batch, n_chunks, data.data(), parity.data(), bytes.data(), s) == GS_EINVAL);
+    parity[0] = keep;
+    const int three[3] = {0, 1, 2};
+    EXPECT(gs_reconstruct_batch(batch, n_chunks, shards.data(), three, 3, bytes.data(), s) != GS_OK);
+    EXPECT(ops.empty());
+    bytes = {0, 0, 0};
+    EXPECT(gs_encode_batch(batch, n_chunks, data.data(), parity.data(), bytes.data(), s) == GS_OK && ops.empty());
+    gs_batch_destroy(batch);
+    EXPECT(hipStreamDestroy(s) == hipSuccess);
+    gs_free_code(code);
+    return 0;
+}
+
 // device allocations that fail part of the way through object creation: nothing leaks (ASan's leak
 // check at exit), nothing is handed back
 static int check_allocation_failures()
@@ -648,6 +696,7 @@ int main()
     if (check_pipeline_failures()) return 1;
     if (check_pool(4, 11) || check_pool(16, 3) || check_pool(1, 5)) return 1;
     if (check_ring()) return 1;
+    if (check_rdp_ring()) return 1;
     if (check_step_graph()) return 1;
     if (check_allocation_failures()) return 1;
     for (int i = 1; i < kMaxStreams; ++i) EXPECT(!stream_live[i]);  // every stream was destroyed

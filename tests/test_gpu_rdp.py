@@ -275,3 +275,74 @@ def test_rdp_paged_refusals_and_pipelines(gs):
             if k + i in pat:
                 check(out[i], want[i])
     gs.gs_pipe_destroy(pipe)
+
+
+@pytest.mark.parametrize("k,cell", [(4, 16), (6, 64), (10, 1024), (16, 16)])
+def test_rdp_grouped_launch_matches_the_oracle_chunk_by_chunk(gs, k, cell):
+    p = oracle.rdp_prime(k)
+    stripe = (p - 1) * cell
+    # stripes per chunk: empty, one, ragged counts below and above a super-tile of pieces, one long chunk first or last
+    counts = [1, 0, 3, 64 * 4 + 1, 7, 2, 64 * 32 * 2 // max(1, cell // 16) + 5, 1, 33]
+    sizes = [c * stripe for c in counts]
+    code = gs.gs_make_rdp_code(k, cell)
+    chunks = [[inputs.kv_bytes_np(1000 * k + 37 * c + j, S, "bf16", 1.0) for j in range(k)] for c, S in enumerate(sizes)]
+    want = [oracle.rdp_encode(ch, cell) if S else [np.zeros(0, np.uint8)] * 2 for ch, S in zip(chunks, sizes)]
+    hold = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    data = [[dev(x) if x.size else hold for x in ch] for ch in chunks]
+    par = [[out_buf(S), out_buf(S)] for S in sizes]
+    b = gs.gs_batch_create(code, len(sizes))
+    gs.gs_encode_batch(b, data, par, sizes)
+    torch.cuda.synchronize()
+    for c in range(len(sizes)):
+        check(par[c][0], want[c][0])
+        check(par[c][1], want[c][1])
+    # every chunk loses the same shards; one and two losses, data and parity
+    pats = [(0,), (k,), (k + 1,), (0, k - 1) if k > 1 else (0, k), (k - 1, k), (0, k + 1), (k, k + 1)]
+    for pat in pats:
+        shards = []
+        for c, S in enumerate(sizes):
+            full = chunks[c] + want[c]
+            row = []
+            for r in range(k + 2):
+                if r in pat:
+                    t = out_buf(S)
+                    t[:S] = 0xA5
+                else:
+                    t = dev(full[r]) if S else hold
+                row.append(t)
+            shards.append(row)
+        gs.gs_reconstruct_batch(b, shards, list(pat), sizes)
+        torch.cuda.synchronize()
+        for c, S in enumerate(sizes):
+            full = chunks[c] + want[c]
+            for r in range(k + 2):
+                if r in pat:
+                    check(shards[c][r], full[r])
+                elif S:
+                    assert np.array_equal(shards[c][r].cpu().numpy(), full[r])
+    gs.gs_batch_destroy(b)
+
+
+def test_rdp_grouped_launch_refusals(gs):
+    k, cell = 4, 64
+    stripe = 4 * cell
+    code = gs.gs_make_rdp_code(k, cell)
+    b = gs.gs_batch_create(code, 4)
+    data = [[torch.zeros(4 * stripe, dtype=torch.uint8, device="cuda") for _ in range(k)] for _ in range(2)]
+    par = [[out_buf(4 * stripe), out_buf(4 * stripe)] for _ in range(2)]
+    # the second chunk is not whole stripes: nothing may be written for the first either
+    with pytest.raises(gs.GsError) as e:
+        gs.gs_encode_batch(b, data, par, [stripe, stripe + 16])
+    assert e.value.status == gs.GS_EINVAL
+    torch.cuda.synchronize()
+    assert (par[0][0].cpu().numpy() == CANARY).all()
+    # an output that is also an input of its chunk
+    with pytest.raises(gs.GsError):
+        gs.gs_encode_batch(b, data, [[data[0][1], par[0][1]], par[1]], [stripe, stripe])
+    # three erasures
+    with pytest.raises(gs.GsError):
+        gs.gs_reconstruct_batch(b, [d + q for d, q in zip(data, par)], [0, 1, 2], [stripe, stripe])
+    # the allocation-free form has no RDP kernel
+    with pytest.raises(gs.GsError):
+        gs.gs_encode_batch_static(code, data, par, [stripe, stripe])
+    gs.gs_batch_destroy(b)
