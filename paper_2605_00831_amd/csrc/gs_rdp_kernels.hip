@@ -283,19 +283,25 @@ __global__ __launch_bounds__(kThreads) void rdp_paged_kernel(const RdpPagedArgs 
         const uint8_t *dense = a.dense[j];
         if (trow < 0 && dense == nullptr) continue;   // disk absent (imaginary, missing, or not needed)
         if (j == P && !diagonals) continue;
+        // one branch per disk, then all of its table entries, then all of its loads: the p-1
+        // loads of a disk are in flight together
         vec x[kRows];
+        if (trow >= 0) {
+            int64_t page[kRows];
 #pragma unroll
-        for (int row = 0; row < kRows; ++row) {
-            const uint64_t slot = stripe * kRows + row;
-            if (trow >= 0) {
-                const int64_t page = page_of(trow, slot);
-                const vec *src = reinterpret_cast<const vec *>(pbase) + (page < 0 ? 0 : static_cast<uint64_t>(page)) * vpc + off;
-                const vec val = __builtin_nontemporal_load(src);
-                x[row] = page < 0 ? vec(0) : val;
-            } else {
-                const vec *src = reinterpret_cast<const vec *>(dense) + static_cast<uint64_t>(plane) * a.stride[j] + slot * vpc + off;
+            for (int row = 0; row < kRows; ++row) page[row] = page_of(trow, stripe * kRows + row);
+#pragma unroll
+            for (int row = 0; row < kRows; ++row) {
+                const vec *src = reinterpret_cast<const vec *>(pbase) + (page[row] < 0 ? 0 : static_cast<uint64_t>(page[row])) * vpc + off;
                 x[row] = __builtin_nontemporal_load(src);
             }
+#pragma unroll
+            for (int row = 0; row < kRows; ++row)
+                if (page[row] < 0) x[row] = vec(0);
+        } else {
+            const vec *src = reinterpret_cast<const vec *>(dense) + static_cast<uint64_t>(plane) * a.stride[j] + (stripe * kRows) * vpc + off;
+#pragma unroll
+            for (int row = 0; row < kRows; ++row) x[row] = __builtin_nontemporal_load(src + row * vpc);
         }
         if (j < P) {
 #pragma unroll
