@@ -292,10 +292,9 @@ void gs_step_graph_destroy(gs_step_graph *g);
  * stream; anything else gives GS_EINVAL.  The grouped launch (gs_batch)
  * takes it too, every chunk a whole number of stripes; the allocation-free
  * grouped encode does not.  gs_code_matrix / gs_decode_matrix return GS_EINVAL
- * for it.  A single lost
- * shard other than the diagonal
- * parity is rebuilt from the row equations alone (the diagonal parity shard
- * is then not read and may be NULL). */
+ * for it.  A single lost shard other than the diagonal parity is rebuilt from
+ * the row equations alone (the diagonal parity shard is then not read and may
+ * be NULL). */
 #define GS_RDP_DEFAULT_CELL 32768
 int gs_make_rdp_code(int k, size_t cell_bytes, gs_code **out);
 int gs_rdp_prime(const gs_code *code, int *p_out);

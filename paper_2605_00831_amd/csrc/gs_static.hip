@@ -51,6 +51,7 @@ hipError_t scratch_of_current_device(void **out)
 // one word holding the stream length (low 56 bits) and the chunk's interleave
 // shift (high 8 bits).
 constexpr int kFillWords = 384;
+constexpr int kFillThreads = 64;  // one thread per chunk of a fill launch
 
 struct FillArgs {
     uint64_t words[kFillWords];
@@ -58,7 +59,7 @@ struct FillArgs {
     uint32_t count, k, rows;
 };
 
-__global__ __launch_bounds__(64) void fill_descs_kernel(const FillArgs a)
+__global__ __launch_bounds__(kFillThreads) void fill_descs_kernel(const FillArgs a)
 {
     const uint32_t c = threadIdx.x;
     if (c >= a.count) return;
@@ -110,7 +111,9 @@ try {
     const LaunchShape shape = current_shape();
     int order[kLaunchMaxM];
     batch_row_order(m, k, code->P.data(), k, order);
-    const int per_chunk = k + m + 1, per_launch = kFillWords / per_chunk;
+    const int per_chunk = k + m + 1;
+    // what the argument block holds, and no more than the fill kernel has threads (narrow codes)
+    const int per_launch = kFillWords / per_chunk < kFillThreads ? kFillWords / per_chunk : kFillThreads;
     FillArgs a;
     a.k = static_cast<uint32_t>(k);
     a.rows = static_cast<uint32_t>(m);
@@ -125,7 +128,7 @@ try {
         }
         a.descs = descs + c0;
         a.count = static_cast<uint32_t>(n);
-        hipLaunchKernelGGL(fill_descs_kernel, dim3(1), dim3(64), 0, stream, a);
+        hipLaunchKernelGGL(fill_descs_kernel, dim3(1), dim3(kFillThreads), 0, stream, a);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_status(e);
     }

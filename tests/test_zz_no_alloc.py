@@ -58,6 +58,18 @@ def test_static_grouped_encode_equals_grouped_encode_on_two_calls_in_a_row(gs, k
     gs.gs_batch_destroy(batch)
 
 
+@pytest.mark.parametrize("k,m", [(1, 1), (2, 1), (2, 2)])
+def test_static_grouped_encode_of_narrow_codes_with_many_chunks(gs, k, m):
+    # a narrow code's chunks take few argument words each: a fill launch is then bounded by its
+    # thread count, not by the argument block
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    batch = gs.gs_batch_create(code, 200)
+    run_both(gs, code, batch, P, [2048 + 16 * c + (c % 3) for c in range(200)], 3000 * k + m)
+    run_both(gs, code, batch, P, [1024 + c for c in range(70)], 4000 * k + m)
+    gs.gs_batch_destroy(batch)
+
+
 def test_static_grouped_encode_limits(gs):
     code = gs.gs_make_code(4, 2)
     t = torch.zeros(64, dtype=torch.uint8, device="cuda")
