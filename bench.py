@@ -858,6 +858,15 @@ def many_chunks(torch, gs, log):
                      "stream_pool_16_ms": lambda: gs.gs_reconstruct_streams(code, pool, shards, er, sizes),
                      "grouped_launch_ms": lambda: gs.gs_reconstruct_batch(batch, shards, er, sizes)}
             traffic = (k + len(er)) * S * n
+        # the grouped call once more with the addresses kept in numpy arrays (what an engine that tracks
+        # its buffers by address would hand over): no per-pointer work in the interpreter
+        addr = np.array([[t.data_ptr() for t in row_] for row_ in shards], dtype=np.uint64)
+        sizes_np = np.array(sizes, dtype=np.uint64)
+        if er is None:
+            a_in, a_out = np.ascontiguousarray(addr[:, :k]), np.ascontiguousarray(addr[:, k:])
+            forms["grouped_launch_address_arrays_ms"] = lambda: gs.gs_encode_batch(batch, a_in, a_out, sizes_np)
+        else:
+            forms["grouped_launch_address_arrays_ms"] = lambda: gs.gs_reconstruct_batch(batch, addr, er, sizes_np)
         row = {"op": "encode" if er is None else "reconstruct", "k": k, "m": m, "erased": er,
                "chunks": n, "shard_bytes": S}
         for name, fn in forms.items():

@@ -386,7 +386,14 @@ class Pool:
 
 
 def _flat_ptrs(chunks, width):
-    """list (per chunk) of lists of `width` pointers -> one flat pointer array"""
+    """list (per chunk) of lists of `width` pointers -> one flat pointer array.
+    A C-contiguous numpy array of addresses, shape (n_chunks, width), 64-bit integers, is passed
+    as it is: an engine that keeps its addresses in such an array pays no per-pointer work."""
+    if isinstance(chunks, np.ndarray):
+        if chunks.dtype not in (np.uint64, np.int64) or chunks.ndim != 2 or chunks.shape[1] != width \
+                or not chunks.flags["C_CONTIGUOUS"]:
+            raise ValueError("an address array must be C-contiguous 64-bit integers of shape (n_chunks, %d)" % width)
+        return chunks.ctypes.data_as(ctypes.POINTER(ctypes.c_void_p))
     flat = []
     for c in chunks:
         if len(c) != width:
@@ -396,6 +403,9 @@ def _flat_ptrs(chunks, width):
 
 
 def _size_array(sizes):
+    if isinstance(sizes, np.ndarray) and sizes.dtype == np.uint64 and sizes.ndim == 1 and sizes.flags["C_CONTIGUOUS"] \
+            and ctypes.sizeof(ctypes.c_size_t) == 8:
+        return sizes.ctypes.data_as(ctypes.POINTER(ctypes.c_size_t))
     sizes = list(sizes)
     return (ctypes.c_size_t * max(len(sizes), 1))(*sizes)
 

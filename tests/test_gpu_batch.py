@@ -175,3 +175,31 @@ def test_streams_check_every_chunk_before_enqueueing(gs):
     for row in par:
         for t in row:
             assert (t.cpu().numpy() == CANARY).all()
+
+
+def test_grouped_launch_takes_address_arrays(gs):
+    # the same call with the addresses and lengths in numpy arrays instead of lists of tensors
+    k, m = 4, 2
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    sizes = [4096, 100, 0, (1 << 18) + 3]
+    chunks = make_chunks(k, 4242, sizes)
+    hold = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    data = [[dev(x) if x.size else hold for x in ch] for ch in chunks]
+    par = [[out_buf(S) for _ in range(m)] for S in sizes]
+    b = gs.gs_batch_create(code, len(sizes))
+    a_in = np.array([[t.data_ptr() for t in row] for row in data], dtype=np.uint64)
+    a_out = np.array([[t.data_ptr() for t in row] for row in par], dtype=np.uint64)
+    gs.gs_encode_batch(b, a_in, a_out, np.array(sizes, dtype=np.uint64))
+    torch.cuda.synchronize()
+    for c, S in enumerate(sizes):
+        want = oracle.encode(P, chunks[c]) if S else [np.zeros(0, np.uint8)] * m
+        for i in range(m):
+            check(par[c][i], want[i])
+    with pytest.raises(ValueError):
+        gs.gs_encode_batch(b, a_in[:, :3], a_out, sizes)                 # wrong width
+    with pytest.raises(ValueError):
+        gs.gs_encode_batch(b, a_in.astype(np.uint32), a_out, sizes)      # not addresses
+    with pytest.raises(ValueError):
+        gs.gs_encode_batch(b, np.asfortranarray(a_in), a_out, sizes)     # not chunk-major
+    gs.gs_batch_destroy(b)

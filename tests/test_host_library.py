@@ -247,3 +247,24 @@ def test_no_kernel_spills_registers_to_scratch_memory(tmp_path):
         spilled = [(n, int(b)) for n, b in meta if int(b) != 0]
         assert not spilled, spilled
     assert kernels > 100
+
+
+def test_binding_passes_address_arrays_through_unchanged():
+    import ctypes
+
+    import numpy as np
+
+    from paper_2605_00831_amd import binding
+    a = (np.arange(12, dtype=np.uint64) * 4096).reshape(3, 4)
+    p = binding._flat_ptrs(a, 4)
+    assert ctypes.addressof(p.contents) == a.ctypes.data and p[7] == 7 * 4096
+    q = binding._flat_ptrs([[1, 2, 3, 4], [5, 6, 7, 8]], 4)
+    assert list(q) == [1, 2, 3, 4, 5, 6, 7, 8]
+    for bad in (a[:, :3], a.astype(np.uint32), np.asfortranarray(a), a.reshape(-1)):
+        with pytest.raises(ValueError):
+            binding._flat_ptrs(bad, 4)
+    with pytest.raises(ValueError):
+        binding._flat_ptrs([[1, 2, 3]], 4)
+    s = binding._size_array(np.array([5, 6], dtype=np.uint64))
+    assert s[0] == 5 and s[1] == 6
+    assert list(binding._size_array([7, 8])) == [7, 8]
