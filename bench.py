@@ -162,9 +162,9 @@ def main():
     ap.add_argument("--launch-shape", default=None, metavar="U,T,NT,ILV",
                     help="gs_set_launch_shape(unroll, tiles_per_wg, nontemporal, interleave_shift) for sweeps; "
                          "0 / -1 keep a knob's default")
-    ap.add_argument("--only", default=None, choices=["headline", "paged_bulk"],
+    ap.add_argument("--only", default=None, choices=["headline", "paged_bulk", "rdp_forms"],
                     help="headline: the timed steps of --workload and its extras, not the other bulk workloads; "
-                         "paged_bulk: only the bulk paged-gather leg (for profiling runs)")
+                         "paged_bulk / rdp_forms: only that leg (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -175,7 +175,7 @@ def main():
     # The decode-step latency probe is a plain C program: run it as a child process first, before
     # this process opens the GPU, so that the two never hold the device at the same time.
     native = None
-    if not args.no_extras and args.only != "paged_bulk":
+    if not args.no_extras and args.only not in ("paged_bulk", "rdp_forms"):
         native = {"decode": native_probe(log, "decode", inputs_steps(), 32), "many": native_probe(log, "many")}
 
     import torch
@@ -200,6 +200,10 @@ def main():
     if args.only == "paged_bulk":
         print(json.dumps({"paged_bulk": paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras,
                                                    calibrate=args.calibrate_copy)}), flush=True)
+        return 0
+
+    if args.only == "rdp_forms":
+        print(json.dumps({"rdp_forms": rdp_forms(torch, gs, inputs, log, calibrate=args.calibrate_copy)}), flush=True)
         return 0
 
     cfg = inputs.CONFIGS[args.workload]
@@ -312,6 +316,7 @@ def main():
                                                   pipelines=not args.no_extras, default_shape=args.launch_shape is None))
         out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
         out["code_shapes"] = code_shapes(torch, gs, log)
+        out["rdp_forms"] = rdp_forms(torch, gs, inputs, log)
 
     print(json.dumps(out), flush=True)
     return 0
@@ -821,6 +826,76 @@ def chunk_sweep(torch, gs, inputs, log):
                      "encode_frac_of_d2h": round(enc / d2h, 4)})
     log("[bench] chunk sweep: " + json.dumps(rows))
     return rows
+
+
+def rdp_forms(torch, gs, inputs, log, calibrate=False):
+    """The XOR-only RDP code in all of its forms, k = 4, 8, 16 (p = 5, 11, 17), shards of about 1 GiB in
+    cells of 32 KiB: contiguous encode, rebuild of two data shards and of one, the paged encode behind an
+    identity table and behind a seeded random permutation of the pool's pages (a cell = a page), and the
+    grouped launch over 16 chunks.  Events around 10 launches each; fractions are algorithmic bytes
+    (shards read + shards written) over the 8 TB/s HBM peak."""
+    dev = "cuda:0"
+    cell = 32768
+    out = []
+    device_arena(torch, 18 * ((1 << 30) + (2 << 20)))   # the widest code's shards: nothing is freed between the three
+    for k in (4, 8, 16):
+        code = gs.gs_make_rdp_code(k, cell)
+        p = gs.gs_rdp_prime(code)
+        stripe = (p - 1) * cell
+        S = (1 << 30) // (16 * stripe) * (16 * stripe)      # 16 chunks of whole stripes
+        gap = 2 << 20                                       # keeps shards off power-of-two distances
+        arena = device_arena(torch, (k + 2) * (S + gap))
+        inputs.kv_bytes_device(inputs.config_seed("llama8b_prefill") + 40 + k, k * (S + gap), "bf16", 1.0, dev,
+                               out=arena[:k * (S + gap)])
+        sh = [arena[j * (S + gap): j * (S + gap) + S] for j in range(k + 2)]
+        if calibrate and k == 4:
+            sh[k].copy_(sh[0])      # a plain copy of known size (counter calibration under rocprofv3 --pmc)
+            torch.cuda.synchronize()
+            log("[bench] calibration copy: %d bytes read, %d bytes written" % (S, S))
+
+        def ms_of(fn, n=10):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+
+        row = {"k": k, "prime": p, "cell_bytes": cell, "shard_bytes": S}
+
+        def put(name, ms, shards_moved):
+            row[name] = {"ms": round(ms, 4), "frac": round(shards_moved * S / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+        put("encode", ms_of(lambda: gs.gs_encode(code, sh[:k], sh[k:], S)), k + 2)
+        two = [0, k - 1] if k > 1 else [0, k]
+        put("reconstruct_two_data_shards", ms_of(lambda: gs.gs_reconstruct(code, sh, two, S)), k + 2)
+        put("reconstruct_one_data_shard", ms_of(lambda: gs.gs_reconstruct(code, sh, [1], S)), k + 1)
+        gs.gs_encode(code, sh[:k], sh[k:], S)
+        # paged: one plane over the data part of the arena, a page = a cell
+        lo = arena.data_ptr()
+        pps, ppp = S // cell, k * (S + gap) // cell
+        one_plane = torch.tensor([lo], dtype=torch.int64, device=dev)
+        ident = torch.stack([torch.arange(pps, dtype=torch.int32, device=dev) + j * ((S + gap) // cell)
+                             for j in range(k)]).contiguous()
+        put("encode_paged_identity_table",
+            ms_of(lambda: gs.gs_encode_paged(code, one_plane, 1, cell, ppp, ident, pps, sh[k:])), k + 2)
+        perm = torch.from_numpy(inputs.block_table_np(inputs.config_seed("llama8b_prefill") + k, k, pps, ppp)).to(dev)
+        put("encode_paged_random_table",
+            ms_of(lambda: gs.gs_encode_paged(code, one_plane, 1, cell, ppp, perm, pps, sh[k:])), k + 2)
+        n_g, per = 16, S // 16
+        batch = gs.gs_batch_create(code, n_g)
+        addr = np.array([[t.data_ptr() + c * per for t in sh] for c in range(n_g)], dtype=np.uint64)
+        a_in, a_out = np.ascontiguousarray(addr[:, :k]), np.ascontiguousarray(addr[:, k:])
+        sizes = np.full(n_g, per, dtype=np.uint64)
+        put("encode_grouped_16_chunks", ms_of(lambda: gs.gs_encode_batch(batch, a_in, a_out, sizes)), k + 2)
+        gs.gs_batch_destroy(batch)
+        out.append(row)
+    log("[bench] rdp forms: " + json.dumps(out))
+    return out
 
 
 def many_chunks(torch, gs, log):
