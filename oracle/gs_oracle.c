@@ -358,18 +358,19 @@ int gso_encode_mt(int k, int m, const uint8_t *P,
     pthread_t th[256]; struct gso_job jobs[256];
     size_t per = (S + (size_t)nthreads - 1) / (size_t)nthreads;
     int started = 0;
-    for (int t = 0; t < nthreads; t++) {
+    for (int t = 0; t < nthreads; t++) { /* every byte range first: the inline fallback below needs them all */
         size_t lo = (size_t)t * per, hi = lo + per;
         if (lo > S) lo = S;
         if (hi > S) hi = S;
         jobs[t] = (struct gso_job){k, m, P, data, parity, lo, hi};
+    }
+    for (int t = 0; t < nthreads; t++) {
         if (pthread_create(&th[t], NULL, gso_worker, &jobs[t]) != 0) break;
         started++;
     }
     for (int t = 0; t < started; t++) pthread_join(th[t], NULL);
-    if (started != nthreads) { /* finish the rest inline so the result is complete */
-        for (int t = started; t < nthreads; t++) gso_worker(&jobs[t]);
-    }
+    /* a thread that could not be started: its range and the later ones are done here, so the result is complete */
+    for (int t = started; t < nthreads; t++) gso_worker(&jobs[t]);
     return 0;
 }
 
