@@ -203,3 +203,29 @@ def test_grouped_launch_takes_address_arrays(gs):
     with pytest.raises(ValueError):
         gs.gs_encode_batch(b, np.asfortranarray(a_in), a_out, sizes)     # not chunk-major
     gs.gs_batch_destroy(b)
+
+
+def test_grouped_launch_at_its_largest_chunk_count(gs):
+    # 65535 chunks (the grid's y limit) of 48 bytes each, addresses handed over as arrays; chunks are
+    # independent, so the oracle encodes shard position j of all chunks as one long stream
+    k, m, S, n = 2, 2, 48, 65535
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    src_np = inputs.uniform_bytes_np(777, n * k * S)
+    src = dev(src_np)
+    out = torch.full((n * m * S + PAD,), CANARY, dtype=torch.uint8, device="cuda")
+    c = np.arange(n, dtype=np.uint64)
+    a_in = np.ascontiguousarray(np.stack([src.data_ptr() + (c * k + j) * S for j in range(k)], axis=1).astype(np.uint64))
+    a_out = np.ascontiguousarray(np.stack([out.data_ptr() + (c * m + i) * S for i in range(m)], axis=1).astype(np.uint64))
+    b = gs.gs_batch_create(code, n)
+    gs.gs_encode_batch(b, a_in, a_out, np.full(n, S, dtype=np.uint64))
+    torch.cuda.synchronize()
+    want = oracle.encode(P, [np.ascontiguousarray(src_np.reshape(n, k, S)[:, j, :]).reshape(-1) for j in range(k)], nthreads=8)
+    got = out.cpu().numpy()
+    assert (got[n * m * S:] == CANARY).all()
+    got = got[: n * m * S].reshape(n, m, S)
+    for i in range(m):
+        assert np.array_equal(got[:, i, :].reshape(-1), want[i])
+    gs.gs_batch_destroy(b)
+    with pytest.raises(gs.GsError):
+        gs.gs_batch_create(code, n + 1)

@@ -269,3 +269,71 @@ def test_recovery_stress_full_size_through_the_paged_pipelines(gs):
             if r >= k:
                 assert torch.equal(out[r - k], parity[r - k]), (pat, r)
     gs.gs_pipe_destroy(pipe)
+
+
+@pytest.mark.parametrize("kind", ["cauchy", "rdp"])
+def test_paged_pool_with_a_plane_larger_than_4_gib(gs, kind):
+    """Page ids whose byte offset inside the plane is beyond 2^32: one plane of 6 GiB in 32 KiB pages, the
+    shards' pages drawn from all of it (most of them above 4 GiB), parity from gs_encode_paged and from
+    the paged checkpoint pipeline, a lost shard rebuilt into fresh pages above 4 GiB.  The oracle sees
+    only the pages the table names, copied to the host and renumbered."""
+    free, _ = torch.cuda.mem_get_info()
+    if free < (8 << 30):
+        pytest.skip("needs 8 GiB of free device memory")
+    k, m, page, pps = 4, 2, 32768, 64
+    ppp = (6 << 30) // page
+    pool = torch.empty(ppp * page, dtype=torch.uint8, device="cuda")
+    for at in range(0, pool.numel(), 1 << 30):
+        pool[at:at + (1 << 30)].random_(0, 256)
+    pages = pool.view(ppp, page)
+    rng = np.random.default_rng(inputs.SEED_BASE + 0x410)
+    high = (1 << 32) // page
+    low = rng.choice(high, size=pps // 2, replace=False)                             # below 4 GiB
+    above = high + rng.choice(ppp - high, size=(k + 1) * pps - pps // 2, replace=False)
+    ids = rng.permutation(np.concatenate([low, above[pps:]])).astype(np.int32)
+    table_np = np.ascontiguousarray(ids.reshape(k, pps))
+    spare_np = above[:pps].astype(np.int32)                                           # fresh pages, all above 4 GiB
+    table = torch.from_numpy(table_np).cuda()
+    base = torch.tensor([pool.data_ptr()], dtype=torch.int64, device="cuda")
+    S = pps * page
+    # the oracle's pool: the named pages only, numbered 0 .. k*pps-1 in table order
+    small = pages[torch.from_numpy(table_np.reshape(-1).astype(np.int64)).cuda()].cpu().numpy().reshape(-1)
+    small_table = np.arange(k * pps, dtype=np.int32).reshape(k, pps)
+    if kind == "rdp":
+        code = gs.gs_make_rdp_code(k, page)
+        streams = [small.reshape(k, S)[j] for j in range(k)]
+        want = oracle.rdp_encode([np.ascontiguousarray(s) for s in streams], page)
+    else:
+        code = gs.gs_make_code(k, m)
+        want = oracle.encode_paged(oracle.generator(k, m), [small], page, small_table)
+    par = [torch.full((S + 64,), 0xC7, dtype=torch.uint8, device="cuda") for _ in range(m)]
+    gs.gs_encode_paged(code, base, 1, page, ppp, table, pps, par)
+    torch.cuda.synchronize()
+    for i in range(m):
+        got = par[i].cpu().numpy()
+        assert np.array_equal(got[:S], want[i]), (kind, i)
+        assert (got[S:] == 0xC7).all()
+    pipe = gs.gs_pipe_create(code, 16 * page, 2)
+    host = [torch.full((S,), 0x5A, dtype=torch.uint8).pin_memory() for _ in range(m)]
+    gs.gs_checkpoint_paged(pipe, base, 1, page, ppp, table, pps, host)
+    gs.gs_pipe_sync(pipe)
+    for i in range(m):
+        assert np.array_equal(host[i].numpy(), want[i]), (kind, i)
+    # shard 2 is lost and rebuilt into fresh pages above 4 GiB; shard 0 in place through the pipeline
+    lost = 2
+    new_table_np = table_np.copy()
+    new_table_np[lost] = spare_np[:pps]
+    assert (new_table_np[lost].astype(np.int64) * page >= (1 << 32)).all()
+    new_table = torch.from_numpy(np.ascontiguousarray(new_table_np)).cuda()
+    before = pages[torch.from_numpy(table_np[lost].astype(np.int64)).cuda()].clone()
+    gs.gs_reconstruct_paged(code, base, 1, page, ppp, new_table, pps, [p[:S] for p in par], [lost])
+    torch.cuda.synchronize()
+    assert torch.equal(pages[torch.from_numpy(new_table_np[lost].astype(np.int64)).cuda()], before)
+    idx0 = torch.from_numpy(table_np[0].astype(np.int64)).cuda()
+    keep = pages[idx0].clone()
+    pages[idx0] = 0xA5
+    gs.gs_restore_paged(pipe, base, 1, page, ppp, table, pps, host, [0])
+    gs.gs_pipe_sync(pipe)
+    torch.cuda.synchronize()
+    assert torch.equal(pages[idx0], keep)
+    gs.gs_pipe_destroy(pipe)
