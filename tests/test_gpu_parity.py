@@ -510,3 +510,24 @@ def test_one_code_shared_by_host_threads(gs):
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+def test_paged_encode_at_the_largest_plane_count(gs):
+    # 65535 planes (the grid's y limit), 3 slots of 48 bytes per shard and plane, planes cut from one pool
+    k, m, n_planes, pps, page = 3, 2, 65535, 3, 48
+    num_pages = k * pps + 2
+    pool_np = inputs.uniform_bytes_np(4321, n_planes * num_pages * page)
+    planes_np = [pool_np[p * num_pages * page:(p + 1) * num_pages * page] for p in range(n_planes)]
+    table_np = inputs.block_table_np(9, k, pps, num_pages)
+    want = oracle.encode_paged(oracle.generator(k, m), planes_np, page, table_np)
+    pool = dev(pool_np)
+    base = dev(pool.data_ptr() + np.arange(n_planes, dtype=np.int64) * (num_pages * page))
+    out_bytes = n_planes * pps * page
+    par = [out_buf(out_bytes) for _ in range(m)]
+    code = gs.gs_make_code(k, m)
+    gs.gs_encode_paged(code, base, n_planes, page, num_pages, dev(table_np), pps, par)
+    torch.cuda.synchronize()
+    for i in range(m):
+        check_out(par[i], want[i])
+    with pytest.raises(gs.GsError):
+        gs.gs_encode_paged(code, base, n_planes + 1, page, num_pages, dev(table_np), pps, par)
