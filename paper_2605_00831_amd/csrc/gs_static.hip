@@ -22,7 +22,7 @@ namespace {
 // device that loads the library holds its own copy until the process ends).
 // In host code this name is only a handle for hipGetSymbolAddress; the address
 // the kernels use is the one that call returns for the current device.
-__device__ __align__(256) unsigned char scratch[GS_STATIC_MAX_CHUNKS * kBatchDescBytes];
+static __device__ __align__(256) unsigned char scratch[GS_STATIC_MAX_CHUNKS * kBatchDescBytes];
 
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
