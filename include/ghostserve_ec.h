@@ -31,8 +31,8 @@
  *     Calls only enqueue work; they never synchronise unless stated.
  *   - Every entry point returns GS_OK (0) or a negative gs_status; no C++
  *     exception leaves the library.  Arguments are checked before anything
- *     is enqueued: after GS_EINVAL, GS_ETOOMANY or GS_ESINGULAR no buffer is
- *     written.  GS_EHIP / GS_ENOMEM come from the runtime in mid-call: a call
+ *     is enqueued: after GS_EINVAL, GS_ETOOMANY, GS_ESINGULAR or GS_ELIMIT no
+ *     buffer is written.  GS_EHIP / GS_ENOMEM come from the runtime in mid-call: a call
  *     that issues several launches or copies (wide codes, pipelines, stream
  *     pools) may by then have enqueued some of them.
  *   - Shard base pointers must be 16-byte aligned; shard_bytes may be any
@@ -321,9 +321,10 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
  * Grouped launch (gs_batch): all chunks go through ONE kernel launch; their
  * pointers and lengths travel in a descriptor array that the gs_batch owns
  * (device buffer + pinned host mirror, a ring of 4 slots so that consecutive
- * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only (RDP
- * codes included),
- * max_chunks <= 65535.  One gs_batch serves one thread at a time.  The
+ * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only
+ * (RDP codes included: then every chunk must be a whole number of stripes,
+ * else GS_EINVAL with nothing enqueued), max_chunks <= 65535, chunks below
+ * 64 GiB.  One gs_batch serves one thread at a time.  The
  * descriptor slot is filled by the host at call time and may make the host
  * wait for the launch that used it four calls earlier, so these two calls
  * must not be made on a stream that is being captured into a graph (the
@@ -352,7 +353,8 @@ int gs_reconstruct_batch(gs_batch *batch, int n_chunks, void *const *shards, con
  * kernel launches only -- no allocation, no copy, no host wait -- and may be
  * captured into a graph.
  *   n_chunks > GS_STATIC_MAX_CHUNKS, or a chunk of 64 GiB or more: GS_ELIMIT,
- *   nothing enqueued.  Codes with k <= 16 and m <= 4 only (else GS_EINVAL).
+ *   nothing enqueued.  Codes with k <= 16 and m <= 4 only, and no RDP code
+ *   (else GS_EINVAL).
  * All calls on one device share that device's array, and a call overwrites
  * what the previous one left there: calls on the same stream are ordered by
  * the stream; calls that may run at the same time on different streams of one
