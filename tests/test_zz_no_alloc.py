@@ -99,3 +99,44 @@ def test_static_grouped_encode_limits(gs):
     want = oracle.encode(P, [np.ascontiguousarray(src[:, j, :]).reshape(-1) for j in range(k)])
     for i in range(m):
         assert np.array_equal(got[:, i, :].reshape(-1), want[i])
+
+
+def test_static_grouped_encode_replays_from_a_graph(gs):
+    """The call enqueues kernel launches only, so it can be captured; the graph (two descriptor-fill
+    launches and the grouped kernel) is replayed several times on changing data, with eager work and
+    synchronisation between the replays, and every replay is checked against the oracle."""
+    k, m, n = 8, 2, 60
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    sizes = [8192 + 16 * c + (c % 7) for c in range(n)]
+    data = [[torch.zeros(S, dtype=torch.uint8, device="cuda") for _ in range(k)] for S in sizes]
+    par = [[torch.zeros(S + 64, dtype=torch.uint8, device="cuda") for _ in range(m)] for S in sizes]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        gs.gs_encode_batch_static(code, data, par, sizes)     # first use on this device: outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gs.gs_encode_batch_static(code, data, par, sizes)
+    for rep in range(4):
+        data_np = [[inputs.uniform_bytes_np(7000 + 1000 * rep + 10 * c + j, S) for j in range(k)] for c, S in enumerate(sizes)]
+        for c in range(n):
+            for j in range(k):
+                data[c][j].copy_(torch.from_numpy(data_np[c][j]))     # eager work between replays
+            for t in par[c]:
+                t.fill_(0xEE)
+        # another eager call in between overwrites the shared descriptor array: the replay must rewrite it
+        gs.gs_encode_batch_static(code, data[:3], par[:3], sizes[:3])
+        for t in par[0] + par[1] + par[2]:
+            t.fill_(0xEE)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for c, S in enumerate(sizes):
+            want = oracle.encode(P, data_np[c])
+            for i in range(m):
+                got = par[c][i].cpu().numpy()
+                assert np.array_equal(got[:S], want[i]), (rep, c, i)
+                assert (got[S:] == 0xEE).all(), (rep, c, i)
