@@ -338,34 +338,3 @@ def test_paged_pool_with_a_plane_larger_than_4_gib(gs, kind):
     assert torch.equal(pages[idx0], keep)
     gs.gs_pipe_destroy(pipe)
 
-
-def test_shards_longer_than_one_grid_of_single_tile_workgroups(gs):
-    """Shards of 36 GiB: more tiles than a launch may have workgroups, so every workgroup takes two
-    tiles without being asked to.  k=2, m=2 (144 GiB resident, 180 GiB with the copy kept for the
-    rebuild); sampled windows incl. both sides of 2^32 and the last bytes, and the XOR-fold invariant
-    over the whole buffers; then a lost data shard is rebuilt bit for bit."""
-    k, m = 2, 2
-    S = (36 << 30) + 3 * FOLD
-    free, _ = torch.cuda.mem_get_info()
-    if free < 5 * S + (8 << 30):
-        pytest.skip("needs %.0f GiB of free device memory" % ((5 * S + (8 << 30)) / 2**30))
-    buf = inputs.kv_bytes_device(inputs.SEED_BASE + 0x420, k * S, "bf16", 1.0, "cuda")
-    data = [buf[j * S:(j + 1) * S] for j in range(k)]
-    parity = [torch.full((S,), 0xEE, dtype=torch.uint8, device="cuda") for _ in range(m)]
-    code = gs.gs_make_code(k, m)
-    P = oracle.generator(k, m)
-    gs.gs_encode(code, data, parity, S)
-    torch.cuda.synchronize()
-    check_windows(P, data, parity, S, inputs.SEED_BASE + 0x421)
-    # both sides of the 32 GiB mark, where the tile count passes the grid limit
-    for off, n in (((32 << 30) - 70001, 140003), (S - 5, 5)):
-        host = [np.ascontiguousarray(d[off:off + n].cpu().numpy()) for d in data]
-        want = oracle.encode(P, host, nthreads=8)
-        for i in range(m):
-            assert np.array_equal(parity[i][off:off + n].cpu().numpy(), want[i]), (i, off)
-    check_folds(P, data, parity)
-    keep = data[1].clone()
-    data[1].fill_(0xA5)
-    gs.gs_reconstruct(code, data + parity, [1], S)
-    torch.cuda.synchronize()
-    assert torch.equal(data[1], keep)
