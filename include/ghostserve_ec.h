@@ -289,7 +289,8 @@ void gs_step_graph_destroy(gs_step_graph *g);
  * gs_make_rdp_code(k, page_bytes)), page_bytes >= 1024, and pages_per_shard a
  * multiple of p-1 -- a stripe is then p-1 consecutive page slots of a plane,
  * which is the contiguous definition applied to the shard's gathered byte
- * stream; anything else gives GS_EINVAL.  The grouped launch (gs_batch)
+ * stream, and a shard's share of one plane must be below (p-1) x 16 GiB;
+ * anything else gives GS_EINVAL.  The grouped launch (gs_batch)
  * takes it too, every chunk a whole number of stripes; the allocation-free
  * grouped encode does not.  gs_code_matrix / gs_decode_matrix return GS_EINVAL
  * for it.  A single lost shard other than the diagonal parity is rebuilt from
@@ -322,9 +323,9 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
  * pointers and lengths travel in a descriptor array that the gs_batch owns
  * (device buffer + pinned host mirror, a ring of 4 slots so that consecutive
  * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only
- * (RDP codes included: then every chunk must be a whole number of stripes,
- * else GS_EINVAL with nothing enqueued), max_chunks <= 65535, chunks below
- * 64 GiB.  One gs_batch serves one thread at a time.  The
+ * (RDP codes included: then every chunk must be a whole number of stripes
+ * and shorter than (p-1) x 16 GiB, else GS_EINVAL with nothing enqueued),
+ * max_chunks <= 65535, chunks below 64 GiB.  One gs_batch serves one thread at a time.  The
  * descriptor slot is filled by the host at call time and may make the host
  * wait for the launch that used it four calls earlier, so these two calls
  * must not be made on a stream that is being captured into a graph (the

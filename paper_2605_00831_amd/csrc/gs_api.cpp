@@ -157,6 +157,8 @@ int check_rdp_paged(const gs_code *code, size_t page_bytes, int n_slots)
 {
     if (page_bytes != code->rdp_cell || page_bytes < 1024) return GS_EINVAL;
     if (n_slots % (code->rdp_encode.p - 1) != 0) return GS_EINVAL;
+    // one launch covers 16 GiB per stripe row of a plane (p = 3: 32 GiB of a shard per plane)
+    if (static_cast<uint64_t>(n_slots) / (code->rdp_encode.p - 1) * page_bytes >= (16ull << 30)) return GS_EINVAL;
     return GS_OK;
 }
 

@@ -83,7 +83,8 @@ static int run_rdp_batch(gs_batch *b, const RdpPlan &plan, int n, const void *co
     const LaunchShape shape = current_shape();
     size_t max_bytes = 0;
     for (int c = 0; c < n; ++c) {
-        if (bytes[c] % stripe != 0 || bytes[c] >= (1ull << 36)) return GS_EINVAL;
+        // whole stripes, and what one launch covers: 16 GiB per stripe row (p = 3: chunks below 32 GiB)
+        if (bytes[c] % stripe != 0 || bytes[c] >= (1ull << 36) || bytes[c] / (plan.p - 1) >= (16ull << 30)) return GS_EINVAL;
         max_bytes = std::max(max_bytes, bytes[c]);
     }
     if (max_bytes == 0) return GS_OK;

@@ -108,7 +108,8 @@ __global__ __launch_bounds__(kThreads) void rdp_kernel(const RdpArgs a)
 {
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
     constexpr uint32_t kPieces = kThreads / 64;  // one piece per wavefront
-    const uint64_t t = blockIdx.x;
+    // tiles beyond one grid row continue in the next (gridDim.x is a multiple of the interleave modulus)
+    const uint64_t t = static_cast<uint64_t>(blockIdx.y) * gridDim.x + blockIdx.x;
     const uint64_t g = t >> a.nx_shift, r = t & ((1ull << a.nx_shift) - 1);
     if (((g * kPieces) << a.nx_shift) * 64 >= a.nvb) return;
     const uint64_t v = ((((g * kPieces + wave) << a.nx_shift) + r) << 6) + lane;
@@ -466,9 +467,14 @@ hipError_t launch_rdp(const RdpPlan &plan, const void *const *shards, size_t sha
     while (nx_shift > 0 && (tile << nx_shift) > a.nvb) --nx_shift;
     const uint64_t super = tile << nx_shift;
     const uint64_t tiles = ((a.nvb + super - 1) / super) << nx_shift;
-    if (tiles >= (1ull << 23)) return hipErrorInvalidValue;  // launch limit on workgroups per dimension
+    // a grid row holds at most 2^22 workgroups (a power of two, so a multiple of the interleave modulus);
+    // longer shards take further rows
+    constexpr uint64_t kRowTiles = 1ull << 22;
+    const uint64_t grid_rows = (tiles + kRowTiles - 1) / kRowTiles;
+    if (grid_rows > 65535) return hipErrorInvalidValue;
     a.nx_shift = nx_shift;
-    const dim3 grid(static_cast<uint32_t>(tiles ? tiles : 1));
+    const dim3 grid(static_cast<uint32_t>(tiles <= kRowTiles ? (tiles ? tiles : 1) : kRowTiles),
+                    static_cast<uint32_t>(grid_rows ? grid_rows : 1));
 #define GS_RDP_CASE(P_) \
     case P_: return w == 2 ? launch_p<P_, 2>(a, n_out, grid, stream) : launch_p<P_, 4>(a, n_out, grid, stream);
     switch (plan.p) {

@@ -127,3 +127,55 @@ def test_one_million_token_context_of_the_8b_shape(gs):
 def test_shards_of_44_gib(gs):
     """k = 4, m = 1: shard offsets beyond 2^35 and more tiles than one launch has workgroups for."""
     run(gs, 4, 1, 44 * GiB, [2], 0x67532000)
+
+
+def test_rdp_shards_of_34_gib(gs):
+    """RDP with k = 2 (p = 3, stripes of two 32 KiB cells): shards of 34 GiB need more workgroups than one
+    grid row holds.  Row parity must equal the XOR of the data shards over the whole buffers (its
+    definition, computed with torch); sampled runs of whole stripes (both ends, both sides of every
+    4 GiB multiple, seeded random ones) go through the RDP oracle; both data shards are then lost and
+    must come back with the same digests and windows."""
+    k, cell = 2, 32768
+    S = 34 * GiB
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 4 * S + 24 * GiB:
+        pytest.skip("needs %.0f GiB of free device memory" % ((4 * S + 24 * GiB) / 2**30))
+    code = gs.gs_make_rdp_code(k, cell)
+    stripe = (gs.gs_rdp_prime(code) - 1) * cell
+    assert stripe == 2 * cell and S % stripe == 0
+    shards = [torch.empty(S, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    for j in range(k):
+        fill(shards[j], 0x67533000 + j)
+    for t in shards[k:]:
+        t.fill_(0xEE)
+    gs.gs_encode(code, shards[:k], shards[k:], S)
+    torch.cuda.synchronize()
+    for off in range(0, S, 2 * GiB):
+        a, b, p = (t[off:off + 2 * GiB].view(torch.int64) for t in (shards[0], shards[1], shards[2]))
+        assert torch.equal(a ^ b, p), "row parity differs in the piece at %d" % off
+    rng = np.random.default_rng(0x67533010)
+    n_stripes = S // stripe
+    first = [0, n_stripes - 3] + [mult // stripe - 1 for mult in range(4 * GiB, S, 4 * GiB)] + \
+            [int(x) for x in rng.integers(0, n_stripes - 3, size=6)]
+    win = [(s * stripe, 3 * stripe) for s in first]
+    for off, n in win:
+        host = [np.ascontiguousarray(t[off:off + n].cpu().numpy()) for t in shards[:k]]
+        want = oracle.rdp_encode(host, cell)
+        for i in range(2):
+            assert np.array_equal(shards[k + i][off:off + n].cpu().numpy(), want[i]), (i, off)
+    lost = [0, 1]
+    sums = {r: word_sum(shards[r]) for r in lost}
+    folds = {r: xor_fold(shards[r]) for r in lost}
+    keep = {r: [shards[r][off:off + n].clone() for off, n in win] for r in lost}
+    for r in lost:
+        shards[r].fill_(0xA5)
+    gs.gs_reconstruct(code, shards, lost, S)
+    torch.cuda.synchronize()
+    for r in lost:
+        assert word_sum(shards[r]) == sums[r], "word sum of shard %d differs" % r
+        assert np.array_equal(xor_fold(shards[r]), folds[r]), "fold of shard %d differs" % r
+        for (off, n), orig in zip(win, keep[r]):
+            assert torch.equal(shards[r][off:off + n], orig), (r, off)
+    del shards, keep
+    torch.cuda.empty_cache()
