@@ -325,8 +325,8 @@ int gs_rdp_plan(const gs_code *code, const int *missing, int n_missing, int *rea
  * calls do not wait for each other).  Codes with k <= 16 and m <= 4 only
  * (RDP codes included: then every chunk must be a whole number of stripes
  * and shorter than (p-1) x 16 GiB, else GS_EINVAL with nothing enqueued),
- * max_chunks <= 65535, chunks below 64 GiB.  One gs_batch serves one thread at a time.  The
- * descriptor slot is filled by the host at call time and may make the host
+ * max_chunks <= 65535, chunks below 16 GiB (longer ones: gs_encode).  One
+ * gs_batch serves one thread at a time.  The descriptor slot is filled by the host at call time and may make the host
  * wait for the launch that used it four calls earlier, so these two calls
  * must not be made on a stream that is being captured into a graph (the
  * single-chunk entry points can be).
@@ -353,7 +353,7 @@ int gs_reconstruct_batch(gs_batch *batch, int n_chunks, void *const *shards, con
  * a small kernel that receives them as launch arguments, so the call enqueues
  * kernel launches only -- no allocation, no copy, no host wait -- and may be
  * captured into a graph.
- *   n_chunks > GS_STATIC_MAX_CHUNKS, or a chunk of 64 GiB or more: GS_ELIMIT,
+ *   n_chunks > GS_STATIC_MAX_CHUNKS, or a chunk of 16 GiB or more: GS_ELIMIT,
  *   nothing enqueued.  Codes with k <= 16 and m <= 4 only, and no RDP code
  *   (else GS_EINVAL).
  * All calls on one device share that device's array, and a call overwrites

@@ -54,7 +54,7 @@ static int run_batch(gs_batch *b, int rows, const uint8_t *C, int n, const void 
     size_t max_bytes = 0;
     for (int c = 0; c < n; ++c) max_bytes = std::max(max_bytes, bytes[c]);
     if (max_bytes == 0) return GS_OK;
-    if (max_bytes >= (1ull << 36)) return GS_EINVAL;  // 64 GiB per stream and chunk
+    if (max_bytes >= (1ull << 34)) return GS_EINVAL;  // 16 GiB per stream and chunk: one tile per workgroup
     const unsigned slot = b->next % kRing;
     if (b->used[slot]) GS_TRY(hipEventSynchronize(b->done[slot]));
     uint8_t *hslot = b->host + static_cast<size_t>(slot) * b->slot_bytes;
@@ -84,7 +84,7 @@ static int run_rdp_batch(gs_batch *b, const RdpPlan &plan, int n, const void *co
     size_t max_bytes = 0;
     for (int c = 0; c < n; ++c) {
         // whole stripes, and what one launch covers: 16 GiB per stripe row (p = 3: chunks below 32 GiB)
-        if (bytes[c] % stripe != 0 || bytes[c] >= (1ull << 36) || bytes[c] / (plan.p - 1) >= (16ull << 30)) return GS_EINVAL;
+        if (bytes[c] % stripe != 0 || bytes[c] / (plan.p - 1) >= (16ull << 30)) return GS_EINVAL;
         max_bytes = std::max(max_bytes, bytes[c]);
     }
     if (max_bytes == 0) return GS_OK;

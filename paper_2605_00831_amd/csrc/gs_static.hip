@@ -92,7 +92,7 @@ try {
     size_t max_bytes = 0;
     for (int c = 0; c < n_chunks; ++c) {
         if (shard_bytes[c] == 0) continue;
-        if (shard_bytes[c] >= (1ull << 36)) return GS_ELIMIT;  // 64 GiB per stream and chunk
+        if (shard_bytes[c] >= (1ull << 34)) return GS_ELIMIT;  // 16 GiB per stream and chunk: one tile per workgroup
         for (int j = 0; j < k; ++j)
             if (data[c * k + j] == nullptr || !aligned16(data[c * k + j])) return GS_EINVAL;
         for (int i = 0; i < m; ++i)
