@@ -423,6 +423,15 @@ int gs_coef_words(int c, uint32_t *words_out);
  * gs_set_power_horner; both are atomic: a call running in another thread uses
  * either the old or the new setting as a whole. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
+/* Bulk launches of the contiguous, grouped, Horner and RDP kernels (16384
+ * workgroups and more, default vectors per lane and tiles per workgroup) ask
+ * for 52 or 64 KiB of LDS per workgroup that the kernels never touch, which
+ * keeps 3 or 2 workgroups on a CU instead of 8: that moves 1 to 4 points more
+ * of the HBM peak.  While such a kernel runs, other kernels that need LDS find
+ * little of it free on the same CUs; enable = 0 switches the reservation off
+ * (process-wide and atomic like the knobs above; gs_set_launch_shape leaves it
+ * as it is).  Results are identical either way.  Default: enabled. */
+int gs_set_occupancy_cap(int enable);
 /* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
  * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0
  * with g = 2^r; one packed multiply-by-2 per stream and row, no table

@@ -27,6 +27,7 @@ EXPORTS = [
     "gs_pool_create", "gs_pool_destroy", "gs_encode_streams", "gs_reconstruct_streams",
     "gs_recompute_units",
     "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape", "gs_set_power_horner",
+    "gs_set_occupancy_cap",
 ]
 
 _vp = ctypes.c_void_p
@@ -121,6 +122,7 @@ def lib():
     L.gs_coef_words.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_uint32)]
     L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.gs_set_power_horner.argtypes = [ctypes.c_int]
+    L.gs_set_occupancy_cap.argtypes = [ctypes.c_int]
     _lib = L
     return L
 
@@ -487,6 +489,10 @@ def gs_coef_words(c):
 
 def gs_set_power_horner(enable=True):
     _check(lib().gs_set_power_horner(1 if enable else 0), "gs_set_power_horner")
+
+
+def gs_set_occupancy_cap(enable=True):
+    _check(lib().gs_set_occupancy_cap(1 if enable else 0), "gs_set_occupancy_cap")
 
 
 def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1, interleave_shift=-1):

@@ -577,13 +577,13 @@ static bool fill_rows(Args &a, int rows, int k, const uint8_t *coef, int coef_st
 }
 
 template <template <int, bool, int, bool> class Launcher, typename Args>
-static hipError_t dispatch(int rows, bool row0_xor, int unroll, bool nt, const Args &a, dim3 grid,
+static hipError_t dispatch(int rows, bool row0_xor, int unroll, bool nt, const Args &a, dim3 grid, size_t lds,
                            hipStream_t stream)
 {
-#define GS_CASE_U(M_, X_, U_)                                              \
-    if (unroll == U_) {                                                    \
-        if (nt) return Launcher<M_, X_, U_, true>::go(a, grid, stream);    \
-        return Launcher<M_, X_, U_, false>::go(a, grid, stream);           \
+#define GS_CASE_U(M_, X_, U_)                                                   \
+    if (unroll == U_) {                                                         \
+        if (nt) return Launcher<M_, X_, U_, true>::go(a, grid, lds, stream);    \
+        return Launcher<M_, X_, U_, false>::go(a, grid, lds, stream);           \
     }
 #define GS_CASE_MX(M_, X_)  \
     if (rows == M_ && row0_xor == X_) { GS_CASE_U(M_, X_, 1) GS_CASE_U(M_, X_, 2) }
@@ -600,9 +600,9 @@ static hipError_t dispatch(int rows, bool row0_xor, int unroll, bool nt, const A
 
 template <int M, bool X, int U, bool NT>
 struct ContigLauncher {
-    static hipError_t go(const ApplyArgs &a, dim3 grid, hipStream_t stream)
+    static hipError_t go(const ApplyArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
-        hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
         return hipGetLastError();
     }
 };
@@ -615,7 +615,7 @@ struct PagedLauncher {
     {
         hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED>), grid, dim3(kThreads), 0, stream, a);
     }
-    static hipError_t go(const PagedArgs &a, dim3 grid, hipStream_t stream)
+    static hipError_t go(const PagedArgs &a, dim3 grid, size_t, hipStream_t stream)
     {
         const bool wave_page = a.vpp % 64 == 0;
         if (a.mixed) wave_page ? launch<true, true>(a, grid, stream) : launch<false, true>(a, grid, stream);
@@ -659,6 +659,20 @@ static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t
     tiles = ((nvec + super - 1) / super) << nx_shift;
 }
 
+// LDS reservation of a bulk launch of the contiguous or the grouped kernel at
+// two vectors per lane (measured on 2 to 16 GiB shards, 1+1 to 16+4).  Three
+// workgroups per CU gain 0.5 to 1.5 points of HBM peak for nearly every shape;
+// kernels that are all loads and XORs, with at least 8 KiB in flight per
+// wavefront, gain 2 to 3 points more with two; the four-row lookup kernel
+// needs all the wavefronts it can get.
+static size_t contig_reservation(const LaunchShape &shape, int unroll, int rows, bool row0_xor, int k, uint64_t workgroups)
+{
+    if (!shape.occupancy_cap || unroll != 2 || workgroups < kCapMinWorkgroups) return 0;
+    if (rows == 4 && !row0_xor) return 0;
+    if (row0_xor && ((rows == 1 && k >= 4) || (rows == 2 && k >= 8))) return lds_for_workgroups_per_cu(2);
+    return lds_for_workgroups_per_cu(3);
+}
+
 hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
                         const void *const *in, void *const *out, size_t bytes,
                         bool accumulate, const LaunchShape &shape, hipStream_t stream)
@@ -680,7 +694,8 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), stream);
+    const size_t lds = tpw == 1 ? contig_reservation(shape, unroll, rows, row0_xor, k, wgs) : 0;
+    return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds, stream);
 }
 
 hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, const void *const *in,
@@ -713,11 +728,14 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
     const bool nt = shape.nontemporal != 0;
-#define GS_HORNER(M_, U_)                                                                                     \
-    if (rows == M_ && unroll == U_) {                                                                         \
-        if (nt) hipLaunchKernelGGL((horner_contig_kernel<M_, U_, true>), dim3(wgs), dim3(kThreads), 0, stream, a); \
-        else hipLaunchKernelGGL((horner_contig_kernel<M_, U_, false>), dim3(wgs), dim3(kThreads), 0, stream, a);   \
-        return hipGetLastError();                                                                             \
+    // no lookups, a few shifts and XORs per load: two workgroups per CU once a wavefront has 8 KiB in flight
+    const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroups && k >= 4)
+                           ? lds_for_workgroups_per_cu(2) : 0;
+#define GS_HORNER(M_, U_)                                                                                       \
+    if (rows == M_ && unroll == U_) {                                                                           \
+        if (nt) hipLaunchKernelGGL((horner_contig_kernel<M_, U_, true>), dim3(wgs), dim3(kThreads), lds, stream, a); \
+        else hipLaunchKernelGGL((horner_contig_kernel<M_, U_, false>), dim3(wgs), dim3(kThreads), lds, stream, a);   \
+        return hipGetLastError();                                                                               \
     }
     GS_HORNER(2, 1) GS_HORNER(2, 2) GS_HORNER(3, 1) GS_HORNER(3, 2)
 #undef GS_HORNER
@@ -726,9 +744,9 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
 
 template <int M, bool X, int U, bool NT>
 struct BatchLauncher {
-    static hipError_t go(const BatchArgs &a, dim3 grid, hipStream_t stream)
+    static hipError_t go(const BatchArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
-        hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
         return hipGetLastError();
     }
 };
@@ -778,8 +796,11 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
     uint32_t tpw = 1, wgs = 1;
     grid_for(tiles, tpw, wgs);
     if (tpw != 1) return hipErrorInvalidValue;  // chunks this large go through launch_apply
+    // the grouped kernel keeps to three workgroups per CU: its chunks differ in length, and two starve short ones
+    size_t lds = contig_reservation(shape, unroll, rows, p.row0_xor, k, static_cast<uint64_t>(wgs) * n_chunks);
+    if (lds > lds_for_workgroups_per_cu(3)) lds = lds_for_workgroups_per_cu(3);
     return dispatch<BatchLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
-                                   dim3(wgs, static_cast<uint32_t>(n_chunks)), stream);
+                                   dim3(wgs, static_cast<uint32_t>(n_chunks)), lds, stream);
 }
 
 hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_stride,
@@ -849,8 +870,9 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
+    // one vector per lane: the gather needs every wavefront the registers allow, no reservation
     return dispatch<PagedLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
-                                   dim3(wgs, static_cast<uint32_t>(n_planes)), stream);
+                                   dim3(wgs, static_cast<uint32_t>(n_planes)), 0, stream);
 }
 
 }  // namespace gs

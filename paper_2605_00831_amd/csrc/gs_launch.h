@@ -15,7 +15,19 @@ struct LaunchShape {
     int tiles_per_wg;  // consecutive tiles per workgroup
     int nontemporal;   // streaming cache policy on loads and stores
     int interleave_shift;  // log2 of the XCD interleave modulus of the contiguous kernel (0 = off)
+    int occupancy_cap;     // bulk launches reserve LDS so that fewer workgroups share a CU (see lds_for_workgroups_per_cu)
 };
+
+// Resident workgroups per CU are limited by handing every workgroup a slice of
+// the CU's 160 KiB of LDS that it never touches.  The streaming kernels move
+// more bytes per second with 2 or 3 workgroups (8 or 12 wavefronts) on a CU
+// than with the 8 their registers allow: fewer super-tiles are open at once in
+// the memory system.  Which count is best depends on how many loads a
+// wavefront keeps in flight and on its arithmetic, so each launcher picks it
+// per kernel variant; launches too small to fill the chip several times over
+// are left alone.  0 = no reservation.
+constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : 0; }
+constexpr uint64_t kCapMinWorkgroups = 16384;  // below this a launch keeps the default occupancy
 
 // One launch: out[r] (r < rows <= 4) = XOR_j coef[r*coef_stride + j] (x) in[j], j < k <= 16,
 // over `bytes` bytes; with accumulate the previous contents of out[r] are XORed in.

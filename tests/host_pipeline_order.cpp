@@ -51,6 +51,8 @@ struct Op {
     const void *dst, *src;      // copies
     size_t bytes;
     hipMemcpyKind dir;
+    size_t shmem;               // launches: dynamic LDS asked for
+    unsigned grid_x, grid_y;
 };
 
 struct Event { int vc[kMaxStreams]; bool recorded; };
@@ -200,10 +202,13 @@ hipError_t __hipPopCallConfiguration(dim3 *grid, dim3 *block, size_t *shmem, hip
     *grid = cfg_grid; *block = cfg_block; *shmem = cfg_shmem; *stream = cfg_stream;
     return hipSuccess;
 }
-hipError_t hipLaunchKernel(const void *, dim3 grid, dim3 block, void **, size_t, hipStream_t s)
+hipError_t hipLaunchKernel(const void *, dim3 grid, dim3 block, void **, size_t shmem, hipStream_t s)
 {
     if (grid.x == 0 || grid.y == 0 || grid.z == 0 || block.x != 256) return hipErrorInvalidConfiguration;
-    enqueue(LAUNCH, s);
+    Op &op = enqueue(LAUNCH, s);
+    op.shmem = shmem;
+    op.grid_x = grid.x;
+    op.grid_y = grid.y;
     return hipSuccess;
 }
 
@@ -383,6 +388,72 @@ static int check_pool(int n_streams, int n_chunks)
     gs_pool_destroy(pool);
     EXPECT(hipStreamDestroy(cs) == hipSuccess);
     gs_free_code(code);
+    return 0;
+}
+
+// Which launches ask for LDS they never use (to keep 2 or 3 workgroups on a CU instead of 8): bulk
+// launches of the contiguous, Horner, grouped and RDP kernels at the default launch shape, by kernel
+// variant; never the paged gather, never a small launch, never with the switch off.
+static int check_occupancy_reservation()
+{
+    const size_t two = 65536, three = 53248;
+    hipStream_t s = nullptr;
+    EXPECT(hipStreamCreateWithFlags(&s, 0) == hipSuccess);
+    std::vector<void *> ptr(24);
+    for (size_t i = 0; i < ptr.size(); ++i) ptr[i] = reinterpret_cast<void *>(0x100000000ull + 0x800000000ull * i);
+    auto lds_of = [&](gs_code *code, size_t bytes, const int *erased, int n_erased) -> long {
+        reset_record();
+        int k = 0, m = 0;
+        if (gs_code_params(code, &k, &m) != GS_OK) return -1;
+        const int rc = n_erased ? gs_reconstruct(code, ptr.data(), erased, n_erased, bytes, s)
+                                : gs_encode(code, ptr.data(), ptr.data() + k, bytes, s);
+        if (rc != GS_OK || ops.size() != 1 || ops[0].kind != LAUNCH) return -1;
+        return static_cast<long>(ops[0].shmem);
+    };
+    const size_t big = 1ull << 30, small = 1ull << 20;
+    const int e1[1] = {1}, e2[2] = {1, 3}, e4[4] = {0, 1, 2, 3};
+    struct Case { int k, m, kind; const int *erased; int n_erased; size_t want; } cases[] = {
+        {4, 2, GS_CAUCHY, nullptr, 0, three}, {4, 2, GS_CAUCHY, e2, 2, three},   // the 8B workload
+        {8, 2, GS_CAUCHY, nullptr, 0, two},   {8, 2, GS_CAUCHY, e2, 2, three},   // the 70B workload: XOR row + one lookup row
+        {8, 3, GS_CAUCHY, nullptr, 0, three}, {4, 1, GS_CAUCHY, nullptr, 0, two}, {2, 1, GS_CAUCHY, nullptr, 0, three},
+        {8, 4, GS_CAUCHY, nullptr, 0, three}, {8, 4, GS_CAUCHY, e4, 4, 0},       // four lookup rows: left alone
+        {8, 3, GS_POWER, nullptr, 0, two},    {2, 2, GS_POWER, nullptr, 0, 0},   // Horner kernel
+        {2, 2, GS_RDP, nullptr, 0, 0},        {4, 2, GS_RDP, nullptr, 0, three}, {6, 2, GS_RDP, e1, 1, three},
+        {10, 2, GS_RDP, nullptr, 0, two},     {16, 2, GS_RDP, e2, 2, two},
+    };
+    for (const Case &c : cases) {
+        gs_code *code = nullptr;
+        EXPECT(gs_make_code(c.k, c.m, c.kind, &code) == GS_OK);
+        size_t unit = 1;
+        if (c.kind == GS_RDP) {
+            int p = 0;
+            size_t cell = 0;
+            EXPECT(gs_rdp_prime(code, &p) == GS_OK && gs_rdp_cell_bytes(code, &cell) == GS_OK);
+            unit = cell * static_cast<size_t>(p - 1);
+        }
+        const size_t B = big / unit * unit, Sm = small < unit ? unit : small / unit * unit;
+        EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.want));
+        EXPECT(lds_of(code, Sm, c.erased, c.n_erased) == 0);           // a small launch keeps every wavefront
+        EXPECT(gs_set_occupancy_cap(0) == GS_OK);
+        EXPECT(lds_of(code, B, c.erased, c.n_erased) == 0);
+        EXPECT(gs_set_occupancy_cap(1) == GS_OK);
+        EXPECT(gs_set_launch_shape(1, 0, -1, -1) == GS_OK);            // another vector count: no reservation
+        EXPECT(lds_of(code, B, c.erased, c.n_erased) == 0 || c.kind == GS_RDP);
+        EXPECT(gs_set_launch_shape(0, 0, -1, -1) == GS_OK);
+        EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.want));   // the shape knobs left the switch on
+        gs_free_code(code);
+    }
+    // the paged gather never reserves
+    {
+        gs_code *code = nullptr;
+        EXPECT(gs_make_code(4, 2, GS_CAUCHY, &code) == GS_OK);
+        reset_record();
+        EXPECT(gs_encode_paged(code, reinterpret_cast<const void *const *>(ptr[0]), 64, 32768, 1 << 20,
+                               reinterpret_cast<const int32_t *>(ptr[1]), 4096, ptr.data() + 4, s) == GS_OK);
+        EXPECT(ops.size() == 1 && ops[0].kind == LAUNCH && ops[0].shmem == 0);
+        gs_free_code(code);
+    }
+    EXPECT(hipStreamDestroy(s) == hipSuccess);
     return 0;
 }
 
@@ -695,6 +766,7 @@ int main()
     if (check_paged_pipelines(2) || check_paged_pipelines(3)) return 1;
     if (check_pipeline_failures()) return 1;
     if (check_pool(4, 11) || check_pool(16, 3) || check_pool(1, 5)) return 1;
+    if (check_occupancy_reservation()) return 1;
     if (check_ring()) return 1;
     if (check_rdp_ring()) return 1;
     if (check_step_graph()) return 1;

@@ -531,3 +531,55 @@ def test_paged_encode_at_the_largest_plane_count(gs):
         check_out(par[i], want[i])
     with pytest.raises(gs.GsError):
         gs.gs_encode_paged(code, base, n_planes + 1, page, num_pages, dev(table_np), pps, par)
+
+
+def test_occupancy_reservation_changes_no_byte(gs):
+    # bulk launches with and without the LDS reservation that limits the workgroups per CU: the same bytes,
+    # and the oracle's on sampled windows (GF(2^8), Horner and RDP kernels, the grouped launch)
+    S = 320 << 20
+    rng = np.random.default_rng(99)
+    cases = [("cauchy", 4, 2), ("cauchy", 8, 1), ("power", 8, 3), ("rdp", 8, 2)]
+    try:
+        for kind, k, m in cases:
+            if kind == "rdp":
+                code = gs.gs_make_rdp_code(k, 32768)
+                unit = (gs.gs_rdp_prime(code) - 1) * 32768
+            else:
+                code = gs.gs_make_code(k, m, gs.GS_POWER if kind == "power" else gs.GS_CAUCHY)
+                P = oracle.power_generator(k, m) if kind == "power" else oracle.generator(k, m)
+                unit = 1
+            Sk = S // unit * unit
+            data = [torch.empty(Sk, dtype=torch.uint8, device="cuda").random_(0, 256) for _ in range(k)]
+            outs = []
+            for on in (1, 0):
+                gs.gs_set_occupancy_cap(on)
+                par = [torch.full((Sk + PAD,), CANARY, dtype=torch.uint8, device="cuda") for _ in range(m)]
+                gs.gs_encode(code, data, par, Sk)
+                torch.cuda.synchronize()
+                outs.append(par)
+            for i in range(m):
+                assert torch.equal(outs[0][i], outs[1][i]), (kind, k, m, i)
+                assert (outs[0][i][Sk:] == CANARY).all()
+            for _ in range(3):
+                off = int(rng.integers(0, Sk // unit - 1)) * unit
+                n = unit if kind == "rdp" else int(rng.integers(1, 100000))
+                n = min(n, Sk - off)
+                host = [np.ascontiguousarray(d[off:off + n].cpu().numpy()) for d in data]
+                want = oracle.rdp_encode(host, 32768) if kind == "rdp" else oracle.encode(P, host, nthreads=8)
+                for i in range(m):
+                    assert np.array_equal(outs[0][i][off:off + n].cpu().numpy(), want[i]), (kind, k, m, off, i)
+            # rebuild of a lost data shard under both settings
+            lost = [1] if m == 1 else [1, k]
+            for on in (1, 0):
+                gs.gs_set_occupancy_cap(on)
+                shards = data + [p[:Sk] for p in outs[0]]
+                keep = [shards[r].clone() for r in lost]
+                for r in lost:
+                    shards[r].fill_(0xA5)
+                gs.gs_reconstruct(code, shards, lost, Sk)
+                torch.cuda.synchronize()
+                for r, orig in zip(lost, keep):
+                    assert torch.equal(shards[r], orig), (kind, k, m, on, r)
+            del data, outs, shards, keep
+    finally:
+        gs.gs_set_occupancy_cap(1)
