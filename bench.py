@@ -162,6 +162,8 @@ def main():
     ap.add_argument("--launch-shape", default=None, metavar="U,T,NT,ILV",
                     help="gs_set_launch_shape(unroll, tiles_per_wg, nontemporal, interleave_shift) for sweeps; "
                          "0 / -1 keep a knob's default")
+    ap.add_argument("--no-occupancy-cap", action="store_true",
+                    help="gs_set_occupancy_cap(0): bulk launches without the LDS reservation that limits workgroups per CU")
     ap.add_argument("--only", default=None, choices=["headline", "paged_bulk", "rdp_forms"],
                     help="headline: the timed steps of --workload and its extras, not the other bulk workloads; "
                          "paged_bulk / rdp_forms: only that leg (for profiling runs)")
@@ -191,6 +193,8 @@ def main():
     if args.launch_shape:
         u, t, nt, ilv = (int(x) for x in args.launch_shape.split(","))
         gs.gs_set_launch_shape(u, t, nt, ilv)
+    if args.no_occupancy_cap:
+        gs.gs_set_occupancy_cap(False)
     if args.only is None:
         device_arena(torch, 50 << 30)   # the 70B workload with its parity: the largest of the bulk workloads
     if not args.no_extras:
@@ -287,7 +291,7 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "algorithmic_bytes_per_launch": enc_alg_bytes,
             "avg_launch_ms": round(enc_avg, 4),
-            **traffic_fields(args.workload, args.code, args.launch_shape is None),
+            **traffic_fields(args.workload, args.code, args.launch_shape is None and not args.no_occupancy_cap),
         },
     }
 
@@ -313,7 +317,8 @@ def main():
         for name in ("llama8b_prefill", "llama70b_longctx", "recovery_stress"):
             if name != args.workload:
                 out["configs"].append(bulk_config(torch, gs, inputs, name, max(args.steps, 20), args.warmup, log,
-                                                  pipelines=not args.no_extras, default_shape=args.launch_shape is None))
+                                                  pipelines=not args.no_extras,
+                                                  default_shape=args.launch_shape is None and not args.no_occupancy_cap))
         out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
         out["code_shapes"] = code_shapes(torch, gs, log)
         out["rdp_forms"] = rdp_forms(torch, gs, inputs, log)

@@ -664,11 +664,11 @@ static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t
 // workgroups per CU gain 0.5 to 1.5 points of HBM peak for nearly every shape;
 // kernels that are all loads and XORs, with at least 8 KiB in flight per
 // wavefront, gain 2 to 3 points more with two; the four-row lookup kernel
-// needs all the wavefronts it can get.
+// and one-row kernels over one or two streams need all the wavefronts they can get.
 static size_t contig_reservation(const LaunchShape &shape, int unroll, int rows, bool row0_xor, int k, uint64_t workgroups)
 {
     if (!shape.occupancy_cap || unroll != 2 || workgroups < kCapMinWorkgroups) return 0;
-    if (rows == 4 && !row0_xor) return 0;
+    if ((rows == 4 && !row0_xor) || (rows == 1 && k < 4)) return 0;
     if (row0_xor && ((rows == 1 && k >= 4) || (rows == 2 && k >= 8))) return lds_for_workgroups_per_cu(2);
     return lds_for_workgroups_per_cu(3);
 }

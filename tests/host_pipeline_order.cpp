@@ -415,7 +415,7 @@ static int check_occupancy_reservation()
     struct Case { int k, m, kind; const int *erased; int n_erased; size_t want; } cases[] = {
         {4, 2, GS_CAUCHY, nullptr, 0, three}, {4, 2, GS_CAUCHY, e2, 2, three},   // the 8B workload
         {8, 2, GS_CAUCHY, nullptr, 0, two},   {8, 2, GS_CAUCHY, e2, 2, three},   // the 70B workload: XOR row + one lookup row
-        {8, 3, GS_CAUCHY, nullptr, 0, three}, {4, 1, GS_CAUCHY, nullptr, 0, two}, {2, 1, GS_CAUCHY, nullptr, 0, three},
+        {8, 3, GS_CAUCHY, nullptr, 0, three}, {4, 1, GS_CAUCHY, nullptr, 0, two}, {2, 1, GS_CAUCHY, nullptr, 0, 0}, {2, 2, GS_CAUCHY, nullptr, 0, three},
         {8, 4, GS_CAUCHY, nullptr, 0, three}, {8, 4, GS_CAUCHY, e4, 4, 0},       // four lookup rows: left alone
         {8, 3, GS_POWER, nullptr, 0, two},    {2, 2, GS_POWER, nullptr, 0, 0},   // Horner kernel
         {2, 2, GS_RDP, nullptr, 0, 0},        {4, 2, GS_RDP, nullptr, 0, three}, {6, 2, GS_RDP, e1, 1, three},
