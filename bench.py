@@ -34,13 +34,13 @@ PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 # valid for the kernel template and the default launch shape named beside it;
 # a run with another launch shape reports null.
 MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE and WRITE_SIZE scaled to bytes, kernel, profile)
-    ("llama8b_prefill", "cauchy"): (51539161269, "apply_contig_kernel<2, true, 2, true>",
+    ("llama8b_prefill", "cauchy"): (51539328314, "apply_contig_kernel<2, true, 2, true>",
                                     "profiles/encode_contig_llama8b_prefill.md"),
-    ("llama8b_prefill", "power"): (51539042211, "horner_contig_kernel<2, 2, true>",
+    ("llama8b_prefill", "power"): (51540440276, "horner_contig_kernel<2, 2, true>",
                                    "profiles/horner_power_code_llama8b_prefill.md"),
-    ("llama70b_longctx", "cauchy"): (53685737460, "apply_contig_kernel<2, true, 2, true>",
+    ("llama70b_longctx", "cauchy"): (53686558114, "apply_contig_kernel<2, true, 2, true>",
                                      "profiles/encode_contig_llama70b_longctx.md"),
-    ("recovery_stress", "cauchy"): (5905626583, "apply_contig_kernel<3, true, 2, true>",
+    ("recovery_stress", "cauchy"): (5905735985, "apply_contig_kernel<3, true, 2, true>",
                                     "profiles/encode_contig_recovery_stress.md"),
 }
 
@@ -51,7 +51,7 @@ def traffic_fields(workload, code, default_shape):
         return {"traffic": None, "traffic_source": None if t is None else
                 "not reported: the launch shape of this run differs from the profiled one (%s)" % t[2]}
     return {"traffic": t[0], "traffic_source": "%s: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of %s at the default launch "
-                                               "shape, an earlier run of this command (not re-measured by this run)" % (t[2], t[1])}
+                                               "shape (LDS reservation on), an earlier run of this command (not re-measured by this run)" % (t[2], t[1])}
 
 
 NATIVE_SRC = os.path.join(ROOT, "bench_native.c")

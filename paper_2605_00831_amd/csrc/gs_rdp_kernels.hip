@@ -156,11 +156,18 @@ __global__ __launch_bounds__(kThreads) void rdp_batch_kernel(const RdpBatchArgs 
 
 // LDS reservation of a bulk RDP launch (8-byte vectors; measured for every prime on 2 GiB shards):
 // a wavefront of p = 3 has two loads per disk in flight and needs full occupancy; p = 5 and 7 gain
-// 2 to 5 points of HBM peak with three workgroups per CU, p >= 11 with two.
-static size_t rdp_reservation(const LaunchShape &shape, int p, int w, uint64_t workgroups)
+// 2 to 5 points of HBM peak with three workgroups per CU, p >= 11 with two -- except the rebuild of two
+// shards at p = 11 and 13, whose cells are XORs of many syndromes: its arithmetic wants the third workgroup
+// (at p = 17 the registers allow no more than three anyway).
+static size_t rdp_reservation(const LaunchShape &shape, const RdpPlan &plan, int w, uint64_t workgroups)
 {
+    const int p = plan.p;
     if (!shape.occupancy_cap || w != 2 || workgroups < kCapMinWorkgroups || p < 5) return 0;
-    return lds_for_workgroups_per_cu(p >= 11 ? 2 : 3);
+    if (p < 11) return lds_for_workgroups_per_cu(3);
+    size_t bits = 0;
+    for (uint32_t m : plan.syndrome_mask) bits += static_cast<size_t>(__builtin_popcount(m));
+    const bool dense = bits > 4 * plan.syndrome_mask.size();
+    return lds_for_workgroups_per_cu(dense && p < 17 ? 3 : 2);
 }
 
 static uint32_t rdp_interleave_shift(uint64_t nvb, const LaunchShape &shape, uint64_t *tiles)
@@ -221,7 +228,7 @@ hipError_t launch_rdp_batch(const RdpPlan &plan, const void *descs_dev, int n_ch
     if (tiles >= (1ull << 23)) return hipErrorInvalidValue;
     const dim3 grid(static_cast<uint32_t>(tiles ? tiles : 1), static_cast<uint32_t>(n_chunks));
     // chunks differ in length: never fewer than three workgroups per CU
-    size_t lds = rdp_reservation(shape, plan.p, kRdpBatchW, tiles * static_cast<uint64_t>(n_chunks));
+    size_t lds = rdp_reservation(shape, plan, kRdpBatchW, tiles * static_cast<uint64_t>(n_chunks));
     if (lds > lds_for_workgroups_per_cu(3)) lds = lds_for_workgroups_per_cu(3);
 #define GS_RDP_BATCH_CASE(P_) case P_: return launch_batch_p<P_>(a, n_out, grid, lds, stream);
     switch (plan.p) {
@@ -487,7 +494,7 @@ hipError_t launch_rdp(const RdpPlan &plan, const void *const *shards, size_t sha
     a.nx_shift = nx_shift;
     const dim3 grid(static_cast<uint32_t>(tiles <= kRowTiles ? (tiles ? tiles : 1) : kRowTiles),
                     static_cast<uint32_t>(grid_rows ? grid_rows : 1));
-    const size_t lds = rdp_reservation(shape, plan.p, w, tiles);
+    const size_t lds = rdp_reservation(shape, plan, w, tiles);
 #define GS_RDP_CASE(P_) \
     case P_: return w == 2 ? launch_p<P_, 2>(a, n_out, grid, lds, stream) : launch_p<P_, 4>(a, n_out, grid, lds, stream);
     switch (plan.p) {

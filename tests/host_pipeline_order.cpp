@@ -419,7 +419,8 @@ static int check_occupancy_reservation()
         {8, 4, GS_CAUCHY, nullptr, 0, three}, {8, 4, GS_CAUCHY, e4, 4, 0},       // four lookup rows: left alone
         {8, 3, GS_POWER, nullptr, 0, two},    {2, 2, GS_POWER, nullptr, 0, 0},   // Horner kernel
         {2, 2, GS_RDP, nullptr, 0, 0},        {4, 2, GS_RDP, nullptr, 0, three}, {6, 2, GS_RDP, e1, 1, three},
-        {10, 2, GS_RDP, nullptr, 0, two},     {16, 2, GS_RDP, e2, 2, two},
+        {10, 2, GS_RDP, nullptr, 0, two},     {10, 2, GS_RDP, e2, 2, three},     {10, 2, GS_RDP, e1, 1, two},
+        {16, 2, GS_RDP, e2, 2, two},
     };
     for (const Case &c : cases) {
         gs_code *code = nullptr;
