@@ -447,7 +447,7 @@ def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
     """Bulk paged gather (the recovery-stress shape on a paged pool): 64 planes of 272 MiB, shards of
     2 GiB gathered through a block table, 32 KiB pages (16-token blocks) and 2 KiB pages (token slots),
     behind a seeded random permutation and, as controls, behind identity tables and behind permutations
-    of runs of consecutive pages; 4+2 and 8+3.
+    of runs of consecutive pages; 4+2, 8+3 and the paper's default ratio 8+2.
     Each case: events around 10 launches on the launch stream.  Then the paged checkpoint / restore
     pipelines (8+3, 32 KiB pages, shards {2, 5} and parity shard 9 lost)."""
     dev = "cuda:0"
@@ -487,7 +487,7 @@ def paged_bulk(torch, gs, inputs, log, pipelines=True, calibrate=False):
         for tname, tab in variants:
             table = torch.from_numpy(np.ascontiguousarray(tab.astype(np.int32))).to(dev)
             tables[(page, tname)] = table
-            for k, m in ((4, 2), (8, 3)):
+            for k, m in ((4, 2), (8, 3), (8, 2)):
                 code = gs.gs_make_code(k, m)
                 fn = lambda: gs.gs_encode_paged(code, base, n_planes, page, ppp, table, pps, par[:m])
                 for _ in range(3):

@@ -611,15 +611,15 @@ struct ContigLauncher {
 template <int M, bool X, int U, bool NT>
 struct PagedLauncher {
     template <bool WAVE_PAGE, bool MIXED>
-    static void launch(const PagedArgs &a, dim3 grid, hipStream_t stream)
+    static void launch(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
-        hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED>), grid, dim3(kThreads), 0, stream, a);
+        hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED>), grid, dim3(kThreads), lds, stream, a);
     }
-    static hipError_t go(const PagedArgs &a, dim3 grid, size_t, hipStream_t stream)
+    static hipError_t go(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
         const bool wave_page = a.vpp % 64 == 0;
-        if (a.mixed) wave_page ? launch<true, true>(a, grid, stream) : launch<false, true>(a, grid, stream);
-        else wave_page ? launch<true, false>(a, grid, stream) : launch<false, false>(a, grid, stream);
+        if (a.mixed) wave_page ? launch<true, true>(a, grid, lds, stream) : launch<false, true>(a, grid, lds, stream);
+        else wave_page ? launch<true, false>(a, grid, lds, stream) : launch<false, false>(a, grid, lds, stream);
         return hipGetLastError();
     }
 };
@@ -870,9 +870,14 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    // one vector per lane: the gather needs every wavefront the registers allow, no reservation
+    // One vector per lane: the gather needs most of the wavefronts the registers allow.  Only the bulk
+    // encode of a wide code with one or two rows (8+1, 8+2, 16+2: eight loads and more per store) runs
+    // faster with four workgroups per CU (+2 to +4 points of HBM peak behind a random table); three-row
+    // kernels and rebuilds into pages lose 7 to 17 points under any reservation.
+    const bool reserve = shape.occupancy_cap && !a.mixed && unroll == 1 && rows <= 2 && k >= 8 && tpw == 1 &&
+                         static_cast<uint64_t>(wgs) * n_planes >= kCapMinWorkgroups;
     return dispatch<PagedLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
-                                   dim3(wgs, static_cast<uint32_t>(n_planes)), 0, stream);
+                                   dim3(wgs, static_cast<uint32_t>(n_planes)), reserve ? lds_for_workgroups_per_cu(4) : 0, stream);
 }
 
 }  // namespace gs

@@ -26,7 +26,7 @@ struct LaunchShape {
 // wavefront keeps in flight and on its arithmetic, so each launcher picks it
 // per kernel variant; launches too small to fill the chip several times over
 // are left alone.  0 = no reservation.
-constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : 0; }
+constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : n == 4 ? 40960 : 0; }
 constexpr uint64_t kCapMinWorkgroups = 16384;  // below this a launch keeps the default occupancy
 
 // One launch: out[r] (r < rows <= 4) = XOR_j coef[r*coef_stride + j] (x) in[j], j < k <= 16,

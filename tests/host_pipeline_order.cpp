@@ -444,13 +444,22 @@ static int check_occupancy_reservation()
         EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.want));   // the shape knobs left the switch on
         gs_free_code(code);
     }
-    // the paged gather never reserves
-    {
+    // the paged gather keeps full occupancy, except the bulk encode of a wide code with one or two rows
+    struct Paged { int k, m; int pages_per_shard; size_t want; } paged[] = {
+        {4, 2, 4096, 0}, {8, 3, 4096, 0}, {8, 2, 4096, 40960}, {16, 1, 4096, 40960}, {8, 2, 16, 0},
+    };
+    for (const Paged &c : paged) {
         gs_code *code = nullptr;
-        EXPECT(gs_make_code(4, 2, GS_CAUCHY, &code) == GS_OK);
+        EXPECT(gs_make_code(c.k, c.m, GS_CAUCHY, &code) == GS_OK);
         reset_record();
         EXPECT(gs_encode_paged(code, reinterpret_cast<const void *const *>(ptr[0]), 64, 32768, 1 << 20,
-                               reinterpret_cast<const int32_t *>(ptr[1]), 4096, ptr.data() + 4, s) == GS_OK);
+                               reinterpret_cast<const int32_t *>(ptr[1]), c.pages_per_shard, ptr.data() + 4, s) == GS_OK);
+        EXPECT(ops.size() == 1 && ops[0].kind == LAUNCH && ops[0].shmem == c.want);
+        // a rebuild into pages never reserves
+        const int lost[1] = {1};
+        reset_record();
+        EXPECT(gs_reconstruct_paged(code, reinterpret_cast<const void *const *>(ptr[0]), 64, 32768, 1 << 20,
+                                    reinterpret_cast<const int32_t *>(ptr[1]), c.pages_per_shard, ptr.data() + 4, lost, 1, s) == GS_OK);
         EXPECT(ops.size() == 1 && ops[0].kind == LAUNCH && ops[0].shmem == 0);
         gs_free_code(code);
     }
