@@ -425,16 +425,18 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     };
     // stream j at vector u: from its page, or from the dense layout
     const int32_t first_row = a.in_row[0];
+    // No branch on the kind of stream: base and index are selected (the kind is wavefront-uniform), so
+    // the loads of a batch of streams are issued together.  A dense stream still looks up table row 0,
+    // which is always there, and ignores the entry.
     auto gather = [&](int j, int u) -> u32x4 {
         const int32_t row = MIXED ? a.in_row[j] : first_row + j;
-        if (MIXED && row < 0) {
-            const u32x4 x = load16<NT>(a.in_ptr[j], static_cast<uint64_t>(plane) * a.in_stride[j] + v[u]);
-            return ok[u] ? x : u32x4{0, 0, 0, 0};
-        }
-        const int64_t page = page_of(row, u);
-        const bool valid = ok[u] && page >= 0;
-        const uint64_t src = valid ? static_cast<uint64_t>(page) * a.vpp + off[u] : 0ull;
-        const u32x4 x = load16<NT>(pbase, src);
+        const bool dense = MIXED && row < 0;
+        const int64_t page = page_of(dense ? 0 : row, u);
+        const bool valid = ok[u] && (dense || page >= 0);
+        const uint8_t *base = dense ? a.in_ptr[j] : pbase;
+        const uint64_t idx = dense ? static_cast<uint64_t>(plane) * a.in_stride[j] + v[u]
+                                   : static_cast<uint64_t>(page) * a.vpp + off[u];
+        const u32x4 x = load16<NT>(base, valid ? idx : 0ull);
         return valid ? x : u32x4{0, 0, 0, 0};
     };
     // where output r of vector u lives; nullptr if it must not be touched
