@@ -205,7 +205,7 @@ __device__ __forceinline__ void horner_step(Acc4 (&acc)[M][U], const u32x4 (&x)[
     }
 }
 
-constexpr int kBatch = 4;  // streams whose loads are issued together
+constexpr int kPagedBatch = 4;  // paged gather: streams whose loads are issued together
 
 // One tile over contiguous streams: each lane handles the U vectors v[0..U).
 // FULL tiles (every lane in range) carry no predication at all; only tiles
@@ -236,26 +236,12 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
                 if (ok[u]) acc[r][u] = from_vec(load_piece<NT>(s.out[r], piece[u], lane));
     }
 
-    int j = 0;
-    for (; j + kBatch <= k; j += kBatch) {
-        const uint8_t *src[kBatch];
-#pragma unroll
-        for (int b = 0; b < kBatch; ++b) src[b] = s.in[HORNER ? k - 1 - (j + b) : j + b];
-        u32x4 x[kBatch][U];
-#pragma unroll
-        for (int b = 0; b < kBatch; ++b)
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                x[b][u] = u32x4{0, 0, 0, 0};
-                if (ok[u]) x[b][u] = load_piece<NT>(src[b], piece[u], lane);
-            }
-#pragma unroll
-        for (int b = 0; b < kBatch; ++b) {
-            if constexpr (HORNER) horner_step<M, U>(acc, x[b]);
-            else mac<M, ROW0_XOR, U>(acc, x[b], tab, j + b);
-        }
-    }
-    for (; j < k; ++j) {
+    // One stream at a time: a wavefront has the U loads of one stream in flight, does that stream's
+    // arithmetic, and goes on to the next stream.  Overlap comes from the other wavefronts of the CU
+    // (12 to 16 of them, see the LDS reservation of the launchers).  Issuing the loads of two or four
+    // streams together, which looks like the obvious way to keep more bytes in flight, is 1 to 5 points
+    // of HBM peak slower for every code shape at every occupancy.
+    for (int j = 0; j < k; ++j) {
         const uint8_t *src = s.in[HORNER ? k - 1 - j : j];
         u32x4 x[U];
 #pragma unroll
@@ -274,13 +260,12 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
             if (ok[u]) store_piece<NT>(s.out[r], piece[u], lane, to_vec(acc[r][u]));
 }
 
-// Occupancy the register allocator is asked to reach (wavefronts per SIMD).
-// The path is bandwidth-bound: many resident wavefronts with a few loads each
-// beat few wavefronts with long dependency-free instruction runs.  The
-// allocator fills whatever budget it is given to hoist loads, and runs over
-// it into scratch memory for the widest variants, so those get a larger budget
-// (BATCH: pointers and lengths come from a descriptor in memory, which costs
-// a few registers more).
+// Register budget of a kernel variant, as the occupancy (wavefronts per SIMD)
+// the allocator must still be able to reach.  The allocator fills whatever
+// budget it is given and runs over it into scratch memory for the widest
+// variants, so those get a larger budget (BATCH: pointers and lengths come
+// from a descriptor in memory, which costs a few registers more).  How many
+// wavefronts really share a CU is decided at launch (LDS reservation).
 template <int M, bool ROW0_XOR, int U, bool BATCH = false>
 constexpr int kWavesPerEu()
 {
@@ -459,14 +444,14 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     }
 
     int j = 0;
-    for (; j + kBatch <= a.k; j += kBatch) {
-        u32x4 x[kBatch][U];
+    for (; j + kPagedBatch <= a.k; j += kPagedBatch) {
+        u32x4 x[kPagedBatch][U];
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b)
+        for (int b = 0; b < kPagedBatch; ++b)
 #pragma unroll
             for (int u = 0; u < U; ++u) x[b][u] = gather(j + b, u);
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
+        for (int b = 0; b < kPagedBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
     }
     for (; j < a.k; ++j) {
         u32x4 x[U];
@@ -661,18 +646,20 @@ static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t
     tiles = ((nvec + super - 1) / super) << nx_shift;
 }
 
-// LDS reservation of a bulk launch of the contiguous or the grouped kernel at
-// two vectors per lane (measured on 2 to 16 GiB shards, 1+1 to 16+4).  Three
-// workgroups per CU gain 0.5 to 1.5 points of HBM peak for nearly every shape;
-// kernels that are all loads and XORs, with at least 8 KiB in flight per
-// wavefront, gain 2 to 3 points more with two; the four-row lookup kernel
-// and one-row kernels over one or two streams need all the wavefronts they can get.
+// LDS reservation of a bulk launch of the contiguous kernel at two vectors per lane: workgroups
+// per CU by kernel variant, from sweeps inside one process over 0.5 to 16 GiB shards, 1+1 to 16+4,
+// encode and rebuilds of one to four shards.  The lighter the arithmetic per load, the fewer
+// wavefronts: one-row kernels run best with three workgroups (12 wavefronts) per CU, two- and
+// three-row kernels with four, four-row kernels and a lone stream with all eight.
 static size_t contig_reservation(const LaunchShape &shape, int unroll, int rows, bool row0_xor, int k, uint64_t workgroups)
 {
     if (!shape.occupancy_cap || unroll != 2 || workgroups < kCapMinWorkgroups) return 0;
-    if ((rows == 4 && !row0_xor) || (rows == 1 && k < 4)) return 0;
-    if (row0_xor && ((rows == 1 && k >= 4) || (rows == 2 && k >= 8))) return lds_for_workgroups_per_cu(2);
-    return lds_for_workgroups_per_cu(3);
+    switch (rows) {
+        case 1: return lds_for_workgroups_per_cu(k == 1 ? 0 : k == 2 ? 4 : 3);
+        case 2: return lds_for_workgroups_per_cu(row0_xor && k >= 8 ? 3 : 4);
+        case 3: return lds_for_workgroups_per_cu(!row0_xor && k > 8 ? 0 : 4);
+        default: return lds_for_workgroups_per_cu(k == 1 ? 3 : 0);
+    }
 }
 
 hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
@@ -730,9 +717,9 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
     const bool nt = shape.nontemporal != 0;
-    // no lookups, a few shifts and XORs per load: two workgroups per CU once a wavefront has 8 KiB in flight
-    const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroups && k >= 4)
-                           ? lds_for_workgroups_per_cu(2) : 0;
+    // no lookups, a few shifts and XORs per load: three workgroups per CU for every k
+    const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroups)
+                           ? lds_for_workgroups_per_cu(3) : 0;
 #define GS_HORNER(M_, U_)                                                                                       \
     if (rows == M_ && unroll == U_) {                                                                           \
         if (nt) hipLaunchKernelGGL((horner_contig_kernel<M_, U_, true>), dim3(wgs), dim3(kThreads), lds, stream, a); \
@@ -798,9 +785,10 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
     uint32_t tpw = 1, wgs = 1;
     grid_for(tiles, tpw, wgs);
     if (tpw != 1) return hipErrorInvalidValue;  // chunks this large go through launch_apply
-    // the grouped kernel keeps to three workgroups per CU: its chunks differ in length, and two starve short ones
-    size_t lds = contig_reservation(shape, unroll, rows, p.row0_xor, k, static_cast<uint64_t>(wgs) * n_chunks);
-    if (lds > lds_for_workgroups_per_cu(3)) lds = lds_for_workgroups_per_cu(3);
+    // the grouped kernel runs with four workgroups per CU from 4096 workgroups on, whatever the code:
+    // +1 to +3 points of HBM peak for every chunk mix tried, where three help some and ruin others
+    const size_t lds = (shape.occupancy_cap && unroll == 2 && static_cast<uint64_t>(wgs) * n_chunks >= 4096)
+                           ? lds_for_workgroups_per_cu(4) : 0;
     return dispatch<BatchLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
                                    dim3(wgs, static_cast<uint32_t>(n_chunks)), lds, stream);
 }

@@ -20,12 +20,12 @@ struct LaunchShape {
 
 // Resident workgroups per CU are limited by handing every workgroup a slice of
 // the CU's 160 KiB of LDS that it never touches.  The streaming kernels move
-// more bytes per second with 2 or 3 workgroups (8 or 12 wavefronts) on a CU
-// than with the 8 their registers allow: fewer super-tiles are open at once in
-// the memory system.  Which count is best depends on how many loads a
-// wavefront keeps in flight and on its arithmetic, so each launcher picks it
-// per kernel variant; launches too small to fill the chip several times over
-// are left alone.  0 = no reservation.
+// more bytes per second with 2 to 4 workgroups (8 to 16 wavefronts) on a CU
+// than with the 8 their registers allow: fewer pieces of fewer streams are open
+// at once in the memory system.  Which count is best depends on the arithmetic
+// a wavefront does per load, so each launcher picks it per kernel variant;
+// launches too small to fill the chip several times over are left alone.
+// 0 = no reservation.
 constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : n == 4 ? 40960 : 0; }
 constexpr uint64_t kCapMinWorkgroups = 16384;  // below this a launch keeps the default occupancy
 

@@ -396,7 +396,7 @@ static int check_pool(int n_streams, int n_chunks)
 // variant; never the paged gather, never a small launch, never with the switch off.
 static int check_occupancy_reservation()
 {
-    const size_t two = 65536, three = 53248;
+    const size_t two = 65536, three = 53248, four = 40960;
     hipStream_t s = nullptr;
     EXPECT(hipStreamCreateWithFlags(&s, 0) == hipSuccess);
     std::vector<void *> ptr(24);
@@ -411,13 +411,15 @@ static int check_occupancy_reservation()
         return static_cast<long>(ops[0].shmem);
     };
     const size_t big = 1ull << 30, small = 1ull << 20;
-    const int e1[1] = {1}, e2[2] = {1, 3}, e4[4] = {0, 1, 2, 3};
+    const int e1[1] = {1}, e2[2] = {1, 3}, e3[3] = {0, 1, 2}, e4[4] = {0, 1, 2, 3};
     struct Case { int k, m, kind; const int *erased; int n_erased; size_t want; } cases[] = {
-        {4, 2, GS_CAUCHY, nullptr, 0, three}, {4, 2, GS_CAUCHY, e2, 2, three},   // the 8B workload
-        {8, 2, GS_CAUCHY, nullptr, 0, two},   {8, 2, GS_CAUCHY, e2, 2, three},   // the 70B workload: XOR row + one lookup row
-        {8, 3, GS_CAUCHY, nullptr, 0, three}, {4, 1, GS_CAUCHY, nullptr, 0, two}, {2, 1, GS_CAUCHY, nullptr, 0, 0}, {2, 2, GS_CAUCHY, nullptr, 0, three},
-        {8, 4, GS_CAUCHY, nullptr, 0, three}, {8, 4, GS_CAUCHY, e4, 4, 0},       // four lookup rows: left alone
-        {8, 3, GS_POWER, nullptr, 0, two},    {2, 2, GS_POWER, nullptr, 0, 0},   // Horner kernel
+        {4, 2, GS_CAUCHY, nullptr, 0, four},  {4, 2, GS_CAUCHY, e2, 2, four},  {4, 2, GS_CAUCHY, e1, 1, three},   // the 8B workload
+        {8, 2, GS_CAUCHY, nullptr, 0, three}, {8, 2, GS_CAUCHY, e2, 2, four},                                     // the 70B workload
+        {8, 3, GS_CAUCHY, nullptr, 0, four},  {8, 3, GS_CAUCHY, e3, 3, four},  {16, 3, GS_CAUCHY, e3, 3, 0},
+        {4, 1, GS_CAUCHY, nullptr, 0, three}, {2, 1, GS_CAUCHY, nullptr, 0, four}, {1, 1, GS_CAUCHY, nullptr, 0, 0},
+        {2, 2, GS_CAUCHY, nullptr, 0, four},
+        {8, 4, GS_CAUCHY, nullptr, 0, 0},     {8, 4, GS_CAUCHY, e4, 4, 0},     {1, 4, GS_CAUCHY, nullptr, 0, three},   // four rows: left alone
+        {8, 3, GS_POWER, nullptr, 0, three},  {2, 2, GS_POWER, nullptr, 0, three},                                 // Horner kernel
         {2, 2, GS_RDP, nullptr, 0, 0},        {4, 2, GS_RDP, nullptr, 0, three}, {6, 2, GS_RDP, e1, 1, three},
         {10, 2, GS_RDP, nullptr, 0, two},     {10, 2, GS_RDP, e2, 2, three},     {10, 2, GS_RDP, e1, 1, two},
         {16, 2, GS_RDP, e2, 2, two},
