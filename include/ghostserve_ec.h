@@ -423,11 +423,10 @@ int gs_coef_words(int c, uint32_t *words_out);
  * gs_set_power_horner; both are atomic: a call running in another thread uses
  * either the old or the new setting as a whole. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
-/* Bulk launches of the contiguous, grouped, Horner and RDP kernels, and of the
- * paged encode of codes with k >= 8 and m <= 2 (16384 workgroups and more,
- * default vectors per lane and tiles per workgroup) ask for 40 to 64 KiB of
- * LDS per workgroup that the kernels never touch, which keeps 4, 3 or 2
- * workgroups on a CU instead of 8: that moves 1 to 4 points more
+/* Bulk launches of the contiguous, grouped, Horner and RDP kernels (16384
+ * workgroups and more, 4096 for the grouped launch; default vectors per lane
+ * and tiles per workgroup) ask for 40 to 64 KiB of LDS per workgroup that the
+ * kernels never touch, which keeps 4, 3 or 2 workgroups on a CU instead of 8: that moves 1 to 4 points more
  * of the HBM peak.  While such a kernel runs, other kernels that need LDS find
  * little of it free on the same CUs; enable = 0 switches the reservation off
  * (process-wide and atomic like the knobs above; gs_set_launch_shape leaves it

@@ -205,8 +205,6 @@ __device__ __forceinline__ void horner_step(Acc4 (&acc)[M][U], const u32x4 (&x)[
     }
 }
 
-constexpr int kPagedBatch = 4;  // paged gather: streams whose loads are issued together
-
 // One tile over contiguous streams: each lane handles the U vectors v[0..U).
 // FULL tiles (every lane in range) carry no predication at all; only tiles
 // that reach past the end of the shard take the predicated form.
@@ -443,17 +441,8 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
             }
     }
 
-    int j = 0;
-    for (; j + kPagedBatch <= a.k; j += kPagedBatch) {
-        u32x4 x[kPagedBatch][U];
-#pragma unroll
-        for (int b = 0; b < kPagedBatch; ++b)
-#pragma unroll
-            for (int u = 0; u < U; ++u) x[b][u] = gather(j + b, u);
-#pragma unroll
-        for (int b = 0; b < kPagedBatch; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
-    }
-    for (; j < a.k; ++j) {
+    // one stream at a time, as in the contiguous kernel
+    for (int j = 0; j < a.k; ++j) {
         u32x4 x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) x[u] = gather(j, u);
@@ -860,14 +849,10 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    // One vector per lane: the gather needs most of the wavefronts the registers allow.  Only the bulk
-    // encode of a wide code with one or two rows (8+1, 8+2, 16+2: eight loads and more per store) runs
-    // faster with four workgroups per CU (+2 to +4 points of HBM peak behind a random table); three-row
-    // kernels and rebuilds into pages lose 7 to 17 points under any reservation.
-    const bool reserve = shape.occupancy_cap && !a.mixed && unroll == 1 && rows <= 2 && k >= 8 && tpw == 1 &&
-                         static_cast<uint64_t>(wgs) * n_planes >= kCapMinWorkgroups;
+    // One vector per lane and one stream at a time: a wavefront has a single 1 KiB load in flight, so the
+    // gather wants every wavefront the registers allow -- no LDS reservation (any costs it 10 to 25 points).
     return dispatch<PagedLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
-                                   dim3(wgs, static_cast<uint32_t>(n_planes)), reserve ? lds_for_workgroups_per_cu(4) : 0, stream);
+                                   dim3(wgs, static_cast<uint32_t>(n_planes)), 0, stream);
 }
 
 }  // namespace gs
