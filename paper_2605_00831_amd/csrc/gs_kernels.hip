@@ -14,8 +14,10 @@
 //   * the 1 KiB pieces of a shard are dealt to workgroups with an interleave
 //     that keeps every XCD on one residue class of pieces (see "Work
 //     distribution" below) -- worth 8-10 points of HBM peak on MI355X;
-//   * several streams' loads are issued before any arithmetic so that each
-//     lane keeps 4*U 16-byte loads in flight;
+//   * the streams are taken one at a time (load a stream's piece, fold it into
+//     the accumulators), and bulk launches limit the workgroups per CU to 3
+//     or 4 through an LDS reservation: many wavefronts with one short burst of
+//     loads each serve the memory better than fewer with long bursts;
 //   * multiplication by a constant is linear over GF(2), so it is evaluated
 //     as three byte-table lookups on the bit fields [2:0], [5:3], [7:6] of
 //     each byte, four bytes at a time with v_perm_b32 (an 8-byte table fits
@@ -25,7 +27,7 @@
 //     code) is a plain XOR and skips the lookups;
 //   * the power code P[r][j] = 2^(r*j) has a second encode kernel that
 //     evaluates its rows by Horner's rule with a packed multiply-by-2 and no
-//     tables (fewer vector instructions; the same HBM-bound launch time).
+//     tables (fewer vector instructions; HBM-bound like the table kernel).
 #include <hip/hip_runtime.h>
 #include "gs_gf.h"
 #include "gs_launch.h"
@@ -409,8 +411,8 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
     // stream j at vector u: from its page, or from the dense layout
     const int32_t first_row = a.in_row[0];
     // No branch on the kind of stream: base and index are selected (the kind is wavefront-uniform), so
-    // the loads of a batch of streams are issued together.  A dense stream still looks up table row 0,
-    // which is always there, and ignores the entry.
+    // the compiler is free to hoist the next stream's lookup and load.  A dense stream still looks up
+    // table row 0, which is always there, and ignores the entry.
     auto gather = [&](int j, int u) -> u32x4 {
         const int32_t row = MIXED ? a.in_row[j] : first_row + j;
         const bool dense = MIXED && row < 0;
