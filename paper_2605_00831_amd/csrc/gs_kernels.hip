@@ -214,7 +214,8 @@ __device__ __forceinline__ void horner_step(Acc4 (&acc)[M][U], const u32x4 (&x)[
 // (ApplyArgs) or a per-chunk descriptor in device memory (BatchDesc).
 // HORNER: the matrix is the power code's and is evaluated by horner_step over
 // the streams in descending order instead of through the tables.
-template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, bool HORNER, class S>
+// KB: how many streams' loads are issued together before their arithmetic.
+template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, bool HORNER, int KB, class S>
 __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
                                             int k, int accumulate, const uint64_t (&piece)[U], uint32_t lane)
 {
@@ -236,12 +237,34 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
                 if (ok[u]) acc[r][u] = from_vec(load_piece<NT>(s.out[r], piece[u], lane));
     }
 
-    // One stream at a time: a wavefront has the U loads of one stream in flight, does that stream's
-    // arithmetic, and goes on to the next stream.  Overlap comes from the other wavefronts of the CU
-    // (12 to 16 of them, see the LDS reservation of the launchers).  Issuing the loads of two or four
-    // streams together, which looks like the obvious way to keep more bytes in flight, is 1 to 5 points
-    // of HBM peak slower for every code shape at every occupancy.
-    for (int j = 0; j < k; ++j) {
+    // KB = 1, one stream at a time, is the bulk form: a wavefront has the U loads of one stream in
+    // flight, does that stream's arithmetic, and goes on to the next stream.  Overlap comes from the
+    // other wavefronts of the CU (12 to 16 of them, see the LDS reservation of the launchers).
+    // Issuing the loads of two or four streams together, which looks like the obvious way to keep
+    // more bytes in flight, is 1 to 5 points of HBM peak slower for every code shape once the chip is
+    // full.  A launch that does not fill the chip is the other way round: its time is the k memory
+    // round trips of a wavefront one after the other, and KB = 4 makes them k/4.
+    int j = 0;
+    if constexpr (KB > 1) {
+        for (; j + KB <= k; j += KB) {
+            u32x4 x[KB][U];
+#pragma unroll
+            for (int b = 0; b < KB; ++b) {
+                const uint8_t *src = s.in[HORNER ? k - 1 - (j + b) : j + b];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    x[b][u] = u32x4{0, 0, 0, 0};
+                    if (ok[u]) x[b][u] = load_piece<NT>(src, piece[u], lane);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < KB; ++b) {
+                if constexpr (HORNER) horner_step<M, U>(acc, x[b]);
+                else mac<M, ROW0_XOR, U>(acc, x[b], tab, j + b);
+            }
+        }
+    }
+    for (; j < k; ++j) {
         const uint8_t *src = s.in[HORNER ? k - 1 - j : j];
         u32x4 x[U];
 #pragma unroll
@@ -284,7 +307,7 @@ constexpr int kWavesPerEu()
 // i.e. every NX-th piece inside a super-tile of NX*4U pieces, wavefront w
 // taking q = w*U .. w*U+U-1.  All NX tiles of a super-tile together cover it
 // exactly once.  nx_shift = 0 gives plain consecutive tiles.
-template <int M, bool ROW0_XOR, int U, bool NT, bool HORNER, class S>
+template <int M, bool ROW0_XOR, int U, bool NT, bool HORNER, int KB = 1, class S>
 __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
                                                int k, int accumulate, uint32_t tiles_per_wg, bool last_wg)
 {
@@ -308,8 +331,8 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
 #pragma unroll
         for (int u = 0; u < U; ++u) piece[u] = (((g * kPieces + wave * U + u) << nx_shift) + r) << 6;
         const uint64_t super_end = (((g + 1) * kPieces) << nx_shift) * 64;
-        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER>(s, tab, k, accumulate, piece, lane);
-        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER>(s, tab, k, accumulate, piece, lane);
+        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER, KB>(s, tab, k, accumulate, piece, lane);
+        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER, KB>(s, tab, k, accumulate, piece, lane);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
@@ -337,14 +360,23 @@ void apply_contig_kernel(const ApplyArgs a)
     contig_streams<M, ROW0_XOR, U, NT, false>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
 }
 
+// The same for launches that do not fill the chip (a chunk of a few MiB, a
+// decode step): four streams' loads issued together, see contig_tile.
+template <int M, bool ROW0_XOR, bool NT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, 2>(), 8)))
+void apply_contig_small_kernel(const ApplyArgs a)
+{
+    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+}
+
 // Power-code encode by Horner's rule (rows 1, 2^j, 4^j): same tiles, same
 // loads and stores, no table lookups.  The tables are still passed: the up to
 // 15 bytes after the last whole vector go through the per-byte path.
-template <int M, int U, bool NT>
+template <int M, int U, bool NT, int KB = 1>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, true, U>(), 8)))
 void horner_contig_kernel(const ApplyArgs a)
 {
-    contig_streams<M, true, U, NT, true>(a, a.tab, a.k, 0, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, true, U, NT, true, KB>(a, a.tab, a.k, 0, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
 }
 
 // Many independent chunks in one launch (one request's chunk, or one chunk of
@@ -377,7 +409,7 @@ typedef const int32_t __attribute__((address_space(4))) *ConstTable;
 // reconstruct).  Without it (paged encode) input j is table row in_row[0]+j
 // and every output is dense, which keeps the per-stream kind tests and one
 // dependent scalar load off the latency-bound decode-step path.
-template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE, bool MIXED>
+template <int M, bool ROW0_XOR, int U, bool NT, bool WAVE_PAGE, bool MIXED, int KB>
 __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pbase, uint32_t plane,
                                            const uint64_t (&vv)[U])
 {
@@ -443,8 +475,21 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
             }
     }
 
-    // one stream at a time, as in the contiguous kernel
-    for (int j = 0; j < a.k; ++j) {
+    // one stream at a time, or KB streams' loads together in a launch that does not fill the chip,
+    // as in the contiguous kernel
+    int j = 0;
+    if constexpr (KB > 1) {
+        for (; j + KB <= a.k; j += KB) {
+            u32x4 x[KB][U];
+#pragma unroll
+            for (int b = 0; b < KB; ++b)
+#pragma unroll
+                for (int u = 0; u < U; ++u) x[b][u] = gather(j + b, u);
+#pragma unroll
+            for (int b = 0; b < KB; ++b) mac<M, ROW0_XOR, U>(acc, x[b], a.tab, j + b);
+        }
+    }
+    for (; j < a.k; ++j) {
         u32x4 x[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) x[u] = gather(j, u);
@@ -468,7 +513,7 @@ __device__ __forceinline__ void paged_tile(const PagedArgs &a, const uint8_t *pb
 // contiguous kernel (gridDim.x is a multiple of the interleave modulus, so the
 // piece residue still names the XCD).  Each lane finds its page slot, looks
 // the page id up in every shard's table row, and reads from that page.
-template <int M, bool ROW0_XOR, int U, bool WAVE_PAGE, bool MIXED>
+template <int M, bool ROW0_XOR, int U, bool WAVE_PAGE, bool MIXED, int KB = 1>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
 void apply_paged_kernel(const PagedArgs a)
 {
@@ -486,7 +531,7 @@ void apply_paged_kernel(const PagedArgs a)
         uint64_t v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) v[u] = ((((g * kPieces + wave * U + u) << a.nx_shift) + r) << 6) + lane;
-        paged_tile<M, ROW0_XOR, U, true, WAVE_PAGE, MIXED>(a, pbase, plane, v);
+        paged_tile<M, ROW0_XOR, U, true, WAVE_PAGE, MIXED, KB>(a, pbase, plane, v);
     }
 }
 
@@ -585,12 +630,29 @@ struct ContigLauncher {
     }
 };
 
+// launches of at most kSmallWorkgroups workgroups at two vectors per lane
+template <int M, bool X, int U, bool NT>
+struct ContigSmallLauncher {
+    static hipError_t go(const ApplyArgs &a, dim3 grid, size_t lds, hipStream_t stream)
+    {
+        if constexpr (U == 2) hipLaunchKernelGGL((apply_contig_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
+        else hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
+        return hipGetLastError();
+    }
+};
+
 // the paged kernels always use the streaming cache policy (NT is ignored)
 template <int M, bool X, int U, bool NT>
 struct PagedLauncher {
     template <bool WAVE_PAGE, bool MIXED>
     static void launch(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
+        if constexpr (U == 1) {
+            if (a.k > 1 && static_cast<uint64_t>(grid.x) * grid.y <= kSmallWorkgroups) {
+                hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED, 4>), grid, dim3(kThreads), lds, stream, a);
+                return;
+            }
+        }
         hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED>), grid, dim3(kThreads), lds, stream, a);
     }
     static hipError_t go(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t stream)
@@ -675,6 +737,8 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
     const size_t lds = tpw == 1 ? contig_reservation(shape, unroll, rows, row0_xor, k, wgs) : 0;
+    if (unroll == 2 && tpw == 1 && k > 1 && wgs <= kSmallWorkgroups)
+        return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds, stream);
     return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds, stream);
 }
 
@@ -711,6 +775,16 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     // no lookups, a few shifts and XORs per load: three workgroups per CU for every k
     const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroups)
                            ? lds_for_workgroups_per_cu(3) : 0;
+    if (unroll == 2 && tpw == 1 && wgs <= kSmallWorkgroups) {  // does not fill the chip: four streams' loads together
+        if (rows == 2) {
+            if (nt) hipLaunchKernelGGL((horner_contig_kernel<2, 2, true, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
+            else hipLaunchKernelGGL((horner_contig_kernel<2, 2, false, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
+        } else {
+            if (nt) hipLaunchKernelGGL((horner_contig_kernel<3, 2, true, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
+            else hipLaunchKernelGGL((horner_contig_kernel<3, 2, false, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
+        }
+        return hipGetLastError();
+    }
 #define GS_HORNER(M_, U_)                                                                                       \
     if (rows == M_ && unroll == U_) {                                                                           \
         if (nt) hipLaunchKernelGGL((horner_contig_kernel<M_, U_, true>), dim3(wgs), dim3(kThreads), lds, stream, a); \

@@ -29,6 +29,15 @@ struct LaunchShape {
 constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : n == 4 ? 40960 : 0; }
 constexpr uint64_t kCapMinWorkgroups = 16384;  // below this a launch keeps the default occupancy
 
+// The other end: a launch of at most this many workgroups (half of what the
+// chip holds at once: 256 CUs x 8) is over when its slowest wavefront is, and
+// a wavefront's time is its memory round trips one after the other.  Such
+// launches run kernel forms that issue the loads of four streams together
+// (measured from a host thread, launch to idle: 8+2 on 4 MiB shards 26.1 ->
+// 23.7 us, 16+2 on 2 MiB shards 30.8 -> 27.0 us; from 2048 workgroups on one
+// stream at a time is the faster form again).
+constexpr uint32_t kSmallWorkgroups = 1024;
+
 // One launch: out[r] (r < rows <= 4) = XOR_j coef[r*coef_stride + j] (x) in[j], j < k <= 16,
 // over `bytes` bytes; with accumulate the previous contents of out[r] are XORed in.
 hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,

@@ -398,6 +398,7 @@ def test_misaligned_or_null_pointers_are_rejected(gs):
     (8, 3, 2, 7, 512, [(2, 5, 9), (0, 1, 2), (8, 9, 10), (7, 8)]),
     (3, 2, 2, 11, 48, [(0, 2), (1, 4)]),
     (20, 5, 2, 3, 1040, [(0, 19, 20, 24, 7)]),
+    (4, 2, 8, 288, 2048, [(1, 3), (0, 4)]),   # more than 1024 workgroups: the bulk form of the kernel
 ])
 def test_paged_reconstruct_rebuilds_into_fresh_pages(gs, k, m, n_planes, pps, page_bytes, pats):
     spare = 3 * pps + 5
@@ -583,3 +584,53 @@ def test_occupancy_reservation_changes_no_byte(gs):
             del data, outs, shards, keep
     finally:
         gs.gs_set_occupancy_cap(1)
+
+
+# the library runs launches of at most 1024 workgroups (8 KiB per stream and workgroup for contiguous
+# shards, 4 KiB for the paged gather) in a kernel form of their own; sizes on both sides of that line
+SMALL_FORM_SIZES = [1024 * 8192 - 16, 1024 * 8192, 1024 * 8192 + 16 + 5, 1100 * 8192 + 4080]
+
+
+@pytest.mark.parametrize("k,m", [(2, 1), (5, 2), (8, 3), (3, 4), (16, 2)])
+def test_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m):
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    for S in SMALL_FORM_SIZES:
+        data = rand_shards(S % 1000 + k, k, S)
+        want = oracle.encode(P, data, nthreads=8)
+        _, p = gpu_encode(gs, code, data, S)
+        for i in range(m):
+            check_out(p[i], want[i])
+
+
+@pytest.mark.parametrize("k,m,pat", [(4, 2, (1,)), (4, 2, (0, 3)), (8, 3, (2, 5, 9)), (6, 4, (0, 1, 2, 3)), (9, 2, (9, 10))])
+def test_reconstruct_on_both_sides_of_the_small_launch_threshold(gs, k, m, pat):
+    # rebuild matrices without an all-ones row: the kernel variants an encode never runs
+    code = gs.gs_make_code(k, m)
+    for S in (SMALL_FORM_SIZES[1], SMALL_FORM_SIZES[2]):
+        P, full = _stripe_on_gpu(gs, k, m, S, seed=S % 997 + k)
+        _reconstruct_and_check(gs, code, P, full, pat, S)
+
+
+@pytest.mark.parametrize("k,m", [(4, 2), (7, 3)])
+def test_horner_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m):
+    P = oracle.power_generator(k, m)
+    code = gs.gs_make_code(k, m, gs.GS_POWER)
+    for S in SMALL_FORM_SIZES[1:3]:
+        data = rand_shards(S % 1000 + 3 * k, k, S)
+        want = oracle.encode(P, data, nthreads=8)
+        _, p = gpu_encode(gs, code, data, S)
+        for i in range(m):
+            check_out(p[i], want[i])
+
+
+@pytest.mark.parametrize("k,m,n_planes,pps,page_bytes", [
+    (4, 1, 8, 256, 2048),     # 8 planes x 128 workgroups = 1024: the small form
+    (4, 1, 8, 258, 2048),     # one super-tile more per plane: the bulk form
+    (8, 3, 4, 16, 65536),     # 4 x 256 = 1024
+    (8, 3, 4, 17, 65536),
+    (5, 2, 2, 1000, 1040),    # lane-indexed pages, 254 tiles rounded up to 256 per plane: 512
+    (5, 2, 2, 4100, 1040),
+])
+def test_paged_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m, n_planes, pps, page_bytes):
+    _paged_case(gs, k, m, n_planes, pps, page_bytes, seed=k + pps)
