@@ -423,11 +423,12 @@ int gs_coef_words(int c, uint32_t *words_out);
  * gs_set_power_horner; both are atomic: a call running in another thread uses
  * either the old or the new setting as a whole. */
 int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int interleave_shift);
-/* Bulk launches of the contiguous, grouped, Horner and RDP kernels (16384
- * workgroups and more, 4096 for the grouped launch; default vectors per lane
- * and tiles per workgroup) ask for 40 to 64 KiB of LDS per workgroup that the
- * kernels never touch, which keeps 4, 3 or 2 workgroups on a CU instead of 8: that moves 1 to 4 points more
- * of the HBM peak.  While such a kernel runs, other kernels that need LDS find
+/* Bulk launches of the contiguous, grouped, Horner and RDP kernels (shards
+ * of 48 MiB and more, 96 MiB for one-row launches and RDP, 4096 workgroups
+ * for the grouped launch; default vectors per lane and tiles per workgroup)
+ * ask for 40 to 64 KiB of LDS per workgroup that the kernels never touch,
+ * which keeps 4, 3 or 2 workgroups on a CU instead of 8: that moves 1 to 4
+ * points more of the HBM peak.  While such a kernel runs, other kernels that need LDS find
  * little of it free on the same CUs; enable = 0 switches the reservation off
  * (process-wide and atomic like the knobs above; gs_set_launch_shape leaves it
  * as it is).  Results are identical either way.  Default: enabled. */

@@ -703,10 +703,13 @@ static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t
 // per CU by kernel variant, from sweeps inside one process over 0.5 to 16 GiB shards, 1+1 to 16+4,
 // encode and rebuilds of one to four shards.  The lighter the arithmetic per load, the fewer
 // wavefronts: one-row kernels run best with three workgroups (12 wavefronts) per CU, two- and
-// three-row kernels with four, four-row kernels and a lone stream with all eight.
+// three-row kernels with four, four-row kernels and a lone stream with all eight.  The reservation
+// starts to pay once a launch fills the chip several times over: from 6144 workgroups (48 MiB
+// shards) for kernels of two and more rows (+1 to +2 points there, +2 to +4 from 12288), from
+// 12288 for one-row kernels (below that they lose 0.5 to 4 points to it).
 static size_t contig_reservation(const LaunchShape &shape, int unroll, int rows, bool row0_xor, int k, uint64_t workgroups)
 {
-    if (!shape.occupancy_cap || unroll != 2 || workgroups < kCapMinWorkgroups) return 0;
+    if (!shape.occupancy_cap || unroll != 2 || workgroups < (rows == 1 ? kCapMinWorkgroupsOneRow : kCapMinWorkgroupsRows)) return 0;
     switch (rows) {
         case 1: return lds_for_workgroups_per_cu(k == 1 ? 0 : k == 2 ? 4 : 3);
         case 2: return lds_for_workgroups_per_cu(row0_xor && k >= 8 ? 3 : 4);
@@ -773,7 +776,7 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     a.nx_shift = nx_shift;
     const bool nt = shape.nontemporal != 0;
     // no lookups, a few shifts and XORs per load: three workgroups per CU for every k
-    const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroups)
+    const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroupsRows)
                            ? lds_for_workgroups_per_cu(3) : 0;
     if (unroll == 2 && tpw == 1 && wgs <= kSmallWorkgroups) {  // does not fill the chip: four streams' loads together
         if (rows == 2) {

@@ -27,7 +27,11 @@ struct LaunchShape {
 // launches too small to fill the chip several times over are left alone.
 // 0 = no reservation.
 constexpr size_t lds_for_workgroups_per_cu(int n) { return n == 2 ? 65536 : n == 3 ? 53248 : n == 4 ? 40960 : 0; }
-constexpr uint64_t kCapMinWorkgroups = 16384;  // below this a launch keeps the default occupancy
+// Launches below these sizes keep the default occupancy (measured crossovers; a workgroup of the
+// GF(2^8) kernels moves 8 KiB of every stream, one of the RDP kernels 2 KiB of each of a disk's p - 1 rows):
+constexpr uint64_t kCapMinWorkgroupsRows = 6144;     // table kernels of two and more rows, Horner kernel: 48 MiB shards
+constexpr uint64_t kCapMinWorkgroupsOneRow = 12288;  // table kernels of one row: 96 MiB shards
+constexpr uint64_t kRdpCapMinRowPieces = 49152;      // RDP, workgroups x (p - 1): 96 MiB disks
 
 // The other end: a launch of at most this many workgroups (half of what the
 // chip holds at once: 256 CUs x 8) is over when its slowest wavefront is, and

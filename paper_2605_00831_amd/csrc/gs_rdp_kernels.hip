@@ -162,7 +162,10 @@ __global__ __launch_bounds__(kThreads) void rdp_batch_kernel(const RdpBatchArgs 
 static size_t rdp_reservation(const LaunchShape &shape, const RdpPlan &plan, int w, uint64_t workgroups)
 {
     const int p = plan.p;
-    if (!shape.occupancy_cap || w != 2 || workgroups < kCapMinWorkgroups || p < 5) return 0;
+    if (!shape.occupancy_cap || w != 2 || p < 5) return 0;
+    // a workgroup moves 2 KiB of each of a disk's p - 1 rows; the reservation pays from 96 MiB per disk
+    // on (p = 17: from 256 MiB), below that it costs up to 5 points
+    if (workgroups * static_cast<uint64_t>(p - 1) < (p < 17 ? kRdpCapMinRowPieces : 8 * kRdpCapMinRowPieces / 3)) return 0;
     if (p < 11) return lds_for_workgroups_per_cu(3);
     size_t bits = 0;
     for (uint32_t m : plan.syndrome_mask) bits += static_cast<size_t>(__builtin_popcount(m));

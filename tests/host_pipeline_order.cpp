@@ -446,6 +446,30 @@ static int check_occupancy_reservation()
         EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.want));   // the shape knobs left the switch on
         gs_free_code(code);
     }
+    // where the reservation starts: 6144 workgroups of 8 KiB per stream for two and more rows, 12288 for one row
+    {
+        gs_code *two_rows = nullptr, *one_row = nullptr;
+        EXPECT(gs_make_code(8, 2, GS_CAUCHY, &two_rows) == GS_OK && gs_make_code(4, 1, GS_CAUCHY, &one_row) == GS_OK);
+        EXPECT(lds_of(two_rows, 6144ull * 8192, nullptr, 0) == static_cast<long>(three));
+        EXPECT(lds_of(two_rows, 6144ull * 8192, e2, 2) == static_cast<long>(four));
+        EXPECT(lds_of(two_rows, 6112ull * 8192, nullptr, 0) == 0);
+        EXPECT(lds_of(one_row, 12288ull * 8192, nullptr, 0) == static_cast<long>(three));
+        EXPECT(lds_of(one_row, 12256ull * 8192, nullptr, 0) == 0);
+        EXPECT(lds_of(two_rows, 12256ull * 8192, e1, 1) == 0);   // one lost shard: a one-row launch
+        gs_free_code(two_rows);
+        gs_free_code(one_row);
+        // the Horner kernel from 6144 workgroups, RDP from 96 MiB per disk (workgroups x (p - 1) >= 49152)
+        gs_code *power = nullptr, *rdp = nullptr;
+        EXPECT(gs_make_code(8, 3, GS_POWER, &power) == GS_OK && gs_make_code(8, 2, GS_RDP, &rdp) == GS_OK);
+        EXPECT(lds_of(power, 6144ull * 8192, nullptr, 0) == static_cast<long>(three));
+        EXPECT(lds_of(power, 6112ull * 8192, nullptr, 0) == 0);
+        size_t cell = 0;
+        EXPECT(gs_rdp_cell_bytes(rdp, &cell) == GS_OK && cell == 32768);
+        EXPECT(lds_of(rdp, 308 * 10 * cell, nullptr, 0) == static_cast<long>(two));   // p = 11: 4928 x 10
+        EXPECT(lds_of(rdp, 306 * 10 * cell, nullptr, 0) == 0);                                            // 4896 x 10
+        gs_free_code(power);
+        gs_free_code(rdp);
+    }
     // the paged gather keeps full occupancy
     struct Paged { int k, m; int pages_per_shard; size_t want; } paged[] = {
         {4, 2, 4096, 0}, {8, 3, 4096, 0}, {8, 2, 4096, 0}, {16, 1, 4096, 0}, {8, 2, 16, 0},
