@@ -591,7 +591,7 @@ def test_occupancy_reservation_changes_no_byte(gs):
 SMALL_FORM_SIZES = [1024 * 8192 - 16, 1024 * 8192, 1024 * 8192 + 16 + 5, 1100 * 8192 + 4080]
 
 
-@pytest.mark.parametrize("k,m", [(2, 1), (5, 2), (8, 3), (3, 4), (16, 2)])
+@pytest.mark.parametrize("k,m", [(2, 1), (5, 2), (8, 3), (3, 4), (16, 2), (20, 5)])   # (20, 5): accumulating launches
 def test_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m):
     P = oracle.generator(k, m)
     code = gs.gs_make_code(k, m)
@@ -631,6 +631,7 @@ def test_horner_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m):
     (8, 3, 4, 17, 65536),
     (5, 2, 2, 1000, 1040),    # lane-indexed pages, 254 tiles rounded up to 256 per plane: 512
     (5, 2, 2, 4100, 1040),
+    (18, 5, 2, 2100, 1040),   # accumulating launches in the bulk form
 ])
 def test_paged_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m, n_planes, pps, page_bytes):
     _paged_case(gs, k, m, n_planes, pps, page_bytes, seed=k + pps)
