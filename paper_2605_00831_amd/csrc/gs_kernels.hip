@@ -393,6 +393,15 @@ void apply_batch_kernel(const BatchArgs a)
     contig_streams<M, ROW0_XOR, U, NT, false>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
 }
 
+// The grouped launch when all its chunks together do not fill the chip.
+template <int M, bool ROW0_XOR, bool NT>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, 2, true>(), 8)))
+void apply_batch_small_kernel(const BatchArgs a)
+{
+    ConstDesc d = (ConstDesc)a.descs + blockIdx.y;
+    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
+}
+
 // One tile of the paged gather.  A lane whose vector index is past the end of
 // the plane, or whose page id is outside the plane, reads vector 0 / page 0
 // instead (always a valid address) and its value is replaced by zero, so the
@@ -808,6 +817,16 @@ struct BatchLauncher {
     }
 };
 
+template <int M, bool X, int U, bool NT>
+struct BatchSmallLauncher {
+    static hipError_t go(const BatchArgs &a, dim3 grid, size_t lds, hipStream_t stream)
+    {
+        if constexpr (U == 2) hipLaunchKernelGGL((apply_batch_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
+        else hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
+        return hipGetLastError();
+    }
+};
+
 size_t batch_desc_bytes() { return sizeof(BatchDesc); }
 
 void batch_row_order(int rows, int k, const uint8_t *coef, int coef_stride, int *order)
@@ -857,6 +876,11 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
     // +1 to +3 points of HBM peak for every chunk mix tried, where three help some and ruin others
     const size_t lds = (shape.occupancy_cap && unroll == 2 && static_cast<uint64_t>(wgs) * n_chunks >= 4096)
                            ? lds_for_workgroups_per_cu(4) : 0;
+    // all chunks together do not fill the chip (512 workgroups: 1.4 to 3.1 us less from launch to idle; at
+    // 1024 the two forms are level)
+    if (unroll == 2 && k > 1 && static_cast<uint64_t>(wgs) * n_chunks <= kSmallWorkgroups / 2)
+        return dispatch<BatchSmallLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
+                                            dim3(wgs, static_cast<uint32_t>(n_chunks)), lds, stream);
     return dispatch<BatchLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
                                    dim3(wgs, static_cast<uint32_t>(n_chunks)), lds, stream);
 }

@@ -36,7 +36,8 @@ constexpr uint64_t kRdpCapMinRowPieces = 49152;      // RDP, workgroups x (p - 1
 // The other end: a launch of at most this many workgroups (half of what the
 // chip holds at once: 256 CUs x 8) is over when its slowest wavefront is, and
 // a wavefront's time is its memory round trips one after the other.  Such
-// launches run kernel forms that issue the loads of four streams together
+// launches (grouped ones: half as many workgroups over all chunks) run
+// kernel forms that issue the loads of four streams together
 // (measured from a host thread, launch to idle: 8+2 on 4 MiB shards 26.1 ->
 // 23.7 us, 16+2 on 2 MiB shards 30.8 -> 27.0 us; from 2048 workgroups on one
 // stream at a time is the faster form again).

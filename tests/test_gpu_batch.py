@@ -229,3 +229,41 @@ def test_grouped_launch_at_its_largest_chunk_count(gs):
     gs.gs_batch_destroy(b)
     with pytest.raises(gs.GsError):
         gs.gs_batch_create(code, n + 1)
+
+
+SMALL_GROUP = [4096, 1, 15, 4097, 65536, 16 * 64 * 33, 777, 8192, 100000, 16]
+
+
+@pytest.mark.parametrize("k,m,pat", [(4, 2, (1, 3)), (8, 3, (2, 5, 9)), (4, 1, (2,)), (6, 4, (0, 1, 2, 3)), (16, 2, (16,))])
+def test_grouped_launch_that_does_not_fill_the_chip(gs, k, m, pat):
+    """All chunks together are a few hundred workgroups: the grouped launch then runs the kernel form of
+    small launches.  Encode and rebuild against the oracle, every kernel variant."""
+    P = oracle.generator(k, m)
+    code = gs.gs_make_code(k, m)
+    chunks = make_chunks(k, 31 * k + m, SMALL_GROUP)
+    full = [ch + oracle.encode(P, ch, nthreads=8) for ch in chunks]
+    b = gs.gs_batch_create(code, len(SMALL_GROUP))
+    data = [[dev(x) for x in ch] for ch in chunks]
+    par = [[out_buf(S) for _ in range(m)] for S in SMALL_GROUP]
+    gs.gs_encode_batch(b, data, par, SMALL_GROUP)
+    torch.cuda.synchronize()
+    for c in range(len(SMALL_GROUP)):
+        for i in range(m):
+            check(par[c][i], full[c][k + i])
+    shards = []
+    for c, S in enumerate(SMALL_GROUP):
+        row = []
+        for r in range(k + m):
+            if r in pat:
+                t = out_buf(S)
+                t[:S] = 0xA5
+            else:
+                t = dev(full[c][r])
+            row.append(t)
+        shards.append(row)
+    gs.gs_reconstruct_batch(b, shards, list(pat), SMALL_GROUP)
+    torch.cuda.synchronize()
+    for c in range(len(SMALL_GROUP)):
+        for r in pat:
+            check(shards[c][r], full[c][r])
+    gs.gs_batch_destroy(b)
