@@ -644,8 +644,10 @@ template <int M, bool X, int U, bool NT>
 struct ContigSmallLauncher {
     static hipError_t go(const ApplyArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
-        if constexpr (U == 2) hipLaunchKernelGGL((apply_contig_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
-        else hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
+        if constexpr (U == 2)
+            hipLaunchKernelGGL((apply_contig_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
+        else
+            hipLaunchKernelGGL((apply_contig_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
         return hipGetLastError();
     }
 };
@@ -718,7 +720,8 @@ static void interleave_for(uint64_t nvec, int unroll, int wanted_shift, uint32_t
 // 12288 for one-row kernels (below that they lose 0.5 to 4 points to it).
 static size_t contig_reservation(const LaunchShape &shape, int unroll, int rows, bool row0_xor, int k, uint64_t workgroups)
 {
-    if (!shape.occupancy_cap || unroll != 2 || workgroups < (rows == 1 ? kCapMinWorkgroupsOneRow : kCapMinWorkgroupsRows)) return 0;
+    if (!shape.occupancy_cap || unroll != 2) return 0;
+    if (workgroups < (rows == 1 ? kCapMinWorkgroupsOneRow : kCapMinWorkgroupsRows)) return 0;
     switch (rows) {
         case 1: return lds_for_workgroups_per_cu(k == 1 ? 0 : k == 2 ? 4 : 3);
         case 2: return lds_for_workgroups_per_cu(row0_xor && k >= 8 ? 3 : 4);
@@ -821,8 +824,10 @@ template <int M, bool X, int U, bool NT>
 struct BatchSmallLauncher {
     static hipError_t go(const BatchArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
-        if constexpr (U == 2) hipLaunchKernelGGL((apply_batch_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
-        else hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
+        if constexpr (U == 2)
+            hipLaunchKernelGGL((apply_batch_small_kernel<M, X, NT>), grid, dim3(kThreads), lds, stream, a);
+        else
+            hipLaunchKernelGGL((apply_batch_kernel<M, X, U, NT>), grid, dim3(kThreads), lds, stream, a);
         return hipGetLastError();
     }
 };
