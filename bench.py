@@ -164,9 +164,9 @@ def main():
                          "0 / -1 keep a knob's default")
     ap.add_argument("--no-occupancy-cap", action="store_true",
                     help="gs_set_occupancy_cap(0): bulk launches without the LDS reservation that limits workgroups per CU")
-    ap.add_argument("--only", default=None, choices=["headline", "paged_bulk", "rdp_forms"],
+    ap.add_argument("--only", default=None, choices=["headline", "paged_bulk", "rdp_forms", "launch_sizes"],
                     help="headline: the timed steps of --workload and its extras, not the other bulk workloads; "
-                         "paged_bulk / rdp_forms: only that leg (for profiling runs)")
+                         "paged_bulk / rdp_forms / launch_sizes: only that leg (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -177,7 +177,7 @@ def main():
     # The decode-step latency probe is a plain C program: run it as a child process first, before
     # this process opens the GPU, so that the two never hold the device at the same time.
     native = None
-    if not args.no_extras and args.only not in ("paged_bulk", "rdp_forms"):
+    if not args.no_extras and args.only not in ("paged_bulk", "rdp_forms", "launch_sizes"):
         native = {"decode": native_probe(log, "decode", inputs_steps(), 32), "many": native_probe(log, "many")}
 
     import torch
@@ -210,6 +210,10 @@ def main():
 
     if args.only == "rdp_forms":
         print(json.dumps({"rdp_forms": rdp_forms(torch, gs, inputs, log, calibrate=args.calibrate_copy)}), flush=True)
+        return 0
+
+    if args.only == "launch_sizes":
+        print(json.dumps({"launch_sizes": launch_sizes(torch, gs, log, cap=not args.no_occupancy_cap)}), flush=True)
         return 0
 
     cfg = inputs.CONFIGS[args.workload]
@@ -324,6 +328,7 @@ def main():
         out["paged_bulk"] = paged_bulk(torch, gs, inputs, log, pipelines=not args.no_extras)
         out["code_shapes"] = code_shapes(torch, gs, log)
         out["rdp_forms"] = rdp_forms(torch, gs, inputs, log)
+        out["launch_sizes"] = launch_sizes(torch, gs, log, cap=not args.no_occupancy_cap)
 
     print(json.dumps(out), flush=True)
     return 0
@@ -442,6 +447,69 @@ def code_shapes(torch, gs, log):
         rows.append({"k": k, "m": m, "shard_bytes": S, "encode_ms": round(ms, 4),
                      "frac": round((k + m) * S / ms / 1e6 / HBM_PEAK_GBPS, 4)})
     log("[bench] code shapes: " + json.dumps(rows))
+    return rows
+
+
+def launch_sizes(torch, gs, log, cap=True):
+    """One launch against its size, 64 KiB to 1 GiB per shard (4+2 and 8+2; encode, and the rebuild of
+    shards 1 and 3): microseconds per launch from events around back-to-back launches, the HBM fraction
+    that is, and for launches that do not fill the chip the time from the call to an idle stream as a
+    host thread sees it.  Bulk sizes are timed with the LDS reservation on and off.  The library picks
+    a kernel form by size (four streams' loads together up to 1024 workgroups of 8 KiB per stream, one
+    stream at a time above, fewer workgroups per CU from 48 MiB on); this leg shows all three regimes."""
+    arena = device_arena(torch, 10 << 30)
+    rows = []
+
+    def per_launch_us(fn, n):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1000.0 / n
+            best = us if best is None or us < best else best
+        return best
+
+    def to_idle_us(fn, n=200):
+        ts = []
+        for i in range(n + 20):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            if i >= 20:
+                ts.append(time.perf_counter() - t0)
+        return pctl(ts, 50) * 1e6
+
+    for k, m in ((4, 2), (8, 2)):
+        code = gs.gs_make_code(k, m)
+        for S in (64 << 10, 1 << 20, 4 << 20, 8 << 20, 16 << 20, 32 << 20, 48 << 20, 64 << 20, 96 << 20, 128 << 20,
+                  256 << 20, 1 << 30):
+            shards = [arena[j * S:(j + 1) * S] for j in range(k + m)]
+            enc = lambda: gs.gs_encode(code, shards[:k], shards[k:], S)
+            rec = lambda: gs.gs_reconstruct(code, shards, [1, 3], S)
+            enc()
+            n = 200 if S <= (8 << 20) else 40 if S <= (128 << 20) else 10
+            row = {"k": k, "m": m, "shard_bytes": S, "workgroups": (S + 8191) // 8192}
+            for name, fn in (("encode", enc), ("reconstruct", rec)):
+                us = per_launch_us(fn, n)
+                row[name] = {"us": round(us, 2), "frac": round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)}
+                if S <= (8 << 20):
+                    row[name]["call_to_idle_us"] = round(to_idle_us(fn), 1)
+                if cap and S >= (48 << 20):
+                    gs.gs_set_occupancy_cap(False)
+                    try:
+                        us = per_launch_us(fn, n)
+                    finally:
+                        gs.gs_set_occupancy_cap(True)
+                    row[name]["frac_without_reservation"] = round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)
+            rows.append(row)
+    log("[bench] launch sizes: " + json.dumps(rows))
     return rows
 
 
