@@ -126,4 +126,48 @@ CoefWords split_tables(uint8_t c)
     return t;
 }
 
+XorFold find_xor_fold(int rows, int k, const uint8_t *coef, int coef_stride)
+{
+    XorFold best;
+    best.found = false;
+    best.n_xor = 0;
+    best.fold = 0;
+    for (int r = 0; r < 4; ++r) best.order[r] = r;
+    for (int j = 0; j < 16; ++j) best.perm[j] = j;
+    if (rows < 1 || rows > 4 || k < 1 || k > 16) return best;
+    int best_size = rows + 1;
+    for (int r0 = 0; r0 < rows; ++r0)
+        for (uint32_t T = 0; T < (1u << rows); ++T) {
+            if (T & (1u << r0)) continue;
+            const int size = __builtin_popcount(T);
+            if (size >= best_size) continue;
+            uint8_t v[16];
+            bool zero_one = true;
+            for (int j = 0; j < k && zero_one; ++j) {
+                v[j] = coef[r0 * coef_stride + j];
+                for (int t = 0; t < rows; ++t)
+                    if (T & (1u << t)) v[j] ^= coef[t * coef_stride + j];
+                zero_one = v[j] <= 1;
+            }
+            if (!zero_one) continue;
+            best.found = true;
+            best_size = size;
+            best.order[0] = r0;
+            best.fold = 0;
+            int pos = 1;
+            for (int r = 0; r < rows; ++r)
+                if (r != r0) {
+                    if (T & (1u << r)) best.fold |= 1u << pos;
+                    best.order[pos++] = r;
+                }
+            int n = 0;
+            for (int j = 0; j < k; ++j)
+                if (v[j] == 1) best.perm[n++] = j;
+            best.n_xor = n;
+            for (int j = 0; j < k; ++j)
+                if (v[j] == 0) best.perm[n++] = j;
+        }
+    return best;
+}
+
 }  // namespace gs

@@ -58,4 +58,25 @@ bool invert_in_place(int n, Matrix &a);
 struct CoefWords { uint32_t w[5]; };
 CoefWords split_tables(uint8_t c);
 
+// A rebuild matrix has no all-ones row, but when the all-ones parity row is
+// among the survivors one of the lost data shards is the XOR of that parity
+// with all the other data shards, rebuilt ones included.  In terms of the
+// matrix R (rows x k, rows <= 4, k <= 16): some row r0 and some set T of other
+// rows satisfy
+//     R[r0] = v + sum of R[t], t in T,   with every v[j] zero or one,
+// so out[r0] = XOR of the inputs with v[j] = 1, XORed with the outputs of the
+// rows in T: one XOR per input byte instead of a table lookup.  The result
+// puts r0 first (order: position -> row of R), the inputs with v[j] = 1 first
+// (perm: position -> column of R; n_xor of them) and names T by row positions
+// (bit p of fold, p >= 1).  The smallest T is taken; found = false if there
+// is no such row.
+struct XorFold {
+    bool found;
+    int order[4];
+    int perm[16];
+    int n_xor;
+    uint32_t fold;
+};
+XorFold find_xor_fold(int rows, int k, const uint8_t *coef, int coef_stride);
+
 }  // namespace gs

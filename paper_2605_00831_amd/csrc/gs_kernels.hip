@@ -46,6 +46,12 @@ struct ApplyArgs {
     int32_t accumulate;   // XOR into the existing outputs
     uint32_t tiles_per_wg;
     uint32_t nx_shift;    // log2 of the interleave modulus (0 = plain consecutive tiles)
+    // Kernels with an XOR row: that row takes streams [0, n_xor) only, and before the stores the
+    // accumulators of the rows in `fold` (bit r = row r, r >= 1) are XORed into it.  An encode has
+    // n_xor = k and fold = 0; a rebuild whose matrix has a row that differs from the XOR of some of
+    // its other rows only by zeros and ones (see plan_fold) runs with the XOR shortcut this way.
+    int32_t n_xor;
+    uint32_t fold;
 };
 
 static_assert(sizeof(BatchDesc) == kBatchDescBytes, "descriptor size is part of the internal interface");
@@ -148,7 +154,8 @@ __device__ __forceinline__ u32x4 to_vec(const Acc4 &a) { return u32x4{a.c[0], a.
 __device__ __forceinline__ Acc4 from_vec(u32x4 v) { return Acc4{{v[0], v[1], v[2], v[3]}}; }
 
 // acc[r][u] ^= C[r][j] (x) x[u] for all rows
-template <int M, bool ROW0_XOR, int U>
+// (SKIP0: the stream is not part of the XOR row)
+template <int M, bool ROW0_XOR, int U, bool SKIP0 = false>
 __device__ __forceinline__ void mac(Acc4 (&acc)[M][U], const u32x4 (&x)[U],
                                     const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8], int j)
 {
@@ -157,7 +164,7 @@ __device__ __forceinline__ void mac(Acc4 (&acc)[M][U], const u32x4 (&x)[U],
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint32_t d = x[u][c];
-            if (ROW0_XOR) {
+            if (ROW0_XOR && !SKIP0) {
                 acc[0][u].c[c] ^= d;
                 pin(acc[0][u].c[c]);
             }
@@ -217,7 +224,8 @@ __device__ __forceinline__ void horner_step(Acc4 (&acc)[M][U], const u32x4 (&x)[
 // KB: how many streams' loads are issued together before their arithmetic.
 template <int M, bool ROW0_XOR, int U, bool NT, bool FULL, bool HORNER, int KB, class S>
 __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
-                                            int k, int accumulate, const uint64_t (&piece)[U], uint32_t lane)
+                                            int k, int accumulate, int n_xor, uint32_t fold,
+                                            const uint64_t (&piece)[U], uint32_t lane)
 {
     // piece[u]: first vector of this wavefront's u-th piece (wavefront-uniform)
     bool ok[U];
@@ -264,7 +272,10 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
             }
         }
     }
-    for (; j < k; ++j) {
+    // the bulk form of a kernel with an XOR row and more rows: the streams that row takes come first
+    constexpr bool kFolds = ROW0_XOR && !HORNER && KB == 1 && M > 1;
+    const int first_end = kFolds ? n_xor : k;
+    for (; j < first_end; ++j) {
         const uint8_t *src = s.in[HORNER ? k - 1 - j : j];
         u32x4 x[U];
 #pragma unroll
@@ -274,6 +285,25 @@ __device__ __forceinline__ void contig_tile(const S &s, const uint32_t (&tab)[kL
         }
         if constexpr (HORNER) horner_step<M, U>(acc, x);
         else mac<M, ROW0_XOR, U>(acc, x, tab, j);
+    }
+    if constexpr (kFolds) {
+        for (; j < k; ++j) {
+            u32x4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                x[u] = u32x4{0, 0, 0, 0};
+                if (ok[u]) x[u] = load_piece<NT>(s.in[j], piece[u], lane);
+            }
+            mac<M, true, U, true>(acc, x, tab, j);
+        }
+#pragma unroll
+        for (int r = 1; r < M; ++r)
+            if (fold & (1u << r)) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[0][u].c[c] ^= acc[r][u].c[c];
+            }
     }
 
 #pragma unroll
@@ -309,7 +339,8 @@ constexpr int kWavesPerEu()
 // exactly once.  nx_shift = 0 gives plain consecutive tiles.
 template <int M, bool ROW0_XOR, int U, bool NT, bool HORNER, int KB = 1, class S>
 __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)[kLaunchMaxM][kLaunchMaxK][8],
-                                               int k, int accumulate, uint32_t tiles_per_wg, bool last_wg)
+                                               int k, int accumulate, uint32_t tiles_per_wg, bool last_wg,
+                                               int n_xor, uint32_t fold = 0)
 {
     const uint32_t tid = threadIdx.x;
     // the wavefront's index is the same in all of its lanes: say so, which keeps everything derived
@@ -331,8 +362,10 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
 #pragma unroll
         for (int u = 0; u < U; ++u) piece[u] = (((g * kPieces + wave * U + u) << nx_shift) + r) << 6;
         const uint64_t super_end = (((g + 1) * kPieces) << nx_shift) * 64;
-        if (super_end <= nvec) contig_tile<M, ROW0_XOR, U, NT, true, HORNER, KB>(s, tab, k, accumulate, piece, lane);
-        else contig_tile<M, ROW0_XOR, U, NT, false, HORNER, KB>(s, tab, k, accumulate, piece, lane);
+        if (super_end <= nvec)
+            contig_tile<M, ROW0_XOR, U, NT, true, HORNER, KB>(s, tab, k, accumulate, n_xor, fold, piece, lane);
+        else
+            contig_tile<M, ROW0_XOR, U, NT, false, HORNER, KB>(s, tab, k, accumulate, n_xor, fold, piece, lane);
     }
 
     // trailing bytes of a shard whose length is not a multiple of 16: one
@@ -346,7 +379,7 @@ __device__ __forceinline__ void contig_streams(const S &s, const uint32_t (&tab)
             uint32_t sum = accumulate ? dst[t] : 0u;
             for (int j = 0; j < k; ++j) {
                 const uint32_t xb = s.in[j][t];
-                sum ^= (ROW0_XOR && r == 0) ? xb : mul1(tab[r][j], xb);
+                sum ^= mul1(tab[r][j], xb);  // row 0 too: its table holds the row's own coefficients
             }
             dst[t] = static_cast<uint8_t>(sum);
         }
@@ -357,7 +390,8 @@ template <int M, bool ROW0_XOR, int U, bool NT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, U>(), 8)))
 void apply_contig_kernel(const ApplyArgs a)
 {
-    contig_streams<M, ROW0_XOR, U, NT, false>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, U, NT, false>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1,
+                                              a.n_xor, a.fold);
 }
 
 // The same for launches that do not fill the chip (a chunk of a few MiB, a
@@ -366,7 +400,7 @@ template <int M, bool ROW0_XOR, bool NT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, ROW0_XOR, 2>(), 8)))
 void apply_contig_small_kernel(const ApplyArgs a)
 {
-    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(a, a.tab, a.k, a.accumulate, a.tiles_per_wg, blockIdx.x == gridDim.x - 1, a.k);
 }
 
 // Power-code encode by Horner's rule (rows 1, 2^j, 4^j): same tiles, same
@@ -376,7 +410,7 @@ template <int M, int U, bool NT, int KB = 1>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWavesPerEu<M, true, U>(), 8)))
 void horner_contig_kernel(const ApplyArgs a)
 {
-    contig_streams<M, true, U, NT, true, KB>(a, a.tab, a.k, 0, a.tiles_per_wg, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, true, U, NT, true, KB>(a, a.tab, a.k, 0, a.tiles_per_wg, blockIdx.x == gridDim.x - 1, a.k);
 }
 
 // Many independent chunks in one launch (one request's chunk, or one chunk of
@@ -390,7 +424,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWaves
 void apply_batch_kernel(const BatchArgs a)
 {
     ConstDesc d = (ConstDesc)a.descs + blockIdx.y;
-    contig_streams<M, ROW0_XOR, U, NT, false>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, U, NT, false>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1, a.k);
 }
 
 // The grouped launch when all its chunks together do not fill the chip.
@@ -399,7 +433,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kWaves
 void apply_batch_small_kernel(const BatchArgs a)
 {
     ConstDesc d = (ConstDesc)a.descs + blockIdx.y;
-    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1);
+    contig_streams<M, ROW0_XOR, 2, NT, false, 4>(*d, a.tab, a.k, 0, 1u, blockIdx.x == gridDim.x - 1, a.k);
 }
 
 // One tile of the paged gather.  A lane whose vector index is past the end of
@@ -737,8 +771,10 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     if (rows < 1 || rows > kLaunchMaxM || k < 1 || k > kLaunchMaxK) return hipErrorInvalidValue;
     if (bytes == 0) return hipSuccess;
     ApplyArgs a;
-    const bool row0_xor = fill_rows(a, rows, k, coef, coef_stride, out);
+    bool row0_xor = fill_rows(a, rows, k, coef, coef_stride, out);
     for (int j = 0; j < kLaunchMaxK; ++j) a.in[j] = j < k ? static_cast<const uint8_t *>(in[j]) : nullptr;
+    a.n_xor = k;
+    a.fold = 0;
     a.nvec = bytes / 16;
     a.tail = static_cast<uint32_t>(bytes % 16);
     a.k = k;
@@ -751,9 +787,32 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    const size_t lds = tpw == 1 ? contig_reservation(shape, unroll, rows, row0_xor, k, wgs) : 0;
     if (unroll == 2 && tpw == 1 && k > 1 && wgs <= kSmallWorkgroups)
-        return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds, stream);
+        return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), 0, stream);
+    // Three and four lookup rows keep the vector ALU busy 70 to 80 % of the time at the HBM rate; with one
+    // of them turned into an XOR row the rebuild of three shards runs at the rate of the 8+3 encode.
+    // (Measured: 8+3 less three 82 -> 83.5 to 84.5 %, 16+3 80 -> 83.6 %, 8+4 less four 79.5 -> 81 to 82.7 %, 16+4
+    // 73 -> 79 %.  Two-row rebuilds are HBM-bound either way -- level at k = 4 and 16, 1 to 2 points worse
+    // folded at k = 8 -- and stay as they are; a launch that accumulates into its outputs cannot fold,
+    // its accumulators start from the previous contents.)
+    if (!row0_xor && rows >= 3 && !accumulate) {
+        const XorFold f = find_xor_fold(rows, k, coef, coef_stride);
+        if (f.found) {
+            RowPlan p;
+            for (int r = 0; r < kLaunchMaxM; ++r) p.order[r] = f.order[r];
+            p.row0_xor = true;
+            uint8_t permuted[kLaunchMaxM * kLaunchMaxK];
+            for (int r = 0; r < rows; ++r)
+                for (int j = 0; j < k; ++j) permuted[r * kLaunchMaxK + j] = coef[r * coef_stride + f.perm[j]];
+            fill_tables(a, p, rows, k, permuted, kLaunchMaxK);
+            for (int r = 0; r < rows; ++r) a.out[r] = static_cast<uint8_t *>(out[f.order[r]]);
+            for (int j = 0; j < k; ++j) a.in[j] = static_cast<const uint8_t *>(in[f.perm[j]]);
+            a.n_xor = f.n_xor;
+            a.fold = f.fold;
+            row0_xor = true;
+        }
+    }
+    const size_t lds = tpw == 1 ? contig_reservation(shape, unroll, rows, row0_xor, k, wgs) : 0;
     return dispatch<ContigLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds, stream);
 }
 

@@ -415,7 +415,7 @@ static int check_occupancy_reservation()
     struct Case { int k, m, kind; const int *erased; int n_erased; size_t want; } cases[] = {
         {4, 2, GS_CAUCHY, nullptr, 0, four},  {4, 2, GS_CAUCHY, e2, 2, four},  {4, 2, GS_CAUCHY, e1, 1, three},   // the 8B workload
         {8, 2, GS_CAUCHY, nullptr, 0, three}, {8, 2, GS_CAUCHY, e2, 2, four},                                     // the 70B workload
-        {8, 3, GS_CAUCHY, nullptr, 0, four},  {8, 3, GS_CAUCHY, e3, 3, four},  {16, 3, GS_CAUCHY, e3, 3, 0},
+        {8, 3, GS_CAUCHY, nullptr, 0, four},  {8, 3, GS_CAUCHY, e3, 3, four},  {16, 3, GS_CAUCHY, e3, 3, four},
         {4, 1, GS_CAUCHY, nullptr, 0, three}, {2, 1, GS_CAUCHY, nullptr, 0, four}, {1, 1, GS_CAUCHY, nullptr, 0, 0},
         {2, 2, GS_CAUCHY, nullptr, 0, four},
         {8, 4, GS_CAUCHY, nullptr, 0, 0},     {8, 4, GS_CAUCHY, e4, 4, 0},     {1, 4, GS_CAUCHY, nullptr, 0, three},   // four rows: left alone

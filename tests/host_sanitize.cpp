@@ -93,6 +93,70 @@ int main()
         double t = -1.0;
         if (gs_recompute_units(n, &costs, &r, &t) != GS_OK || r < 0 || r > n || !(t >= 0.0)) return fail("planner", n, r);
     }
+    // The XOR fold of a rebuild matrix: for every loss of three or four shards of several codes, rebuild
+    // matrix from the k lowest survivors, then the plan applied to random bytes the way the kernel applies
+    // it (XOR row over the first n_xor permuted inputs, lookup rows, fold) against the plain product.
+    {
+        unsigned rng = 12345;
+        auto next = [&]() { rng = rng * 1664525u + 1013904223u; return static_cast<uint8_t>(rng >> 24); };
+        const int shapes[][2] = {{4, 3}, {8, 3}, {6, 4}, {16, 4}, {5, 4}};
+        for (const auto &km : shapes) {
+            const int k = km[0], m = km[1], n = k + m;
+            const Matrix P = cauchy_parity_block(k, m);
+            auto g = [&](int row, int col) -> uint8_t { return row < k ? (row == col) : P[(row - k) * k + col]; };
+            int with_p0 = 0, found_with_p0 = 0;
+            for (unsigned pat = 0; pat < (1u << n); ++pat) {
+                const int e = __builtin_popcount(pat);
+                if (e < 3 || e > m) continue;
+                std::vector<int> lost, surv;
+                for (int r = 0; r < n; ++r) {
+                    if (pat & (1u << r)) lost.push_back(r);
+                    else if (static_cast<int>(surv.size()) < k) surv.push_back(r);
+                }
+                Matrix A(static_cast<size_t>(k) * k);
+                for (int r = 0; r < k; ++r)
+                    for (int c = 0; c < k; ++c) A[r * k + c] = g(surv[r], c);
+                if (!invert_in_place(k, A)) return fail("survivors singular", k, static_cast<int>(pat));
+                Matrix R(static_cast<size_t>(e) * k, 0);
+                for (int r = 0; r < e; ++r)
+                    for (int c = 0; c < k; ++c)
+                        for (int t = 0; t < k; ++t) R[r * k + c] ^= gf_mul(g(lost[r], t), A[t * k + c]);
+                const XorFold f = find_xor_fold(e, k, R.data(), k);
+                bool data_lost = false, p0_used = false;
+                for (int r : lost) data_lost = data_lost || r < k;
+                for (int r : surv) p0_used = p0_used || r == k;
+                if (data_lost && p0_used) {
+                    ++with_p0;
+                    found_with_p0 += f.found;
+                }
+                if (!f.found) continue;
+                if (f.n_xor < 0 || f.n_xor > k || (f.fold & 1u) || (f.fold >> e)) return fail("fold plan range", k, static_cast<int>(pat));
+                uint8_t x[16], want[4], acc[4] = {0, 0, 0, 0};
+                for (int j = 0; j < k; ++j) x[j] = next();
+                for (int r = 0; r < e; ++r) {
+                    want[r] = 0;
+                    for (int j = 0; j < k; ++j) want[r] ^= gf_mul(R[r * k + j], x[j]);
+                }
+                for (int jj = 0; jj < k; ++jj) {
+                    const uint8_t xp = x[f.perm[jj]];
+                    if (jj < f.n_xor) acc[0] ^= xp;
+                    for (int pos = 1; pos < e; ++pos) acc[pos] ^= gf_mul(R[f.order[pos] * k + f.perm[jj]], xp);
+                }
+                for (int pos = 1; pos < e; ++pos)
+                    if (f.fold & (1u << pos)) acc[0] ^= acc[pos];
+                for (int pos = 0; pos < e; ++pos)
+                    if (acc[pos] != want[f.order[pos]]) return fail("fold plan result", k, static_cast<int>(pat));
+            }
+            // whenever the all-ones parity row is used and a data shard is lost there is such a row
+            if (with_p0 == 0 || found_with_p0 != with_p0) return fail("fold not found", with_p0, found_with_p0);
+        }
+        // an encode matrix has its all-ones row found with nothing to fold; a matrix without structure has none
+        const Matrix P = cauchy_parity_block(8, 3);
+        const XorFold enc = find_xor_fold(3, 8, P.data(), 8);
+        if (!enc.found || enc.order[0] != 0 || enc.n_xor != 8 || enc.fold != 0) return fail("encode fold", enc.n_xor, enc.fold);
+        const uint8_t none[2 * 3] = {2, 3, 4, 5, 7, 9};
+        if (find_xor_fold(2, 3, none, 3).found) return fail("fold in a matrix without one", 0, 0);
+    }
     std::printf("OK\n");
     return 0;
 }

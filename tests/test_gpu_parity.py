@@ -635,3 +635,26 @@ def test_horner_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m):
 ])
 def test_paged_encode_on_both_sides_of_the_small_launch_threshold(gs, k, m, n_planes, pps, page_bytes):
     _paged_case(gs, k, m, n_planes, pps, page_bytes, seed=k + pps)
+
+
+@pytest.mark.parametrize("k,m,sizes", [(8, 3, (3,)), (6, 4, (3, 4)), (16, 3, (3,)), (4, 4, (3, 4))])
+def test_bulk_rebuild_of_three_and_four_shards_every_pattern(gs, k, m, sizes):
+    """Launches above the small-launch threshold rebuild three and four shards with one row of the matrix
+    turned into an XOR row where the matrix allows it (the all-ones parity among the survivors).  Every
+    loss pattern (a seeded sample of 120 for 16+3), ragged length: a partial last tile and trailing bytes.
+    The stripe is the oracle's; a rebuilt shard must equal the oracle's shard."""
+    S = 1056 * 8192 + 3 * 16 + 5
+    P, full = _stripe_on_gpu(gs, k, m, S, seed=17 * k + m)
+    code = gs.gs_make_code(k, m)
+    good = [torch.cat([dev(x), torch.full((PAD,), CANARY, dtype=torch.uint8, device="cuda")]) for x in full]
+    work = [g.clone() for g in good]
+    pats = [p for e in sizes for p in itertools.combinations(range(k + m), e)]
+    if len(pats) > 400:
+        rng = np.random.default_rng(5)
+        pats = [pats[i] for i in sorted(rng.choice(len(pats), 120, replace=False))]
+    for pat in pats:
+        for r in pat:
+            work[r][:S] = 0xA5
+        gs.gs_reconstruct(code, work, list(pat), S)
+        for r in range(k + m):
+            assert torch.equal(work[r], good[r]), (pat, r)
