@@ -40,7 +40,7 @@ MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE and WRITE_SIZE scaled to 
                                    "profiles/horner_power_code_llama8b_prefill.md"),
     ("llama70b_longctx", "cauchy"): (53686516541, "apply_contig_kernel<2, true, 2, true>",
                                      "profiles/encode_contig_llama70b_longctx.md"),
-    ("recovery_stress", "cauchy"): (5905705984, "apply_contig_kernel<3, true, 2, true>",
+    ("recovery_stress", "cauchy"): (5905681714, "apply_contig_kernel<3, true, 2, true>",
                                     "profiles/encode_contig_recovery_stress.md"),
 }
 
