@@ -263,3 +263,45 @@ def test_random_grouped_and_rdp_paged_cases_against_the_oracle():
             gs.gs_pipe_destroy(pipe)
     finally:
         gs.gs_set_launch_shape()
+
+
+def test_random_bulk_size_cases_against_the_oracle():
+    """The kernel forms of launches that fill the chip (one stream at a time, LDS reservation from 48 MiB
+    shards on, rebuilds of three and four shards with a folded XOR row): random code, length between
+    9 and 70 MiB with a ragged end, default launch shape, random loss pattern; encode against the oracle,
+    the rebuilt shards against the stripe."""
+    from paper_2605_00831_amd import binding as gs
+    gs.lib()
+    gs.gs_set_launch_shape()
+    rng = np.random.default_rng(inputs.SEED_BASE + 0x340)
+    for case in range(12):
+        kind = ["cauchy", "power", "rdp"][int(rng.integers(0, 3))]
+        if kind == "rdp":
+            k, m = int(rng.integers(2, 13)), 2
+            cell = 4096
+            code = gs.gs_make_rdp_code(k, cell)
+            unit = (gs.gs_rdp_prime(code) - 1) * cell
+            S = unit * int(rng.integers((9 << 20) // unit + 1, (70 << 20) // unit))
+        else:
+            k = int(rng.integers(2, 13))
+            m = int(rng.integers(1, 4 if kind == "power" else 5))
+            code = gs.gs_make_code(k, m, gs.GS_POWER if kind == "power" else gs.GS_CAUCHY)
+            S = int(rng.integers(9 << 20, 70 << 20)) | 1
+            P = oracle.power_generator(k, m) if kind == "power" else oracle.generator(k, m)
+        data_np = [inputs.uniform_bytes_np(7000 + case * 100 + j, S) for j in range(k)]
+        want = oracle.rdp_encode(data_np, cell) if kind == "rdp" else oracle.encode(P, data_np, nthreads=8)
+        good = [torch.cat([torch.from_numpy(x).cuda(), torch.full((32,), 0xC7, dtype=torch.uint8, device="cuda")])
+                for x in data_np + want]
+        par = [torch.full((S + 32,), 0xC7, dtype=torch.uint8, device="cuda") for _ in range(m)]
+        gs.gs_encode(code, good[:k], par, S)
+        for i in range(m):
+            assert torch.equal(par[i], good[k + i]), (case, kind, k, m, S, i)
+        for _ in range(3):
+            e = int(rng.integers(1, m + 1))
+            pat = sorted(int(x) for x in rng.choice(k + m, size=e, replace=False))
+            shards = [g.clone() for g in good]
+            for r in pat:
+                shards[r][:S] = 0xA5
+            gs.gs_reconstruct(code, shards, pat, S)
+            for r in range(k + m):
+                assert torch.equal(shards[r], good[r]), (case, kind, k, m, S, pat, r)
