@@ -154,11 +154,12 @@ __global__ __launch_bounds__(kThreads) void rdp_batch_kernel(const RdpBatchArgs 
     else rdp_tile<P, E, W, false>(a, v);
 }
 
-// LDS reservation of a bulk RDP launch (8-byte vectors; measured for every prime on 2 GiB shards):
+// LDS reservation of a bulk RDP launch (8-byte vectors; measured for every prime on 1 and 2 GiB shards):
 // a wavefront of p = 3 has two loads per disk in flight and needs full occupancy; p = 5 and 7 gain
-// 2 to 5 points of HBM peak with three workgroups per CU, p >= 11 with two -- except the rebuild of two
-// shards at p = 11 and 13, whose cells are XORs of many syndromes: its arithmetic wants the third workgroup
-// (at p = 17 the registers allow no more than three anyway).
+// 2 to 5 points of HBM peak with three workgroups per CU, p >= 11 with two.  Rebuilds of two data
+// shards, whose cells are XORs of many syndromes, want one workgroup more for their arithmetic: four
+// at p = 5 and 7 (+1.5 to +2 points over three), three at p = 11 and 13 (at p = 17 the registers allow
+// no more than three anyway).  Such plans are told by the share of syndromes in a cell.
 static size_t rdp_reservation(const LaunchShape &shape, const RdpPlan &plan, int w, uint64_t workgroups)
 {
     const int p = plan.p;
@@ -166,10 +167,11 @@ static size_t rdp_reservation(const LaunchShape &shape, const RdpPlan &plan, int
     // a workgroup moves 2 KiB of each of a disk's p - 1 rows; the reservation pays from 96 MiB per disk
     // on (p = 17: from 256 MiB), below that it costs up to 5 points
     if (workgroups * static_cast<uint64_t>(p - 1) < (p < 17 ? kRdpCapMinRowPieces : 8 * kRdpCapMinRowPieces / 3)) return 0;
-    if (p < 11) return lds_for_workgroups_per_cu(3);
     size_t bits = 0;
     for (uint32_t m : plan.syndrome_mask) bits += static_cast<size_t>(__builtin_popcount(m));
-    const bool dense = bits > 4 * plan.syndrome_mask.size();
+    const size_t cells = plan.syndrome_mask.size();
+    if (p < 11) return lds_for_workgroups_per_cu(10 * bits > 7 * static_cast<size_t>(p - 1) * cells ? 4 : 3);
+    const bool dense = bits > 4 * cells;
     return lds_for_workgroups_per_cu(dense && p < 17 ? 3 : 2);
 }
 

@@ -411,7 +411,7 @@ static int check_occupancy_reservation()
         return static_cast<long>(ops[0].shmem);
     };
     const size_t big = 1ull << 30, small = 1ull << 20;
-    const int e1[1] = {1}, e2[2] = {1, 3}, e3[3] = {0, 1, 2}, e4[4] = {0, 1, 2, 3};
+    const int e1[1] = {1}, e2[2] = {1, 3}, e3[3] = {0, 1, 2}, e4[4] = {0, 1, 2, 3}, e14[2] = {1, 6}, e02[2] = {0, 2};
     struct Case { int k, m, kind; const int *erased; int n_erased; size_t want; } cases[] = {
         {4, 2, GS_CAUCHY, nullptr, 0, four},  {4, 2, GS_CAUCHY, e2, 2, four},  {4, 2, GS_CAUCHY, e1, 1, three},   // the 8B workload
         {8, 2, GS_CAUCHY, nullptr, 0, three}, {8, 2, GS_CAUCHY, e2, 2, four},                                     // the 70B workload
@@ -421,6 +421,7 @@ static int check_occupancy_reservation()
         {8, 4, GS_CAUCHY, nullptr, 0, 0},     {8, 4, GS_CAUCHY, e4, 4, 0},     {1, 4, GS_CAUCHY, nullptr, 0, three},   // four rows: left alone
         {8, 3, GS_POWER, nullptr, 0, three},  {2, 2, GS_POWER, nullptr, 0, three},                                 // Horner kernel
         {2, 2, GS_RDP, nullptr, 0, 0},        {4, 2, GS_RDP, nullptr, 0, three}, {6, 2, GS_RDP, e1, 1, three},
+        {4, 2, GS_RDP, e2, 2, four},          {6, 2, GS_RDP, e02, 2, four},      {6, 2, GS_RDP, e14, 2, three},   // cells of many syndromes; of few
         {10, 2, GS_RDP, nullptr, 0, two},     {10, 2, GS_RDP, e2, 2, three},     {10, 2, GS_RDP, e1, 1, two},
         {16, 2, GS_RDP, e2, 2, two},
     };
