@@ -837,6 +837,8 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     a.tail = static_cast<uint32_t>(bytes % 16);
     a.k = k;
     a.accumulate = 0;
+    a.n_xor = k;
+    a.fold = 0;
     const int unroll = sane_unroll(shape.unroll, rows);
     uint32_t nx_shift;
     uint64_t tiles;
