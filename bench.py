@@ -456,7 +456,9 @@ def launch_sizes(torch, gs, log, cap=True):
     that is, and for launches that do not fill the chip the time from the call to an idle stream as a
     host thread sees it.  Bulk sizes are timed with the LDS reservation on and off.  The library picks
     a kernel form by size (four streams' loads together up to 1024 workgroups of 8 KiB per stream, one
-    stream at a time above, fewer workgroups per CU from 48 MiB on); this leg shows all three regimes."""
+    stream at a time above, fewer workgroups per CU from 48 MiB on); this leg shows all three regimes.
+    (The small-launch form against the bulk form on small launches is timed from C, without the
+    interpreter's per-call cost: `many_chunks.from_c`, `decode_step.native`.)"""
     arena = device_arena(torch, 10 << 30)
     rows = []
 
@@ -509,6 +511,22 @@ def launch_sizes(torch, gs, log, cap=True):
                         gs.gs_set_occupancy_cap(True)
                     row[name]["frac_without_reservation"] = round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)
             rows.append(row)
+    # a rebuild of three shards with the all-ones parity among the survivors: one lost shard as a plain XOR
+    # (the default) against three lookup rows (gs_set_size_forms(0)), in one process on the same buffers
+    k, m, S, erased = 8, 3, 512 << 20, [2, 5, 9]
+    code = gs.gs_make_code(k, m)
+    shards = [arena[j * S:(j + 1) * S] for j in range(k + m)]
+    gs.gs_encode(code, shards[:k], shards[k:], S)
+    rec = lambda: gs.gs_reconstruct(code, shards, erased, S)
+    row = {"k": k, "m": m, "shard_bytes": S, "erased": erased}
+    for name, on in (("xor_fold", True), ("lookup_rows", False), ("xor_fold_again", True), ("lookup_rows_again", False)):
+        gs.gs_set_size_forms(on)
+        try:
+            us = per_launch_us(rec, 10)
+        finally:
+            gs.gs_set_size_forms(True)
+        row[name] = {"us": round(us, 2), "frac": round((k + len(erased)) * S / us / 1e3 / HBM_PEAK_GBPS, 4)}
+    rows.append({"rebuild_of_three_shards": row})
     log("[bench] launch sizes: " + json.dumps(rows))
     return rows
 

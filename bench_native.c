@@ -191,13 +191,15 @@ static int run_decode(int steps, int layers)
     CHECK_HIP(hipStreamSynchronize(c.stream));
 
     /* ---- (a) one step at a time: launch -> stream idle on the host clock */
+    /* the last one is the eager step again with the kernel form of small launches switched off */
     static const char *names[] = {"eager", "eager_d2h", "eager_pinned", "graph", "graph_d2h", "graph_captured_on_launch_stream",
-                                  "graph_uploaded"};
-    const step_fn fns[] = {eager, eager_d2h, eager_pinned, graph, graph_d2h, graph_own, graph_uploaded};
+                                  "graph_uploaded", "eager_bulk_kernel_form"};
+    const step_fn fns[] = {eager, eager_d2h, eager_pinned, graph, graph_d2h, graph_own, graph_uploaded, eager};
     double *lat = (double *)malloc(sizeof(double) * steps);
     printf("{\"steps\": %d, \"layers\": %d, \"new_kv_bytes_per_step\": %zu, \"parity_bytes_per_step\": %zu",
            steps, layers, (size_t)K * c.out_bytes, (size_t)M * c.out_bytes);
-    for (int v = 0; v < 7; v++) {
+    for (int v = 0; v < 8; v++) {
+        CHECK_GS(gs_set_size_forms(v != 7));
         for (int s = 0; s < steps + warm; s++) {
             CHECK_HIP(hipMemcpyAsync(c.table_dev, tables + (size_t)s * SEQS, table_bytes, hipMemcpyHostToDevice, c.stream));
             CHECK_HIP(hipStreamSynchronize(c.stream));
@@ -209,6 +211,7 @@ static int run_decode(int steps, int layers)
         }
         print_stats(names[v], lat, steps);
     }
+    CHECK_GS(gs_set_size_forms(1));
     /* a graph that holds GRAPH_STEPS steps: the engine writes that many tables ahead, one replay
      * encodes them all; time per step = replay -> idle / GRAPH_STEPS */
     {
@@ -439,12 +442,14 @@ static int run_many(void)
             for (int i = 0; i < m; i++) par[c * m + i] = shards[c * (k + m) + k + i];
             sizes[c] = S;
         }
-        double t[3][32];
-        for (int form = 0; form < 3; form++)
+        double t[4][32];
+        for (int form = 0; form < 4; form++) {
+            /* form 3: one launch per chunk again, with the kernel form of small launches switched off */
+            CHECK_GS(gs_set_size_forms(form != 3));
             for (int it = 0; it < iters + warm; it++) {
                 CHECK_HIP(hipStreamSynchronize(stream));
                 const double t0 = now_us();
-                if (form == 0) {
+                if (form == 0 || form == 3) {
                     for (int c = 0; c < n; c++)
                         CHECK_GS(e ? gs_reconstruct(code, shards + (size_t)c * (k + m), shapes[sh].erased, e, S, stream)
                                    : gs_encode(code, data + (size_t)c * k, par + (size_t)c * m, S, stream));
@@ -458,13 +463,15 @@ static int run_many(void)
                 CHECK_HIP(hipStreamSynchronize(stream));
                 if (it >= warm) t[form][it - warm] = (now_us() - t0) * 1e-3;
             }
+        }
+        CHECK_GS(gs_set_size_forms(1));
         const double traffic = (double)(k + (e ? e : m)) * S * n;
         const double grouped = median_of(t[2], iters);
         printf("%s{\"op\": \"%s\", \"k\": %d, \"m\": %d, \"n_erased\": %d, \"chunks\": %d, \"shard_bytes\": %zu, "
                "\"one_launch_per_chunk_ms\": %.4f, \"stream_pool_16_ms\": %.4f, \"grouped_launch_ms\": %.4f, "
-               "\"grouped_launch_traffic_GBps\": %.1f}",
+               "\"grouped_launch_traffic_GBps\": %.1f, \"one_launch_per_chunk_bulk_kernel_form_ms\": %.4f}",
                sh ? ", " : "", e ? "reconstruct" : "encode", k, m, e, n, S, median_of(t[0], iters), median_of(t[1], iters),
-               grouped, traffic / grouped / 1e6);
+               grouped, traffic / grouped / 1e6, median_of(t[3], iters));
         gs_batch_destroy(batch);
         gs_pool_destroy(pool);
         gs_free_code(code);

@@ -433,6 +433,18 @@ int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int inter
  * (process-wide and atomic like the knobs above; gs_set_launch_shape leaves it
  * as it is).  Results are identical either way.  Default: enabled. */
 int gs_set_occupancy_cap(int enable);
+/* Two kinds of launches run kernel forms of their own.  A launch that does
+ * not fill the chip (at most 1024 workgroups: shards up to 8 MiB, a decode
+ * step, a small group of chunks) issues the loads of four streams together,
+ * because its time is a wavefront's memory round trips one after the other.
+ * A bulk rebuild of three or four contiguous shards with the all-ones parity
+ * among the survivors computes one of the lost shards as a plain XOR of
+ * inputs and of the other rebuilt shards instead of by table lookups.
+ * enable = 0 sends both through the general bulk form; the bytes are the same
+ * either way, which is what the switch is for: tests compare the forms, and
+ * bench.py times them side by side.  Process-wide and atomic like the knobs
+ * above; gs_set_launch_shape leaves it as it is.  Default: enabled. */
+int gs_set_size_forms(int enable);
 /* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
  * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0
  * with g = 2^r; one packed multiply-by-2 per stream and row, no table

@@ -28,6 +28,7 @@ EXPORTS = [
     "gs_recompute_units",
     "gs_strerror", "gs_last_hip_error", "gs_coef_words", "gs_set_launch_shape", "gs_set_power_horner",
     "gs_set_occupancy_cap",
+    "gs_set_size_forms",
 ]
 
 _vp = ctypes.c_void_p
@@ -123,6 +124,7 @@ def lib():
     L.gs_set_launch_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.gs_set_power_horner.argtypes = [ctypes.c_int]
     L.gs_set_occupancy_cap.argtypes = [ctypes.c_int]
+    L.gs_set_size_forms.argtypes = [ctypes.c_int]
     _lib = L
     return L
 
@@ -493,6 +495,10 @@ def gs_set_power_horner(enable=True):
 
 def gs_set_occupancy_cap(enable=True):
     _check(lib().gs_set_occupancy_cap(1 if enable else 0), "gs_set_occupancy_cap")
+
+
+def gs_set_size_forms(enable=True):
+    _check(lib().gs_set_size_forms(1 if enable else 0), "gs_set_size_forms")
 
 
 def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1, interleave_shift=-1):

@@ -23,13 +23,13 @@ thread_local int g_last_hip_error = 0;
 // gs_set_launch_shape().  The four knobs live in one atomic word, so a launch
 // that runs while another thread changes them sees either the old or the new
 // set, never a mixture; every setting gives the same bytes.
-static constexpr LaunchShape kDefaultShape = {0, 1, 1, 5, 1};  // unroll 0: chosen per kernel family
+static constexpr LaunchShape kDefaultShape = {0, 1, 1, 5, 1, 1};  // unroll 0: chosen per kernel family
 
 static constexpr uint64_t pack_shape(const LaunchShape &s)
 {
     return static_cast<uint64_t>(static_cast<uint8_t>(s.unroll)) | (static_cast<uint64_t>(static_cast<uint8_t>(s.nontemporal)) << 8) |
            (static_cast<uint64_t>(static_cast<uint8_t>(s.interleave_shift)) << 16) |
-           (static_cast<uint64_t>(s.occupancy_cap ? 1u : 0u) << 24) |
+           (static_cast<uint64_t>(s.occupancy_cap ? 1u : 0u) << 24) | (static_cast<uint64_t>(s.size_forms ? 1u : 0u) << 25) |
            (static_cast<uint64_t>(static_cast<uint32_t>(s.tiles_per_wg)) << 32);
 }
 
@@ -43,6 +43,7 @@ LaunchShape current_shape()
     s.nontemporal = static_cast<int>((w >> 8) & 0xFF);
     s.interleave_shift = static_cast<int>((w >> 16) & 0xFF);
     s.occupancy_cap = static_cast<int>((w >> 24) & 1);
+    s.size_forms = static_cast<int>((w >> 25) & 1);
     s.tiles_per_wg = static_cast<int>(w >> 32);
     return s;
 }
@@ -605,10 +606,11 @@ int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int inter
         if (interleave_shift > 10) return GS_EINVAL;
         s.interleave_shift = interleave_shift;
     }
-    // the occupancy switch is a knob of its own: keep what it says
+    // the occupancy and kernel-form switches are knobs of their own: keep what they say
     uint64_t old = g_shape.load(std::memory_order_relaxed), next;
     do {
         s.occupancy_cap = static_cast<int>((old >> 24) & 1);
+        s.size_forms = static_cast<int>((old >> 25) & 1);
         next = pack_shape(s);
     } while (!g_shape.compare_exchange_weak(old, next, std::memory_order_relaxed));
     return GS_OK;
@@ -619,6 +621,15 @@ int gs_set_occupancy_cap(int enable)
     uint64_t old = g_shape.load(std::memory_order_relaxed), next;
     do {
         next = enable ? (old | (1ull << 24)) : (old & ~(1ull << 24));
+    } while (!g_shape.compare_exchange_weak(old, next, std::memory_order_relaxed));
+    return GS_OK;
+}
+
+int gs_set_size_forms(int enable)
+{
+    uint64_t old = g_shape.load(std::memory_order_relaxed), next;
+    do {
+        next = enable ? (old | (1ull << 25)) : (old & ~(1ull << 25));
     } while (!g_shape.compare_exchange_weak(old, next, std::memory_order_relaxed));
     return GS_OK;
 }

@@ -84,6 +84,7 @@ struct PagedArgs {
     uint32_t tiles_per_wg;
     uint32_t nx_shift;         // log2 of the piece interleave modulus
     uint32_t mixed;            // 0: inputs are consecutive table rows, outputs dense
+    uint32_t small_form;       // host side only: a launch that does not fill the chip may take its own kernel form
 };
 
 template <bool NT>
@@ -693,7 +694,7 @@ struct PagedLauncher {
     static void launch(const PagedArgs &a, dim3 grid, size_t lds, hipStream_t stream)
     {
         if constexpr (U == 1) {
-            if (a.k > 1 && static_cast<uint64_t>(grid.x) * grid.y <= kSmallWorkgroups) {
+            if (a.small_form && a.k > 1 && static_cast<uint64_t>(grid.x) * grid.y <= kSmallWorkgroups) {
                 hipLaunchKernelGGL((apply_paged_kernel<M, X, U, WAVE_PAGE, MIXED, 4>), grid, dim3(kThreads), lds, stream, a);
                 return;
             }
@@ -787,7 +788,7 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    if (unroll == 2 && tpw == 1 && k > 1 && wgs <= kSmallWorkgroups)
+    if (shape.size_forms && unroll == 2 && tpw == 1 && k > 1 && wgs <= kSmallWorkgroups)
         return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), 0, stream);
     // Three and four lookup rows keep the vector ALU busy 70 to 80 % of the time at the HBM rate; with one
     // of them turned into an XOR row the rebuild of three shards runs at the rate of the 8+3 encode.
@@ -795,7 +796,7 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     // 73 -> 79 %.  Two-row rebuilds are HBM-bound either way -- level at k = 4 and 16, 1 to 2 points worse
     // folded at k = 8 -- and stay as they are; a launch that accumulates into its outputs cannot fold,
     // its accumulators start from the previous contents.)
-    if (!row0_xor && rows >= 3 && !accumulate) {
+    if (shape.size_forms && !row0_xor && rows >= 3 && !accumulate) {
         const XorFold f = find_xor_fold(rows, k, coef, coef_stride);
         if (f.found) {
             RowPlan p;
@@ -851,7 +852,7 @@ hipError_t launch_horner(int rows, int k, const uint8_t *coef, int coef_stride, 
     // no lookups, a few shifts and XORs per load: three workgroups per CU for every k
     const size_t lds = (shape.occupancy_cap && unroll == 2 && tpw == 1 && wgs >= kCapMinWorkgroupsRows)
                            ? lds_for_workgroups_per_cu(3) : 0;
-    if (unroll == 2 && tpw == 1 && wgs <= kSmallWorkgroups) {  // does not fill the chip: four streams' loads together
+    if (shape.size_forms && unroll == 2 && tpw == 1 && wgs <= kSmallWorkgroups) {  // does not fill the chip: four streams' loads together
         if (rows == 2) {
             if (nt) hipLaunchKernelGGL((horner_contig_kernel<2, 2, true, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
             else hipLaunchKernelGGL((horner_contig_kernel<2, 2, false, 4>), dim3(wgs), dim3(kThreads), 0, stream, a);
@@ -944,7 +945,7 @@ hipError_t launch_apply_batch(int rows, int k, const uint8_t *coef, int coef_str
                            ? lds_for_workgroups_per_cu(4) : 0;
     // all chunks together do not fill the chip (512 workgroups: 1.4 to 3.1 us less from launch to idle; at
     // 1024 the two forms are level)
-    if (unroll == 2 && k > 1 && static_cast<uint64_t>(wgs) * n_chunks <= kSmallWorkgroups / 2)
+    if (shape.size_forms && unroll == 2 && k > 1 && static_cast<uint64_t>(wgs) * n_chunks <= kSmallWorkgroups / 2)
         return dispatch<BatchSmallLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
                                             dim3(wgs, static_cast<uint32_t>(n_chunks)), lds, stream);
     return dispatch<BatchLauncher>(rows, p.row0_xor, unroll, shape.nontemporal != 0, a,
@@ -995,6 +996,7 @@ hipError_t launch_apply_paged(int rows, int k, const uint8_t *coef, int coef_str
     for (int j = 0; j < k; ++j) plain = plain && in[j].table_row >= 0 && in[j].table_row == in[0].table_row + j;
     for (int r = 0; r < rows; ++r) plain = plain && out[r].table_row < 0;
     a.mixed = plain ? 0u : 1u;
+    a.small_form = shape.size_forms ? 1u : 0u;
     a.plane_base = reinterpret_cast<const uint8_t *const *>(plane_base_dev);
     a.table = table_dev;
     a.vecs_per_plane = vecs;

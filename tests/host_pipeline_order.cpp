@@ -445,6 +445,10 @@ static int check_occupancy_reservation()
         EXPECT(lds_of(code, B, c.erased, c.n_erased) == 0 || c.kind == GS_RDP);
         EXPECT(gs_set_launch_shape(0, 0, -1, -1) == GS_OK);
         EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.want));   // the shape knobs left the switch on
+        // without the kernel forms by size a rebuild of three shards of a wide code is three lookup rows again
+        EXPECT(gs_set_size_forms(0) == GS_OK);
+        EXPECT(lds_of(code, B, c.erased, c.n_erased) == static_cast<long>(c.k == 16 && c.n_erased == 3 ? 0 : c.want));
+        EXPECT(gs_set_size_forms(1) == GS_OK);
         gs_free_code(code);
     }
     // where the reservation starts: 6144 workgroups of 8 KiB per stream for two and more rows, 12288 for one row

@@ -221,6 +221,7 @@ void worker(const Shared &sh, int id, int rounds)
         if (id == 0) {
             EXPECT(gs_set_launch_shape(1 + (r & 1), 1 + (r % 3), r & 1, r % 7) == GS_OK);
             EXPECT(gs_set_power_horner(r & 1) == GS_OK);
+            EXPECT(gs_set_size_forms((r >> 1) & 1) == GS_OK);
         }
     }
     gs_pool_destroy(pool);
@@ -258,6 +259,7 @@ int main()
     for (std::thread &t : threads) t.join();
     gs_set_launch_shape(0, 0, -1, -1);
     gs_set_power_horner(1);
+    gs_set_size_forms(1);
     gs_free_code(sh.cauchy);
     gs_free_code(sh.power);
     gs_free_code(sh.rdp);

@@ -658,3 +658,39 @@ def test_bulk_rebuild_of_three_and_four_shards_every_pattern(gs, k, m, sizes):
         gs.gs_reconstruct(code, work, list(pat), S)
         for r in range(k + m):
             assert torch.equal(work[r], good[r]), (pat, r)
+
+
+def test_kernel_forms_by_size_change_no_byte(gs):
+    """gs_set_size_forms(0) sends small launches and rebuilds of three and four shards through the general
+    bulk form: the same bytes as the forms of their own, and the oracle's."""
+    cases = [(8, 3, (2, 5, 9), 1056 * 8192 + 16 + 7), (6, 4, (0, 1, 3, 7), 1030 * 8192 + 5), (8, 2, (1, 3), 300000),
+             (16, 2, (0, 17), 65536 + 3), (5, 1, (2,), 4097)]
+    try:
+        for k, m, pat, S in cases:
+            code = gs.gs_make_code(k, m)
+            P, full = _stripe_on_gpu(gs, k, m, S, seed=S % 991 + k)
+            outs = []
+            for on in (1, 0):
+                gs.gs_set_size_forms(on)
+                d = [dev(x) for x in full[:k]]
+                p = [out_buf(S) for _ in range(m)]
+                gs.gs_encode(code, d, p, S)
+                shards = []
+                for r in range(k + m):
+                    if r in pat:
+                        t = out_buf(S)
+                        t[:S] = 0xA5
+                    else:
+                        t = torch.cat([dev(full[r]), torch.full((PAD,), CANARY, dtype=torch.uint8, device="cuda")])
+                    shards.append(t)
+                gs.gs_reconstruct(code, shards, list(pat), S)
+                torch.cuda.synchronize()
+                for i in range(m):
+                    check_out(p[i], full[k + i])
+                for r in pat:
+                    check_out(shards[r], full[r])
+                outs.append([x.clone() for x in p] + [shards[r].clone() for r in pat])
+            for a, b in zip(*outs):
+                assert torch.equal(a, b)
+    finally:
+        gs.gs_set_size_forms(1)
