@@ -428,6 +428,7 @@ def code_shapes(torch, gs, log):
     how the number of streams and of parity rows moves the HBM fraction.  Events around 7 launches."""
     total = 40 << 30
     arena = device_arena(torch, total)
+    arena[:total].random_(0, 256)   # the rate depends on the data: all-zero buffers run about 2 points faster
     rows = []
     for k, m in ((1, 1), (2, 1), (2, 2), (4, 1), (4, 2), (8, 1), (8, 2), (8, 3), (8, 4), (16, 1), (16, 2), (16, 4), (1, 4)):
         S = total // (k + m) // 4096 * 4096
@@ -459,7 +460,8 @@ def launch_sizes(torch, gs, log, cap=True):
     stream at a time above, fewer workgroups per CU from 48 MiB on); this leg shows all three regimes.
     (The small-launch form against the bulk form on small launches is timed from C, without the
     interpreter's per-call cost: `many_chunks.from_c`, `decode_step.native`.)"""
-    arena = device_arena(torch, 10 << 30)
+    arena = device_arena(torch, 11 << 30)
+    arena[:11 << 30].random_(0, 256)   # never time fresh (all-zero) memory: it runs about 2 points faster than real bytes
     rows = []
 
     def per_launch_us(fn, n):
@@ -510,6 +512,21 @@ def launch_sizes(torch, gs, log, cap=True):
                     finally:
                         gs.gs_set_occupancy_cap(True)
                     row[name]["frac_without_reservation"] = round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)
+                if S >= (16 << 20):
+                    # the form of small launches at this size: the loads of four streams issued together,
+                    # with the reservation of the size and (the design before one stream at a time) without
+                    gs.gs_set_size_forms(2)
+                    try:
+                        us = per_launch_us(fn, n)
+                        row[name]["frac_four_streams_together"] = round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)
+                        if cap and S >= (48 << 20):
+                            gs.gs_set_occupancy_cap(False)
+                            us = per_launch_us(fn, n)
+                            row[name]["frac_four_streams_together_without_reservation"] = \
+                                round((k + m) * S / us / 1e3 / HBM_PEAK_GBPS, 4)
+                    finally:
+                        gs.gs_set_size_forms(1)
+                        gs.gs_set_occupancy_cap(cap)
             rows.append(row)
     # a rebuild of three shards with the all-ones parity among the survivors: one lost shard as a plain XOR
     # (the default) against three lookup rows (gs_set_size_forms(0)), in one process on the same buffers
@@ -722,7 +739,7 @@ def extras(torch, gs, inputs, args, cfg, k, m, S, data, parity, shards, erased, 
 
     # ---- what the checkpoint costs other GPU work: a stream of HBM-bound 1 GiB device copies
     # (stand-in for serving kernels), timed alone and while a checkpoint runs beside it
-    a_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    a_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 256)
     b_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     side, cstream = torch.cuda.Stream(), torch.cuda.Stream()
 

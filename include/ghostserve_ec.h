@@ -440,11 +440,15 @@ int gs_set_occupancy_cap(int enable);
  * A bulk rebuild of three or four contiguous shards with the all-ones parity
  * among the survivors computes one of the lost shards as a plain XOR of
  * inputs and of the other rebuilt shards instead of by table lookups.
- * enable = 0 sends both through the general bulk form; the bytes are the same
- * either way, which is what the switch is for: tests compare the forms, and
- * bench.py times them side by side.  Process-wide and atomic like the knobs
- * above; gs_set_launch_shape leaves it as it is.  Default: enabled. */
-int gs_set_size_forms(int enable);
+ * mode = 0 sends both through the general bulk form; mode = 2 runs every
+ * contiguous launch, whatever its size, in the form of small launches (the
+ * loads of four streams together, which is what bulk launches used before one
+ * stream at a time measured faster); mode = 1 is the default.  The bytes are
+ * the same in every mode, which is what the switch is for: tests compare the
+ * forms, and bench.py times them side by side.  Other values: GS_EINVAL.
+ * Process-wide and atomic like the knobs above; gs_set_launch_shape leaves it
+ * as it is. */
+int gs_set_size_forms(int mode);
 /* gs_encode of a GS_POWER code with m = 2 or 3 and k <= 16 evaluates the
  * parity rows by Horner's rule (par_r = (..(d_{k-1} g + d_{k-2}) g ..) g + d_0
  * with g = 2^r; one packed multiply-by-2 per stream and row, no table

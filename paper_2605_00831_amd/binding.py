@@ -497,8 +497,8 @@ def gs_set_occupancy_cap(enable=True):
     _check(lib().gs_set_occupancy_cap(1 if enable else 0), "gs_set_occupancy_cap")
 
 
-def gs_set_size_forms(enable=True):
-    _check(lib().gs_set_size_forms(1 if enable else 0), "gs_set_size_forms")
+def gs_set_size_forms(mode=1):
+    _check(lib().gs_set_size_forms(int(mode)), "gs_set_size_forms")
 
 
 def gs_set_launch_shape(unroll=0, tiles_per_wg=0, nontemporal=-1, interleave_shift=-1):

@@ -29,7 +29,7 @@ static constexpr uint64_t pack_shape(const LaunchShape &s)
 {
     return static_cast<uint64_t>(static_cast<uint8_t>(s.unroll)) | (static_cast<uint64_t>(static_cast<uint8_t>(s.nontemporal)) << 8) |
            (static_cast<uint64_t>(static_cast<uint8_t>(s.interleave_shift)) << 16) |
-           (static_cast<uint64_t>(s.occupancy_cap ? 1u : 0u) << 24) | (static_cast<uint64_t>(s.size_forms ? 1u : 0u) << 25) |
+           (static_cast<uint64_t>(s.occupancy_cap ? 1u : 0u) << 24) | (static_cast<uint64_t>(static_cast<uint32_t>(s.size_forms) & 3u) << 25) |
            (static_cast<uint64_t>(static_cast<uint32_t>(s.tiles_per_wg)) << 32);
 }
 
@@ -43,7 +43,7 @@ LaunchShape current_shape()
     s.nontemporal = static_cast<int>((w >> 8) & 0xFF);
     s.interleave_shift = static_cast<int>((w >> 16) & 0xFF);
     s.occupancy_cap = static_cast<int>((w >> 24) & 1);
-    s.size_forms = static_cast<int>((w >> 25) & 1);
+    s.size_forms = static_cast<int>((w >> 25) & 3);
     s.tiles_per_wg = static_cast<int>(w >> 32);
     return s;
 }
@@ -610,7 +610,7 @@ int gs_set_launch_shape(int unroll, int tiles_per_wg, int nontemporal, int inter
     uint64_t old = g_shape.load(std::memory_order_relaxed), next;
     do {
         s.occupancy_cap = static_cast<int>((old >> 24) & 1);
-        s.size_forms = static_cast<int>((old >> 25) & 1);
+        s.size_forms = static_cast<int>((old >> 25) & 3);
         next = pack_shape(s);
     } while (!g_shape.compare_exchange_weak(old, next, std::memory_order_relaxed));
     return GS_OK;
@@ -625,11 +625,12 @@ int gs_set_occupancy_cap(int enable)
     return GS_OK;
 }
 
-int gs_set_size_forms(int enable)
+int gs_set_size_forms(int mode)
 {
+    if (mode < 0 || mode > 2) return GS_EINVAL;
     uint64_t old = g_shape.load(std::memory_order_relaxed), next;
     do {
-        next = enable ? (old | (1ull << 25)) : (old & ~(1ull << 25));
+        next = (old & ~(3ull << 25)) | (static_cast<uint64_t>(mode) << 25);
     } while (!g_shape.compare_exchange_weak(old, next, std::memory_order_relaxed));
     return GS_OK;
 }

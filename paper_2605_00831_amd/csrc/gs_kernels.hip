@@ -788,15 +788,18 @@ hipError_t launch_apply(int rows, int k, const uint8_t *coef, int coef_stride,
     grid_for(tiles, tpw, wgs);
     a.tiles_per_wg = tpw;
     a.nx_shift = nx_shift;
-    if (shape.size_forms && unroll == 2 && tpw == 1 && k > 1 && wgs <= kSmallWorkgroups)
-        return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), 0, stream);
+    if (shape.size_forms && unroll == 2 && tpw == 1 && k > 1 && (wgs <= kSmallWorkgroups || shape.size_forms == 2)) {
+        // (mode 2: every contiguous launch in this form, with the reservation of its size, for comparison)
+        const size_t lds_small = wgs <= kSmallWorkgroups ? 0 : contig_reservation(shape, unroll, rows, row0_xor, k, wgs);
+        return dispatch<ContigSmallLauncher>(rows, row0_xor, unroll, shape.nontemporal != 0, a, dim3(wgs), lds_small, stream);
+    }
     // Three and four lookup rows keep the vector ALU busy 70 to 80 % of the time at the HBM rate; with one
     // of them turned into an XOR row the rebuild of three shards runs at the rate of the 8+3 encode.
     // (Measured: 8+3 less three 82 -> 83.5 to 84.5 %, 16+3 80 -> 83.6 %, 8+4 less four 79.5 -> 81 to 82.7 %, 16+4
     // 73 -> 79 %.  Two-row rebuilds are HBM-bound either way -- level at k = 4 and 16, 1 to 2 points worse
     // folded at k = 8 -- and stay as they are; a launch that accumulates into its outputs cannot fold,
     // its accumulators start from the previous contents.)
-    if (shape.size_forms && !row0_xor && rows >= 3 && !accumulate) {
+    if (shape.size_forms == 1 && !row0_xor && rows >= 3 && !accumulate) {
         const XorFold f = find_xor_fold(rows, k, coef, coef_stride);
         if (f.found) {
             RowPlan p;

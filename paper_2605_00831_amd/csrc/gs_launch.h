@@ -16,7 +16,7 @@ struct LaunchShape {
     int nontemporal;   // streaming cache policy on loads and stores
     int interleave_shift;  // log2 of the XCD interleave modulus of the contiguous kernel (0 = off)
     int occupancy_cap;     // bulk launches reserve LDS so that fewer workgroups share a CU (see lds_for_workgroups_per_cu)
-    int size_forms;        // small launches and rebuilds of 3-4 shards run kernel forms of their own (see gs_set_size_forms)
+    int size_forms;        // 1: small launches and rebuilds of 3-4 shards run kernel forms of their own; 0 / 2: see gs_set_size_forms
 };
 
 // Resident workgroups per CU are limited by handing every workgroup a slice of

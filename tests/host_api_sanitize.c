@@ -134,6 +134,8 @@ int main(void)
     }
     EXPECT(gs_set_launch_shape(0, 0, -1, -1) == GS_OK);
     EXPECT(gs_set_power_horner(1) == GS_OK);
+    EXPECT(gs_set_size_forms(3) == GS_EINVAL && gs_set_size_forms(-1) == GS_EINVAL);
+    EXPECT(gs_set_size_forms(2) == GS_OK && gs_set_size_forms(0) == GS_OK && gs_set_size_forms(1) == GS_OK);
 
     gs_code *rdp = NULL;
     EXPECT(gs_make_rdp_code(6, 4096, &rdp) == GS_OK);

@@ -221,7 +221,7 @@ void worker(const Shared &sh, int id, int rounds)
         if (id == 0) {
             EXPECT(gs_set_launch_shape(1 + (r & 1), 1 + (r % 3), r & 1, r % 7) == GS_OK);
             EXPECT(gs_set_power_horner(r & 1) == GS_OK);
-            EXPECT(gs_set_size_forms((r >> 1) & 1) == GS_OK);
+            EXPECT(gs_set_size_forms((r >> 1) % 3) == GS_OK);
         }
     }
     gs_pool_destroy(pool);

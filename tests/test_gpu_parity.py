@@ -662,7 +662,8 @@ def test_bulk_rebuild_of_three_and_four_shards_every_pattern(gs, k, m, sizes):
 
 def test_kernel_forms_by_size_change_no_byte(gs):
     """gs_set_size_forms(0) sends small launches and rebuilds of three and four shards through the general
-    bulk form: the same bytes as the forms of their own, and the oracle's."""
+    bulk form, gs_set_size_forms(2) every contiguous launch through the form of small launches: the same
+    bytes as the default, and the oracle's."""
     cases = [(8, 3, (2, 5, 9), 1056 * 8192 + 16 + 7), (6, 4, (0, 1, 3, 7), 1030 * 8192 + 5), (8, 2, (1, 3), 300000),
              (16, 2, (0, 17), 65536 + 3), (5, 1, (2,), 4097)]
     try:
@@ -670,7 +671,7 @@ def test_kernel_forms_by_size_change_no_byte(gs):
             code = gs.gs_make_code(k, m)
             P, full = _stripe_on_gpu(gs, k, m, S, seed=S % 991 + k)
             outs = []
-            for on in (1, 0):
+            for on in (1, 0, 2):
                 gs.gs_set_size_forms(on)
                 d = [dev(x) for x in full[:k]]
                 p = [out_buf(S) for _ in range(m)]
@@ -690,7 +691,10 @@ def test_kernel_forms_by_size_change_no_byte(gs):
                 for r in pat:
                     check_out(shards[r], full[r])
                 outs.append([x.clone() for x in p] + [shards[r].clone() for r in pat])
-            for a, b in zip(*outs):
-                assert torch.equal(a, b)
+            for other in outs[1:]:
+                for a, b in zip(outs[0], other):
+                    assert torch.equal(a, b)
+        with pytest.raises(gs.GsError):
+            gs.gs_set_size_forms(3)
     finally:
         gs.gs_set_size_forms(1)
