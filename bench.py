@@ -34,13 +34,13 @@ PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
 # valid for the kernel template and the default launch shape named beside it;
 # a run with another launch shape reports null.
 MEASURED_TRAFFIC = {   # (workload, code): (FETCH_SIZE and WRITE_SIZE scaled to bytes, kernel, profile)
-    ("llama8b_prefill", "cauchy"): (51539245985, "apply_contig_kernel<2, true, 2, true>",
+    ("llama8b_prefill", "cauchy"): (51539234413, "apply_contig_kernel<2, true, 2, true>",
                                     "profiles/encode_contig_llama8b_prefill.md"),
     ("llama8b_prefill", "power"): (51539233697, "horner_contig_kernel<2, 2, true>",
                                    "profiles/horner_power_code_llama8b_prefill.md"),
-    ("llama70b_longctx", "cauchy"): (53686516541, "apply_contig_kernel<2, true, 2, true>",
+    ("llama70b_longctx", "cauchy"): (53686501590, "apply_contig_kernel<2, true, 2, true>",
                                      "profiles/encode_contig_llama70b_longctx.md"),
-    ("recovery_stress", "cauchy"): (5905681714, "apply_contig_kernel<3, true, 2, true>",
+    ("recovery_stress", "cauchy"): (5905690725, "apply_contig_kernel<3, true, 2, true>",
                                     "profiles/encode_contig_recovery_stress.md"),
 }
 
